@@ -1,0 +1,274 @@
+/*
+ * tally.h -- C ABI of the block-level kernel scheduling library for one MI355X (gfx950).
+ *
+ * Problem statement (Section 3, "Tally: system design"): one high-priority job and
+ * best-effort job(s) share a single GPU.  High-priority kernels are dispatched at once
+ * in their original form; best-effort kernels are run at thread-block granularity,
+ * either as sliced launches or as preemptible persistent-worker kernels, so that they
+ * release the compute units within microseconds (Section 4.1, Section 4.2).
+ *
+ * Conventions
+ *   - Every function returns TALLY_OK (0) or a negative tally_status.  No exception
+ *     crosses the boundary.  Out-parameters are written only on success.
+ *   - "device pointer" = address in the GPU's HBM valid on the current device;
+ *     "host pointer" = ordinary process memory.  Pointers inside tally_*_args are
+ *     DEVICE pointers owned by the caller, who keeps them alive until the job that
+ *     uses them is COMPLETE or freed.  The args struct itself is HOST memory and is
+ *     copied at launch.
+ *   - Streams are HIP streams (hipStream_t passed as void*), borrowed, never destroyed
+ *     here, and must have the default priority.
+ *   - The logical grid of a kernel is a function of its arguments (see the args
+ *     structs); tally_logical_grid() computes it and the launch calls reject any other.
+ *   - Threading: tally_preempt() and tally_progress() may be called from any thread
+ *     while a job runs.  All other calls on one context are serialised by the caller.
+ */
+#ifndef TALLY_H
+#define TALLY_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  TALLY_OK = 0,
+  TALLY_ERR_INVALID_ARG = -1, /* null pointer, zero size, unknown kernel, wrong grid/args size */
+  TALLY_ERR_BAD_STATE = -2,   /* e.g. resume of a job that is still running                   */
+  TALLY_ERR_HIP = -3,         /* a HIP call failed; tally_last_hip_error() has the code        */
+  TALLY_ERR_NOMEM = -4,
+  TALLY_ERR_UNSUPPORTED = -5  /* kernel needs all blocks co-resident (Section 6: kernels with
+                                 inter-block synchronisation are never sliced or preempted)    */
+} tally_status;
+
+/* Job states, after the running()/stopped() predicates of the scheduling algorithm
+ * (Section 4.2, Figure 4). */
+typedef enum {
+  TALLY_JOB_QUEUED = 0,
+  TALLY_JOB_RUNNING = 1,
+  TALLY_JOB_STOPPED = 2,  /* drained after a preemption, progress < total */
+  TALLY_JOB_COMPLETE = 3
+} tally_job_state;
+
+typedef enum {
+  TALLY_K_SAXPY = 0,          /* y <- a*x + y, fp32                                         */
+  TALLY_K_REDUCE_SUM = 1,     /* partial[b] = sum of 4096 consecutive fp32                  */
+  TALLY_K_REDUCE_FINAL = 2,   /* total (fp64) = sum of the partials; one block              */
+  TALLY_K_GEMM_BF16 = 3,      /* C = A * B, bf16 in/out, fp32 accumulate, 256x256 tiles     */
+  TALLY_K_GEMV_BF16 = 4,      /* y = W * x, bf16 in/out, fp32 accumulate                    */
+  TALLY_K_SOFTMAX_F32 = 5,    /* row softmax, fp32                                          */
+  TALLY_K_LAYERNORM_F32 = 6,  /* row LayerNorm with gain and bias, fp32                     */
+  TALLY_K_ATTN_DECODE_BF16 = 7, /* one query per head over a bf16 K/V cache (native only)   */
+  TALLY_K_GEMM_BF16_SMALL = 8,  /* same operator as GEMM_BF16 with 64x64 tiles, ragged edges */
+  TALLY_K_COUNT = 9
+} tally_kernel_id;
+
+typedef struct { uint32_t x, y, z; } tally_dim3;
+
+/* ---- kernel arguments (host structs holding device pointers) --------------------- */
+
+/* Block b covers elements [256 b, 256 b + 256); thread t handles 256 b + t if < n. */
+typedef struct { const float *x; float *y; float a; uint32_t n; } tally_saxpy_args;
+
+/* Block b sums x[4096 b .. 4096 b + 4096) (256 threads x 16 elements, ragged tail
+ * allowed) into partial[b].  grid.x = ceil(n / 4096). */
+typedef struct { const float *x; float *partial; uint64_t n; } tally_reduce_sum_args;
+
+/* One block: *total = sum(partial[0..count)), carried in fp64. */
+typedef struct { const float *partial; double *total; uint32_t count; } tally_reduce_final_args;
+
+/* C[z] (m x n, row-major, ld = n) = A[z] (m x k, row-major) * B[z] (k x n) where B is
+ * stored K-contiguous: Bt[z] is n x k row-major.  All bf16 bit patterns; products are
+ * accumulated in fp32 and rounded to nearest-even bf16 once.  Batch z uses element
+ * strides stride_a/b/c.  Block (bx, by, bz) owns the output tile rows [T by, T by + T),
+ * columns [T bx, T bx + T) of batch bz, T = 256 (GEMM_BF16: m, n multiples of 256 and
+ * k a multiple of 64 required) or T = 64 (GEMM_BF16_SMALL: any m, n; k multiple of 32). */
+typedef struct {
+  const uint16_t *A; const uint16_t *Bt; uint16_t *C;
+  uint32_t m, n, k, batch;
+  uint64_t stride_a, stride_b, stride_c;
+} tally_gemm_bf16_args;
+
+/* y[r] = sum_k W[r][k] x[k]; W is n x k row-major.  Block b owns rows [4b, 4b+4), one
+ * 64-lane wave per row.  k must be a multiple of 8. */
+typedef struct { const uint16_t *x; const uint16_t *W; uint16_t *y; uint32_t n, k; } tally_gemv_bf16_args;
+
+/* Row-wise kernels: block b owns rows [4b, 4b+4), one wave per row; rows are cols
+ * fp32 apart.  cols <= 8192. */
+typedef struct { const float *x; float *y; uint32_t rows, cols; } tally_softmax_f32_args;
+typedef struct {
+  const float *x; const float *gamma; const float *beta; float *y;
+  uint32_t rows, cols; float eps;
+} tally_layernorm_f32_args;
+
+/* out[h] = softmax(q[h] . K[:,h,:]^T / sqrt(dim)) . V[:,h,:]; q, out: heads x dim;
+ * K, V: tokens x heads x dim; dim must be 128.  `scratch` is caller-owned device memory
+ * of tally_attn_decode_scratch_bytes(heads) bytes (split partial results). */
+typedef struct {
+  const uint16_t *q; const uint16_t *K; const uint16_t *V; uint16_t *out; void *scratch;
+  uint32_t tokens, heads, dim;
+} tally_attn_decode_args;
+
+typedef struct {
+  uint32_t kernel_id;        /* tally_kernel_id                                           */
+  tally_dim3 grid, block;    /* LOGICAL grid and block, as the original kernel is launched */
+  const void *args;          /* host pointer to the matching tally_*_args                  */
+  size_t args_size;          /* sizeof of that struct                                      */
+} tally_kernel_desc;
+
+/* Per-logical-block coverage record, written by the transformed kernels when a job is
+ * created with coverage enabled (test/diagnostic).  `count` is incremented atomically;
+ * b[] is the block index the kernel rebuilt from the offset or task index. */
+typedef struct { uint32_t count, bx, by, bz, segment, worker; } tally_cover_rec;
+
+typedef struct tally_ctx tally_ctx; /* owns flags, counters, status words, marker words */
+typedef struct tally_job tally_job; /* one best-effort kernel instance and its progress  */
+
+/* ---- context ---------------------------------------------------------------------- */
+
+/* Create a context on the current device for one high-priority and one best-effort
+ * stream (Section 3: one high-priority task next to best-effort tasks). */
+int tally_create(tally_ctx **out, void *hip_stream_hi, void *hip_stream_be);
+int tally_destroy(tally_ctx *ctx); /* all jobs must have been freed */
+
+/* Logical grid/block of a kernel for given arguments (host struct). */
+int tally_logical_grid(uint32_t kernel_id, const void *args, size_t args_size,
+                       tally_dim3 *grid, tally_dim3 *block);
+size_t tally_attn_decode_scratch_bytes(uint32_t heads);
+
+/* ---- the three launch forms ------------------------------------------------------- */
+
+/* Original form: one launch of the whole logical grid on the high-priority stream
+ * (on_hi_stream != 0) or on the best-effort stream (Section 4.2: high-priority
+ * kernels are launched with the default configuration).  Asynchronous. */
+int tally_launch_native(tally_ctx *ctx, const tally_kernel_desc *desc, int on_hi_stream);
+
+/* Sliced form (Section 4.1, slicing transformation): the grid is cut into sub-kernels
+ * of slice_blocks consecutive logical blocks (last one: the remainder); each sub-kernel
+ * receives a block offset and rebuilds its logical block index as offset + blockIdx.
+ * At most max_in_flight (>= 1; 1 = "one at a time", Section 4.2) sub-kernels are
+ * enqueued; this call issues the first ones, tally_pump() the following.
+ * coverage != 0 allocates per-block coverage records. */
+int tally_launch_sliced(tally_ctx *ctx, const tally_kernel_desc *desc, uint32_t slice_blocks,
+                        uint32_t max_in_flight, int coverage, tally_job **out);
+
+/* Preemptible persistent-worker form (Section 4.1, preemption transformation):
+ * num_workers worker blocks loop { check flag; fetch-and-add the global task counter;
+ * map the task index to the logical block index; run the block; barrier }.
+ * `chunk` (>= 1) is the number of consecutive task indices taken per fetch; 1 is the
+ * paper's form.  A fetched index is always executed before the worker exits. */
+int tally_launch_ptb(tally_ctx *ctx, const tally_kernel_desc *desc, uint32_t num_workers,
+                     uint32_t chunk, int coverage, tally_job **out);
+
+/* Non-blocking.  Persistent-worker job: raise its preemption flag (one host store);
+ * workers finish their current block(s) and exit.  Sliced job: stop issuing
+ * sub-kernels.  No-op on STOPPED / COMPLETE jobs. */
+int tally_preempt(tally_job *job);
+
+/* Continue a STOPPED job from its saved task counter / block offset (Section 4.1:
+ * progress is held in the global task index).  BAD_STATE while RUNNING; no-op when
+ * COMPLETE. */
+int tally_resume(tally_job *job);
+
+/* Non-blocking snapshot.  done_blocks = min(counter, total) as last published by the
+ * device; exact once the job is STOPPED or COMPLETE.  Any out pointer may be null. */
+int tally_progress(tally_job *job, uint64_t *done_blocks, uint64_t *total_blocks, int *state);
+
+/* Sliced jobs: retire finished sub-kernels and, unless preempted, enqueue the next
+ * ones.  Persistent-worker jobs: refresh the state.  Non-blocking. */
+int tally_pump(tally_job *job);
+
+/* Block (host spin) until the job is STOPPED or COMPLETE, then synchronise the
+ * best-effort stream so outputs are visible. */
+int tally_wait(tally_job *job, int *state);
+int tally_job_free(tally_job *job); /* waits for in-flight launches of the job first */
+
+/* ---- test / diagnostic ------------------------------------------------------------- */
+
+/* Deterministic preemption "at counter value stop_at": the workers treat stop_at as
+ * the end of the grid, which is what a preemption observed exactly when the counter
+ * reached stop_at produces; the job ends STOPPED with progress == stop_at (or COMPLETE
+ * if stop_at >= total). */
+int tally_launch_ptb_until(tally_ctx *ctx, const tally_kernel_desc *desc, uint32_t num_workers,
+                           uint32_t chunk, uint64_t stop_at, int coverage, tally_job **out);
+int tally_resume_until(tally_job *job, uint64_t stop_at);
+
+/* Copy the coverage records (one tally_cover_rec per logical block, x-fastest linear
+ * order) to host memory.  Job must be STOPPED or COMPLETE. */
+int tally_coverage(tally_job *job, void *host_records, size_t bytes);
+
+/* Enqueue, on the high-priority (or best-effort) stream, a marker that stores `value`
+ * into the context's host-visible word for that stream once all earlier work on the
+ * stream has finished; tally_marker_read() returns the last stored value. */
+int tally_marker(tally_ctx *ctx, int on_hi_stream, uint32_t value);
+int tally_marker_read(tally_ctx *ctx, int on_hi_stream, uint32_t *value);
+
+/* Time from tally_preempt() to the device reporting the job drained, in microseconds
+ * (host clock); negative if the last segment was not preempted. */
+int tally_last_preempt_latency_us(tally_job *job, double *us);
+
+int tally_last_hip_error(void);
+const char *tally_strerror(int status);
+int tally_device_info(uint32_t *num_cus, uint32_t *lds_bytes_per_cu, uint32_t *wave_size);
+
+/* ---- profile-guided configuration (Section 4.2) ------------------------------------ */
+
+typedef struct {
+  uint32_t kind;          /* 0 = persistent workers, 1 = sliced                          */
+  uint32_t param;         /* worker count, or blocks per slice                            */
+  uint32_t chunk;         /* task indices per fetch (persistent workers), else 1          */
+  float latency_ms;       /* mean whole-kernel latency over the profiling runs            */
+  float turnaround_ms;    /* Eq. 1 for persistent workers; one slice's time when sliced   */
+} tally_config;
+
+/* Eq. 1: kernel_latency * worker_blocks / total_blocks (times `chunk`). */
+double tally_ptb_turnaround_ms(double kernel_latency_ms, uint32_t worker_blocks, uint32_t chunk,
+                               uint64_t total_blocks);
+
+/* Best-performing candidate whose turnaround estimate is <= threshold_ms; if none
+ * complies, the one with the smallest estimate.  Returns its index or a negative status. */
+int tally_select_config(const tally_config *cands, uint32_t n, double threshold_ms);
+
+/* Measure every candidate configuration of a kernel on the best-effort stream (`runs`
+ * timed executions each, after one warm-up; the kernel really runs, so its outputs are
+ * written `runs`+1 times per candidate), fill latency and turnaround, choose under
+ * threshold_ms and cache the choice per (kernel, grid, block).  cands: in/out array. */
+int tally_profile(tally_ctx *ctx, const tally_kernel_desc *desc, tally_config *cands, uint32_t n,
+                  uint32_t runs, double threshold_ms, uint32_t *chosen);
+/* Cached choice for (kernel, grid, block); TALLY_ERR_BAD_STATE if not profiled yet. */
+int tally_lookup_config(tally_ctx *ctx, const tally_kernel_desc *desc, tally_config *out);
+
+/* ---- two-stream priority scheduler (Section 4.2, Figure 4) ------------------------- */
+
+typedef struct {
+  const tally_kernel_desc *kernel; /* one best-effort kernel of the step                   */
+  tally_config config;             /* kind 0/1 as above; kind 2 = native (untransformed)   */
+} tally_be_item;
+
+typedef struct {
+  /* inputs */
+  const tally_kernel_desc *hi_kernels; uint32_t n_hi_kernels; /* one high-priority request  */
+  const double *arrivals_us; uint32_t n_arrivals; /* open-loop arrival times from t0        */
+  const tally_be_item *be_items; uint32_t n_be_items; /* one best-effort step, repeated      */
+  uint32_t policy;            /* 0 = priority scheduling with preemption (the method)
+                                 1 = priority scheduling, best-effort kernels native
+                                 2 = no scheduling: both dispatched on arrival              */
+  double tail_us;             /* keep feeding best-effort work this long after last arrival  */
+  /* outputs (host arrays owned by the caller) */
+  double *latency_us;         /* n_arrivals: scheduled arrival -> completion observed        */
+  double *preempt_latency_us; uint32_t preempt_cap; uint32_t n_preempts; /* per preemption   */
+  uint64_t be_kernels_done;   /* best-effort kernels completed inside the window             */
+  uint64_t be_steps_done;
+  double window_us;           /* wall time of the run                                        */
+} tally_sched_run_t;
+
+/* Run the scheduling loop on the calling thread until every arrival has completed and
+ * tail_us has elapsed.  n_arrivals == 0 runs the best-effort job alone for tail_us;
+ * n_be_items == 0 runs the high-priority job alone. */
+int tally_sched_run(tally_ctx *ctx, tally_sched_run_t *run);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TALLY_H */

@@ -103,18 +103,20 @@ CHECK, FETCHED, EXITED = 0, 1, 2
 class PtbMachine:
     """Micro-step model of W persistent workers sharing one counter and one flag.
 
-    A worker is in CHECK (about to start an iteration), FETCHED(idx) (holds a task
-    index it has not run yet) or EXITED.  `step(w)` advances worker w by one
+    A worker is in CHECK (about to start an iteration), FETCHED(idx) (holds task
+    indices it has not run yet) or EXITED.  `step(w)` advances worker w by one
     micro-step.  `order` = "check_then_fetch" is the paper's order ("at the start of
     each iteration, workers check this flag").  "fetch_then_check" is a deliberately
     wrong variant (a fetched index is dropped when the flag is seen) kept so the
     tests can show the brute-force checker is not vacuous.
     """
 
-    def __init__(self, total, workers, order="check_then_fetch", on_exec=None):
+    def __init__(self, total, workers, order="check_then_fetch", on_exec=None, chunk=1):
         self.total = int(total)
         self.W = int(workers)
         self.order = order
+        self.chunk = int(chunk)          # task indices taken per fetch; 1 is the paper's form
+        self.held_end = [-1] * self.W
         self.counter = 0
         self.flag = False
         self.state = [CHECK] * self.W
@@ -127,6 +129,7 @@ class PtbMachine:
     def clone(self, on_exec=None):
         m = PtbMachine.__new__(PtbMachine)
         m.total, m.W, m.order = self.total, self.W, self.order
+        m.chunk, m.held_end = self.chunk, list(self.held_end)
         m.counter, m.flag, m.segment = self.counter, self.flag, self.segment
         m.state, m.held = list(self.state), list(self.held)
         m.on_exec = on_exec
@@ -160,23 +163,28 @@ class PtbMachine:
                     self.state[w] = EXITED
                     return
                 idx = self.counter
-                self.counter += 1
+                self.counter += self.chunk
                 if idx >= self.total:
                     self.state[w] = EXITED
                     return
                 self.state[w], self.held[w] = FETCHED, idx
+                self.held_end[w] = min(idx + self.chunk, self.total)
             else:  # wrong order: fetch first, then honour the flag and drop the index
                 idx = self.counter
-                self.counter += 1
+                self.counter += self.chunk
                 if idx >= self.total or self.flag:
                     self.state[w] = EXITED
                     return
                 self.state[w], self.held[w] = FETCHED, idx
-        else:  # FETCHED: run the block, reach the end-of-iteration barrier, loop
+                self.held_end[w] = min(idx + self.chunk, self.total)
+        else:  # FETCHED: run one held block, reach the barrier; loop when none is left
             idx = self.held[w]
             if self.on_exec is not None:
                 self.on_exec(idx, self.segment, w)
-            self.state[w], self.held[w] = CHECK, -1
+            if idx + 1 < self.held_end[w]:
+                self.held[w] = idx + 1   # a fetched index is always run before the flag counts
+            else:
+                self.state[w], self.held[w], self.held_end[w] = CHECK, -1, -1
 
     def resume(self):
         """Relaunch after a drain: flag cleared, counter kept."""
@@ -189,13 +197,15 @@ class PtbMachine:
         self.segment += 1
         self.state = [CHECK] * self.W
         self.held = [-1] * self.W
+        self.held_end = [-1] * self.W
         return True
 
 
-def run_ptb(name, grid, args, workers, preempt_points=(), seed=0):
+def run_ptb(name, grid, args, workers, preempt_points=(), seed=0, chunk=1):
     """Run a kernel as `workers` persistent workers under a seeded random
-    interleaving.  The flag is raised when the counter first reaches each value in
-    `preempt_points` (ascending); after every drain the kernel is resumed.
+    interleaving.  The flag is raised when the counter first reaches (or, with
+    chunk > 1, first passes) each value in `preempt_points` (ascending); after every
+    drain the kernel is resumed.
     Returns (coverage, progress value observed at each drain)."""
     total = G.total_blocks(grid)
     cov = Coverage(grid)
@@ -203,15 +213,16 @@ def run_ptb(name, grid, args, workers, preempt_points=(), seed=0):
     def on_exec(idx, segment, w):
         _run_block(name, idx, grid, args, cov, segment)
 
-    m = PtbMachine(total, workers, on_exec=on_exec)
+    m = PtbMachine(total, workers, on_exec=on_exec, chunk=chunk)
     rng = np.random.Generator(np.random.PCG64(seed))
     pts = sorted(int(p) for p in preempt_points)
     nxt = 0
     while True:
-        while nxt < len(pts) and pts[nxt] <= m.counter and not m.flag:
-            if pts[nxt] == m.counter:
-                m.raise_flag()
+        if not m.flag and nxt < len(pts) and pts[nxt] <= m.counter:
+            m.raise_flag()
             nxt += 1
+            while nxt < len(pts) and pts[nxt] < m.counter:
+                nxt += 1                 # points already passed are part of the same drain
         live = m.live()
         if live:
             m.step(live[int(rng.integers(len(live)))])

@@ -1,0 +1,425 @@
+"""Thin ctypes binding of libtally.so: argument marshalling only.
+
+Every step of the path (the three launch forms, preemption, resume, profiling, the
+scheduling loop) runs inside the library.  PyTorch appears only as the owner of
+device memory and streams.  There is no CPU fallback: if the library is missing the
+import fails.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libtally.so")
+
+# ---------------------------------------------------------------- enums
+K_SAXPY, K_REDUCE_SUM, K_REDUCE_FINAL, K_GEMM_BF16, K_GEMV_BF16 = 0, 1, 2, 3, 4
+K_SOFTMAX_F32, K_LAYERNORM_F32, K_ATTN_DECODE_BF16, K_GEMM_BF16_SMALL = 5, 6, 7, 8
+JOB_QUEUED, JOB_RUNNING, JOB_STOPPED, JOB_COMPLETE = 0, 1, 2, 3
+OK, ERR_INVALID_ARG, ERR_BAD_STATE, ERR_HIP, ERR_NOMEM, ERR_UNSUPPORTED = 0, -1, -2, -3, -4, -5
+CFG_PTB, CFG_SLICED, CFG_NATIVE = 0, 1, 2
+POLICY_TALLY, POLICY_PRIORITY_NATIVE, POLICY_NONE = 0, 1, 2
+
+EXPORTS = [
+    "tally_create", "tally_destroy", "tally_logical_grid", "tally_attn_decode_scratch_bytes",
+    "tally_launch_native", "tally_launch_sliced", "tally_launch_ptb", "tally_preempt",
+    "tally_resume", "tally_progress", "tally_pump", "tally_wait", "tally_job_free",
+    "tally_launch_ptb_until", "tally_resume_until", "tally_coverage", "tally_marker",
+    "tally_marker_read", "tally_last_preempt_latency_us", "tally_last_hip_error",
+    "tally_strerror", "tally_device_info", "tally_ptb_turnaround_ms", "tally_select_config",
+    "tally_profile", "tally_lookup_config", "tally_sched_run",
+]
+
+
+class Dim3(C.Structure):
+    _fields_ = [("x", C.c_uint32), ("y", C.c_uint32), ("z", C.c_uint32)]
+
+
+class SaxpyArgs(C.Structure):
+    _fields_ = [("x", C.c_void_p), ("y", C.c_void_p), ("a", C.c_float), ("n", C.c_uint32)]
+
+
+class ReduceSumArgs(C.Structure):
+    _fields_ = [("x", C.c_void_p), ("partial", C.c_void_p), ("n", C.c_uint64)]
+
+
+class ReduceFinalArgs(C.Structure):
+    _fields_ = [("partial", C.c_void_p), ("total", C.c_void_p), ("count", C.c_uint32)]
+
+
+class GemmArgs(C.Structure):
+    _fields_ = [("A", C.c_void_p), ("Bt", C.c_void_p), ("C", C.c_void_p),
+                ("m", C.c_uint32), ("n", C.c_uint32), ("k", C.c_uint32), ("batch", C.c_uint32),
+                ("stride_a", C.c_uint64), ("stride_b", C.c_uint64), ("stride_c", C.c_uint64)]
+
+
+class GemvArgs(C.Structure):
+    _fields_ = [("x", C.c_void_p), ("W", C.c_void_p), ("y", C.c_void_p),
+                ("n", C.c_uint32), ("k", C.c_uint32)]
+
+
+class SoftmaxArgs(C.Structure):
+    _fields_ = [("x", C.c_void_p), ("y", C.c_void_p), ("rows", C.c_uint32), ("cols", C.c_uint32)]
+
+
+class LayerNormArgs(C.Structure):
+    _fields_ = [("x", C.c_void_p), ("gamma", C.c_void_p), ("beta", C.c_void_p), ("y", C.c_void_p),
+                ("rows", C.c_uint32), ("cols", C.c_uint32), ("eps", C.c_float)]
+
+
+class AttnDecodeArgs(C.Structure):
+    _fields_ = [("q", C.c_void_p), ("K", C.c_void_p), ("V", C.c_void_p), ("out", C.c_void_p),
+                ("scratch", C.c_void_p), ("tokens", C.c_uint32), ("heads", C.c_uint32),
+                ("dim", C.c_uint32)]
+
+
+class KernelDesc(C.Structure):
+    _fields_ = [("kernel_id", C.c_uint32), ("grid", Dim3), ("block", Dim3),
+                ("args", C.c_void_p), ("args_size", C.c_size_t)]
+
+
+class CoverRec(C.Structure):
+    _fields_ = [("count", C.c_uint32), ("bx", C.c_uint32), ("by", C.c_uint32), ("bz", C.c_uint32),
+                ("segment", C.c_uint32), ("worker", C.c_uint32)]
+
+
+COVER_DTYPE = np.dtype([("count", "<u4"), ("bx", "<u4"), ("by", "<u4"), ("bz", "<u4"),
+                        ("segment", "<u4"), ("worker", "<u4")])
+
+
+class Config(C.Structure):
+    _fields_ = [("kind", C.c_uint32), ("param", C.c_uint32), ("chunk", C.c_uint32),
+                ("latency_ms", C.c_float), ("turnaround_ms", C.c_float)]
+
+
+class BeItem(C.Structure):
+    _fields_ = [("kernel", C.POINTER(KernelDesc)), ("config", Config)]
+
+
+class SchedRun(C.Structure):
+    _fields_ = [("hi_kernels", C.POINTER(KernelDesc)), ("n_hi_kernels", C.c_uint32),
+                ("arrivals_us", C.POINTER(C.c_double)), ("n_arrivals", C.c_uint32),
+                ("be_items", C.POINTER(BeItem)), ("n_be_items", C.c_uint32),
+                ("policy", C.c_uint32), ("tail_us", C.c_double),
+                ("latency_us", C.POINTER(C.c_double)),
+                ("preempt_latency_us", C.POINTER(C.c_double)), ("preempt_cap", C.c_uint32),
+                ("n_preempts", C.c_uint32),
+                ("be_kernels_done", C.c_uint64), ("be_steps_done", C.c_uint64),
+                ("window_us", C.c_double)]
+
+
+class TallyError(RuntimeError):
+    def __init__(self, status, what):
+        self.status = status
+        msg = _lib.tally_strerror(status).decode() if _lib is not None else str(status)
+        hip = _lib.tally_last_hip_error() if (_lib is not None and status == ERR_HIP) else 0
+        super().__init__(f"{what}: {msg} (status {status}" + (f", hip error {hip})" if hip else ")"))
+
+
+def _load():
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            f"{LIB_PATH} is missing: build it first (python -m paper_2410_07381_amd.build). "
+            "There is no fallback path.")
+    lib = C.CDLL(LIB_PATH)
+    vp, u32, u64, i32, dbl = C.c_void_p, C.c_uint32, C.c_uint64, C.c_int, C.c_double
+    P = C.POINTER
+    sig = {
+        "tally_create": ([P(vp), vp, vp], i32),
+        "tally_destroy": ([vp], i32),
+        "tally_logical_grid": ([u32, vp, C.c_size_t, P(Dim3), P(Dim3)], i32),
+        "tally_attn_decode_scratch_bytes": ([u32], C.c_size_t),
+        "tally_launch_native": ([vp, P(KernelDesc), i32], i32),
+        "tally_launch_sliced": ([vp, P(KernelDesc), u32, u32, i32, P(vp)], i32),
+        "tally_launch_ptb": ([vp, P(KernelDesc), u32, u32, i32, P(vp)], i32),
+        "tally_preempt": ([vp], i32),
+        "tally_resume": ([vp], i32),
+        "tally_progress": ([vp, P(u64), P(u64), P(i32)], i32),
+        "tally_pump": ([vp], i32),
+        "tally_wait": ([vp, P(i32)], i32),
+        "tally_job_free": ([vp], i32),
+        "tally_launch_ptb_until": ([vp, P(KernelDesc), u32, u32, u64, i32, P(vp)], i32),
+        "tally_resume_until": ([vp, u64], i32),
+        "tally_coverage": ([vp, vp, C.c_size_t], i32),
+        "tally_marker": ([vp, i32, u32], i32),
+        "tally_marker_read": ([vp, i32, P(u32)], i32),
+        "tally_last_preempt_latency_us": ([vp, P(dbl)], i32),
+        "tally_last_hip_error": ([], i32),
+        "tally_strerror": ([i32], C.c_char_p),
+        "tally_device_info": ([P(u32), P(u32), P(u32)], i32),
+        "tally_ptb_turnaround_ms": ([dbl, u32, u32, u64], dbl),
+        "tally_select_config": ([P(Config), u32, dbl], i32),
+        "tally_profile": ([vp, P(KernelDesc), P(Config), u32, u32, dbl, P(u32)], i32),
+        "tally_lookup_config": ([vp, P(KernelDesc), P(Config)], i32),
+        "tally_sched_run": ([vp, P(SchedRun)], i32),
+    }
+    for name, (argtypes, restype) in sig.items():
+        fn = getattr(lib, name)
+        fn.argtypes = argtypes
+        fn.restype = restype
+    return lib
+
+
+_lib = None
+_lib = _load()
+
+
+def lib():
+    return _lib
+
+
+def _check(rc, what):
+    if rc != OK:
+        raise TallyError(rc, what)
+
+
+# ---------------------------------------------------------------- descriptors
+_ARGS_FOR = {
+    K_SAXPY: SaxpyArgs, K_REDUCE_SUM: ReduceSumArgs, K_REDUCE_FINAL: ReduceFinalArgs,
+    K_GEMM_BF16: GemmArgs, K_GEMM_BF16_SMALL: GemmArgs, K_GEMV_BF16: GemvArgs,
+    K_SOFTMAX_F32: SoftmaxArgs, K_LAYERNORM_F32: LayerNormArgs, K_ATTN_DECODE_BF16: AttnDecodeArgs,
+}
+
+
+class Kernel:
+    """A kernel descriptor plus the objects that must outlive it (args struct, tensors)."""
+
+    def __init__(self, kernel_id, args, keep=()):
+        assert isinstance(args, _ARGS_FOR[kernel_id])
+        self.kernel_id = kernel_id
+        self.args = args
+        self.keep = tuple(keep)
+        g, b = Dim3(), Dim3()
+        _check(_lib.tally_logical_grid(kernel_id, C.addressof(args), C.sizeof(args),
+                                       C.byref(g), C.byref(b)), "tally_logical_grid")
+        self.desc = KernelDesc(kernel_id, g, b, C.addressof(args), C.sizeof(args))
+
+    @property
+    def grid(self):
+        return (self.desc.grid.x, self.desc.grid.y, self.desc.grid.z)
+
+    @property
+    def total_blocks(self):
+        g = self.grid
+        return g[0] * g[1] * g[2]
+
+
+def logical_grid(kernel_id, args):
+    g, b = Dim3(), Dim3()
+    _check(_lib.tally_logical_grid(kernel_id, C.addressof(args), C.sizeof(args), C.byref(g),
+                                   C.byref(b)), "tally_logical_grid")
+    return (g.x, g.y, g.z), (b.x, b.y, b.z)
+
+
+def saxpy(x, y, a):
+    return Kernel(K_SAXPY, SaxpyArgs(x.data_ptr(), y.data_ptr(), float(a), x.numel()), (x, y))
+
+
+def reduce_sum(x, partial):
+    return Kernel(K_REDUCE_SUM, ReduceSumArgs(x.data_ptr(), partial.data_ptr(), x.numel()),
+                  (x, partial))
+
+
+def reduce_final(partial, total, count=None):
+    n = partial.numel() if count is None else count
+    return Kernel(K_REDUCE_FINAL, ReduceFinalArgs(partial.data_ptr(), total.data_ptr(), n),
+                  (partial, total))
+
+
+def gemm_bf16(A, Bt, Cout, small=False):
+    """A [batch,m,k], Bt [batch,n,k], C [batch,m,n]; 16-bit storage tensors."""
+    batch, m, k = A.shape
+    n = Bt.shape[1]
+    args = GemmArgs(A.data_ptr(), Bt.data_ptr(), Cout.data_ptr(), m, n, k, batch,
+                    m * k, n * k, m * n)
+    return Kernel(K_GEMM_BF16_SMALL if small else K_GEMM_BF16, args, (A, Bt, Cout))
+
+
+def gemv_bf16(x, W, y):
+    n, k = W.shape
+    return Kernel(K_GEMV_BF16, GemvArgs(x.data_ptr(), W.data_ptr(), y.data_ptr(), n, k), (x, W, y))
+
+
+def softmax_f32(x, y):
+    rows, cols = x.shape
+    return Kernel(K_SOFTMAX_F32, SoftmaxArgs(x.data_ptr(), y.data_ptr(), rows, cols), (x, y))
+
+
+def layernorm_f32(x, gamma, beta, y, eps):
+    rows, cols = x.shape
+    return Kernel(K_LAYERNORM_F32,
+                  LayerNormArgs(x.data_ptr(), gamma.data_ptr(), beta.data_ptr(), y.data_ptr(),
+                                rows, cols, float(eps)), (x, gamma, beta, y))
+
+
+def attn_decode_bf16(q, Kc, Vc, out, scratch):
+    tokens, heads, dim = Kc.shape
+    return Kernel(K_ATTN_DECODE_BF16,
+                  AttnDecodeArgs(q.data_ptr(), Kc.data_ptr(), Vc.data_ptr(), out.data_ptr(),
+                                 scratch.data_ptr(), tokens, heads, dim), (q, Kc, Vc, out, scratch))
+
+
+def attn_decode_scratch_bytes(heads):
+    return int(_lib.tally_attn_decode_scratch_bytes(heads))
+
+
+# ---------------------------------------------------------------- context / jobs
+class Job:
+    def __init__(self, handle, kernel):
+        self.h = handle
+        self.kernel = kernel
+
+    def preempt(self):
+        _check(_lib.tally_preempt(self.h), "tally_preempt")
+
+    def resume(self, stop_at=None):
+        if stop_at is None:
+            _check(_lib.tally_resume(self.h), "tally_resume")
+        else:
+            _check(_lib.tally_resume_until(self.h, int(stop_at)), "tally_resume_until")
+
+    def progress(self):
+        d, t, s = C.c_uint64(), C.c_uint64(), C.c_int()
+        _check(_lib.tally_progress(self.h, C.byref(d), C.byref(t), C.byref(s)), "tally_progress")
+        return d.value, t.value, s.value
+
+    def pump(self):
+        _check(_lib.tally_pump(self.h), "tally_pump")
+
+    def wait(self):
+        s = C.c_int()
+        _check(_lib.tally_wait(self.h, C.byref(s)), "tally_wait")
+        return s.value
+
+    def coverage(self):
+        rec = np.zeros(self.kernel.total_blocks, dtype=COVER_DTYPE)
+        _check(_lib.tally_coverage(self.h, rec.ctypes.data, rec.nbytes), "tally_coverage")
+        return rec
+
+    def preempt_latency_us(self):
+        v = C.c_double()
+        _check(_lib.tally_last_preempt_latency_us(self.h, C.byref(v)), "preempt latency")
+        return v.value
+
+    def free(self):
+        if self.h is not None:
+            _check(_lib.tally_job_free(self.h), "tally_job_free")
+            self.h = None
+
+
+class Context:
+    def __init__(self, stream_hi, stream_be):
+        """stream_hi / stream_be: torch.cuda.Stream objects (default priority)."""
+        self._streams = (stream_hi, stream_be)
+        h = C.c_void_p()
+        _check(_lib.tally_create(C.byref(h), C.c_void_p(stream_hi.cuda_stream),
+                                 C.c_void_p(stream_be.cuda_stream)), "tally_create")
+        self.h = h
+
+    def close(self):
+        if self.h is not None:
+            _check(_lib.tally_destroy(self.h), "tally_destroy")
+            self.h = None
+
+    def launch_native(self, kernel, hi=False):
+        _check(_lib.tally_launch_native(self.h, C.byref(kernel.desc), 1 if hi else 0),
+               "tally_launch_native")
+
+    def launch_sliced(self, kernel, slice_blocks, max_in_flight=1, coverage=False):
+        j = C.c_void_p()
+        _check(_lib.tally_launch_sliced(self.h, C.byref(kernel.desc), slice_blocks, max_in_flight,
+                                        int(coverage), C.byref(j)), "tally_launch_sliced")
+        return Job(j, kernel)
+
+    def launch_ptb(self, kernel, workers, chunk=1, coverage=False, stop_at=None):
+        j = C.c_void_p()
+        if stop_at is None:
+            _check(_lib.tally_launch_ptb(self.h, C.byref(kernel.desc), workers, chunk,
+                                         int(coverage), C.byref(j)), "tally_launch_ptb")
+        else:
+            _check(_lib.tally_launch_ptb_until(self.h, C.byref(kernel.desc), workers, chunk,
+                                               int(stop_at), int(coverage), C.byref(j)),
+                   "tally_launch_ptb_until")
+        return Job(j, kernel)
+
+    def marker(self, value, hi=True):
+        _check(_lib.tally_marker(self.h, 1 if hi else 0, value), "tally_marker")
+
+    def marker_read(self, hi=True):
+        v = C.c_uint32()
+        _check(_lib.tally_marker_read(self.h, 1 if hi else 0, C.byref(v)), "tally_marker_read")
+        return v.value
+
+    def profile(self, kernel, candidates, runs=10, threshold_ms=0.0316):
+        """candidates: list of (kind, param, chunk).  Returns (list of dicts, chosen index)."""
+        arr = (Config * len(candidates))(*[Config(k, p, c, 0.0, 0.0) for k, p, c in candidates])
+        chosen = C.c_uint32()
+        _check(_lib.tally_profile(self.h, C.byref(kernel.desc), arr, len(candidates), runs,
+                                  threshold_ms, C.byref(chosen)), "tally_profile")
+        out = [dict(kind=c.kind, param=c.param, chunk=c.chunk, latency_ms=c.latency_ms,
+                    turnaround_ms=c.turnaround_ms) for c in arr]
+        return out, chosen.value
+
+    def lookup_config(self, kernel):
+        c = Config()
+        rc = _lib.tally_lookup_config(self.h, C.byref(kernel.desc), C.byref(c))
+        if rc == ERR_BAD_STATE:
+            return None
+        _check(rc, "tally_lookup_config")
+        return dict(kind=c.kind, param=c.param, chunk=c.chunk, latency_ms=c.latency_ms,
+                    turnaround_ms=c.turnaround_ms)
+
+    def sched_run(self, hi_kernels, arrivals_us, be_items, policy=POLICY_TALLY, tail_us=0.0):
+        """hi_kernels: list of Kernel (one request).  be_items: list of (Kernel, (kind, param,
+        chunk)).  Returns a dict of numpy arrays and counters."""
+        n_hi = len(hi_kernels)
+        hi_arr = (KernelDesc * max(n_hi, 1))(*[k.desc for k in hi_kernels])
+        arrivals = np.ascontiguousarray(arrivals_us, dtype=np.float64)
+        lat = np.zeros(len(arrivals), dtype=np.float64)
+        cap = max(len(arrivals), 1)
+        pre = np.zeros(cap, dtype=np.float64)
+        items = (BeItem * max(len(be_items), 1))()
+        for i, (k, cfg) in enumerate(be_items):
+            items[i].kernel = C.pointer(k.desc)
+            items[i].config = Config(cfg[0], cfg[1], cfg[2] if len(cfg) > 2 else 1, 0.0, 0.0)
+        run = SchedRun()
+        run.hi_kernels = hi_arr
+        run.n_hi_kernels = n_hi
+        run.arrivals_us = arrivals.ctypes.data_as(C.POINTER(C.c_double))
+        run.n_arrivals = len(arrivals)
+        run.be_items = items
+        run.n_be_items = len(be_items)
+        run.policy = policy
+        run.tail_us = float(tail_us)
+        run.latency_us = lat.ctypes.data_as(C.POINTER(C.c_double))
+        run.preempt_latency_us = pre.ctypes.data_as(C.POINTER(C.c_double))
+        run.preempt_cap = cap
+        _check(_lib.tally_sched_run(self.h, C.byref(run)), "tally_sched_run")
+        return {
+            "latency_us": lat,
+            "preempt_latency_us": pre[: min(run.n_preempts, cap)].copy(),
+            "n_preempts": run.n_preempts,
+            "be_kernels_done": run.be_kernels_done,
+            "be_steps_done": run.be_steps_done,
+            "window_us": run.window_us,
+        }
+
+
+def device_info():
+    a, b, c = C.c_uint32(), C.c_uint32(), C.c_uint32()
+    _check(_lib.tally_device_info(C.byref(a), C.byref(b), C.byref(c)), "tally_device_info")
+    return {"num_cus": a.value, "lds_bytes_per_cu": b.value, "wave_size": c.value}
+
+
+def ptb_turnaround_ms(latency_ms, workers, chunk, total):
+    return _lib.tally_ptb_turnaround_ms(latency_ms, workers, chunk, total)
+
+
+def select_config(cands, threshold_ms=0.0316):
+    """cands: list of dicts with kind, param, latency_ms, turnaround_ms (chunk optional)."""
+    arr = (Config * len(cands))(*[Config(c["kind"], c["param"], c.get("chunk", 1),
+                                         c["latency_ms"], c["turnaround_ms"]) for c in cands])
+    return _lib.tally_select_config(arr, len(cands), threshold_ms)

@@ -1,0 +1,239 @@
+// HBM-streaming workload kernels as logical-block bodies: SAXPY, sum reduction, GEMV,
+// row softmax, row LayerNorm.  All are bandwidth-bound: 16-byte coalesced loads, one
+// 64-lane wave per row for the row-wise kernels, cross-lane reductions without LDS
+// where a wave owns the whole row.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/tally.h"
+
+namespace tally {
+
+constexpr int kThreads = 256;
+constexpr int kWave = 64;
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, kWave));
+  return v;
+}
+__device__ __forceinline__ float bf16_lo(uint32_t u) { return __uint_as_float(u << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t u) { return __uint_as_float(u & 0xFFFF0000u); }
+__device__ __forceinline__ uint16_t f32_to_bf16(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7FFFFFFFu) > 0x7F800000u) return 0x7FC0;  // NaN
+  return (uint16_t)((u + 0x7FFFu + ((u >> 16) & 1u)) >> 16);
+}
+
+// ---- SAXPY: thread t of block b handles element 256 b + t ----------------------------
+struct SaxpyBody {
+  using Args = tally_saxpy_args;
+  static constexpr int THREADS = kThreads;
+  static constexpr unsigned DYN_LDS = 0;
+  static __device__ __forceinline__ void run(const Args &a, uint32_t bx, uint32_t, uint32_t) {
+    uint32_t i = bx * kThreads + threadIdx.x;
+    if (i < a.n) a.y[i] = __builtin_fmaf(a.a, a.x[i], a.y[i]);
+  }
+};
+
+// ---- sum reduction: block b -> partial[b] over 4096 consecutive elements --------------
+struct ReduceSumBody {
+  using Args = tally_reduce_sum_args;
+  static constexpr int THREADS = kThreads;
+  static constexpr unsigned DYN_LDS = 0;
+  static constexpr uint32_t PER_BLOCK = 4096;
+  static __device__ __forceinline__ void run(const Args &a, uint32_t bx, uint32_t, uint32_t) {
+    __shared__ float s_part[kThreads / kWave];
+    const uint64_t base = (uint64_t)bx * PER_BLOCK;
+    float s = 0.f;
+    if (base + PER_BLOCK <= a.n) {
+      const float4 *p = reinterpret_cast<const float4 *>(a.x + base);
+      float4 v0 = p[threadIdx.x], v1 = p[threadIdx.x + 256], v2 = p[threadIdx.x + 512],
+             v3 = p[threadIdx.x + 768];
+      s = ((v0.x + v0.y) + (v0.z + v0.w)) + ((v1.x + v1.y) + (v1.z + v1.w)) +
+          (((v2.x + v2.y) + (v2.z + v2.w)) + ((v3.x + v3.y) + (v3.z + v3.w)));
+    } else {
+      for (uint64_t i = base + threadIdx.x; i < a.n; i += kThreads) s += a.x[i];
+    }
+    s = wave_sum(s);
+    // the previous logical block's readers of s_part are past the barrier that ends
+    // every iteration of the persistent-worker loop, or belong to another launch
+    if ((threadIdx.x & (kWave - 1)) == 0) s_part[threadIdx.x / kWave] = s;
+    __syncthreads();
+    if (threadIdx.x == 0) a.partial[bx] = (s_part[0] + s_part[1]) + (s_part[2] + s_part[3]);
+  }
+};
+
+struct ReduceFinalBody {
+  using Args = tally_reduce_final_args;
+  static constexpr int THREADS = kThreads;
+  static constexpr unsigned DYN_LDS = 0;
+  static __device__ __forceinline__ void run(const Args &a, uint32_t, uint32_t, uint32_t) {
+    __shared__ double s_d[kThreads];
+    double s = 0.0;
+    for (uint32_t i = threadIdx.x; i < a.count; i += kThreads) s += (double)a.partial[i];
+    s_d[threadIdx.x] = s;
+    __syncthreads();
+    for (int o = kThreads / 2; o > 0; o >>= 1) {
+      if ((int)threadIdx.x < o) s_d[threadIdx.x] += s_d[threadIdx.x + o];
+      __syncthreads();
+    }
+    if (threadIdx.x == 0) *a.total = s_d[0];
+  }
+};
+
+// ---- GEMV: one wave per output row, 16-byte loads along K -----------------------------
+struct GemvBody {
+  using Args = tally_gemv_bf16_args;
+  static constexpr int THREADS = kThreads;
+  static constexpr unsigned DYN_LDS = 0;
+  static __device__ __forceinline__ float dot8(uint4 w, uint4 x) {
+    float s = bf16_lo(w.x) * bf16_lo(x.x);
+    s = __builtin_fmaf(bf16_hi(w.x), bf16_hi(x.x), s);
+    s = __builtin_fmaf(bf16_lo(w.y), bf16_lo(x.y), s);
+    s = __builtin_fmaf(bf16_hi(w.y), bf16_hi(x.y), s);
+    s = __builtin_fmaf(bf16_lo(w.z), bf16_lo(x.z), s);
+    s = __builtin_fmaf(bf16_hi(w.z), bf16_hi(x.z), s);
+    s = __builtin_fmaf(bf16_lo(w.w), bf16_lo(x.w), s);
+    s = __builtin_fmaf(bf16_hi(w.w), bf16_hi(x.w), s);
+    return s;
+  }
+  static __device__ __forceinline__ void run(const Args &a, uint32_t bx, uint32_t, uint32_t) {
+    const uint32_t lane = threadIdx.x & (kWave - 1);
+    const uint32_t row = bx * 4 + threadIdx.x / kWave;
+    if (row >= a.n) return;  // wave-uniform; the body holds no barrier
+    const uint32_t nvec = a.k / 8;
+    const uint4 *w = reinterpret_cast<const uint4 *>(a.W + (uint64_t)row * a.k);
+    const uint4 *x = reinterpret_cast<const uint4 *>(a.x);
+    float acc0 = 0.f, acc1 = 0.f, acc2 = 0.f, acc3 = 0.f;
+    uint32_t v = lane;
+    for (; v + 3 * kWave < nvec; v += 4 * kWave) {
+      uint4 w0 = w[v], w1 = w[v + kWave], w2 = w[v + 2 * kWave], w3 = w[v + 3 * kWave];
+      acc0 += dot8(w0, x[v]);
+      acc1 += dot8(w1, x[v + kWave]);
+      acc2 += dot8(w2, x[v + 2 * kWave]);
+      acc3 += dot8(w3, x[v + 3 * kWave]);
+    }
+    for (; v < nvec; v += kWave) acc0 += dot8(w[v], x[v]);
+    float s = wave_sum((acc0 + acc1) + (acc2 + acc3));
+    if (lane == 0) a.y[row] = f32_to_bf16(s);
+  }
+};
+
+// ---- row-wise kernels: a wave keeps its row in registers as NV float4 per lane --------
+template <int NV>
+__device__ __forceinline__ void load_row(const float *row, uint32_t cols, uint32_t lane,
+                                         float4 (&v)[NV], float fill) {
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    uint32_t c = (i * kWave + lane) * 4;
+    v[i] = (c < cols) ? *reinterpret_cast<const float4 *>(row + c)
+                      : make_float4(fill, fill, fill, fill);
+  }
+}
+
+template <int NV>
+__device__ __forceinline__ void softmax_row(const float *x, float *y, uint32_t cols, uint32_t lane) {
+  float4 v[NV];
+  load_row<NV>(x, cols, lane, v, -INFINITY);
+  float m = -INFINITY;
+#pragma unroll
+  for (int i = 0; i < NV; ++i) m = fmaxf(m, fmaxf(fmaxf(v[i].x, v[i].y), fmaxf(v[i].z, v[i].w)));
+  m = wave_max(m);
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    v[i].x = __expf(v[i].x - m); v[i].y = __expf(v[i].y - m);
+    v[i].z = __expf(v[i].z - m); v[i].w = __expf(v[i].w - m);
+    s += (v[i].x + v[i].y) + (v[i].z + v[i].w);
+  }
+  s = wave_sum(s);
+  const float inv = 1.0f / s;
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    uint32_t c = (i * kWave + lane) * 4;
+    if (c < cols)
+      *reinterpret_cast<float4 *>(y + c) =
+          make_float4(v[i].x * inv, v[i].y * inv, v[i].z * inv, v[i].w * inv);
+  }
+}
+
+struct SoftmaxBody {
+  using Args = tally_softmax_f32_args;
+  static constexpr int THREADS = kThreads;
+  static constexpr unsigned DYN_LDS = 0;
+  static __device__ __forceinline__ void run(const Args &a, uint32_t bx, uint32_t, uint32_t) {
+    const uint32_t lane = threadIdx.x & (kWave - 1);
+    const uint32_t row = bx * 4 + threadIdx.x / kWave;
+    if (row >= a.rows) return;
+    const float *x = a.x + (uint64_t)row * a.cols;
+    float *y = a.y + (uint64_t)row * a.cols;
+    if (a.cols <= 256) softmax_row<1>(x, y, a.cols, lane);
+    else if (a.cols <= 512) softmax_row<2>(x, y, a.cols, lane);
+    else if (a.cols <= 1024) softmax_row<4>(x, y, a.cols, lane);
+    else if (a.cols <= 2048) softmax_row<8>(x, y, a.cols, lane);
+    else if (a.cols <= 4096) softmax_row<16>(x, y, a.cols, lane);
+    else softmax_row<32>(x, y, a.cols, lane);
+  }
+};
+
+template <int NV>
+__device__ __forceinline__ void layernorm_row(const float *x, const float *g, const float *b,
+                                              float *y, uint32_t cols, float eps, uint32_t lane) {
+  float4 v[NV];
+  load_row<NV>(x, cols, lane, v, 0.f);
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < NV; ++i) s += (v[i].x + v[i].y) + (v[i].z + v[i].w);
+  const float mu = wave_sum(s) / (float)cols;
+  float q = 0.f;
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    uint32_t c = (i * kWave + lane) * 4;
+    if (c < cols) {
+      float dx = v[i].x - mu, dy = v[i].y - mu, dz = v[i].z - mu, dw = v[i].w - mu;
+      q += (dx * dx + dy * dy) + (dz * dz + dw * dw);
+    }
+  }
+  const float rstd = 1.0f / sqrtf(wave_sum(q) / (float)cols + eps);
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    uint32_t c = (i * kWave + lane) * 4;
+    if (c < cols) {
+      float4 gg = *reinterpret_cast<const float4 *>(g + c);
+      float4 bb = *reinterpret_cast<const float4 *>(b + c);
+      *reinterpret_cast<float4 *>(y + c) = make_float4(
+          __builtin_fmaf((v[i].x - mu) * rstd, gg.x, bb.x),
+          __builtin_fmaf((v[i].y - mu) * rstd, gg.y, bb.y),
+          __builtin_fmaf((v[i].z - mu) * rstd, gg.z, bb.z),
+          __builtin_fmaf((v[i].w - mu) * rstd, gg.w, bb.w));
+    }
+  }
+}
+
+struct LayerNormBody {
+  using Args = tally_layernorm_f32_args;
+  static constexpr int THREADS = kThreads;
+  static constexpr unsigned DYN_LDS = 0;
+  static __device__ __forceinline__ void run(const Args &a, uint32_t bx, uint32_t, uint32_t) {
+    const uint32_t lane = threadIdx.x & (kWave - 1);
+    const uint32_t row = bx * 4 + threadIdx.x / kWave;
+    if (row >= a.rows) return;
+    const float *x = a.x + (uint64_t)row * a.cols;
+    float *y = a.y + (uint64_t)row * a.cols;
+    if (a.cols <= 256) layernorm_row<1>(x, a.gamma, a.beta, y, a.cols, a.eps, lane);
+    else if (a.cols <= 512) layernorm_row<2>(x, a.gamma, a.beta, y, a.cols, a.eps, lane);
+    else if (a.cols <= 1024) layernorm_row<4>(x, a.gamma, a.beta, y, a.cols, a.eps, lane);
+    else if (a.cols <= 2048) layernorm_row<8>(x, a.gamma, a.beta, y, a.cols, a.eps, lane);
+    else if (a.cols <= 4096) layernorm_row<16>(x, a.gamma, a.beta, y, a.cols, a.eps, lane);
+    else layernorm_row<32>(x, a.gamma, a.beta, y, a.cols, a.eps, lane);
+  }
+};
+
+}  // namespace tally

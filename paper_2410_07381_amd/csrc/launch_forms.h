@@ -1,0 +1,155 @@
+// The three launch forms of a best-effort kernel, generated from one logical-block body.
+//
+// A Body is a struct with
+//   using Args = <POD passed by value to the kernel>;
+//   static constexpr int THREADS;            threads per logical block
+//   static constexpr unsigned DYN_LDS;       dynamic LDS bytes the body needs
+//   static __device__ void run(const Args&, uint32_t bx, uint32_t by, uint32_t bz);
+// run() performs the work of original block (bx,by,bz); every thread of the workgroup
+// calls it and returns from it (no early exit), so the workgroup-wide barriers of the
+// persistent-worker loop are reached by all threads (Section 4.1: divergent barriers
+// stall a kernel for ever; hand-written bodies handle ragged tails by predication).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/tally.h"
+
+namespace tally {
+
+constexpr uint32_t kStop = 0xFFFFFFFFu;
+
+// Device-side control block of one persistent-worker launch segment.
+struct PtbCtl {
+  uint32_t *counter;        // device: global task counter (next task index)
+  uint32_t *dev_flag;       // device: holds the epoch of the last preemption seen by the relay
+  uint32_t *exited;         // device: workers that have exited, summed over all segments
+  const uint32_t *host_flag;  // pinned host memory: epoch the host wants preempted
+  unsigned long long *host_status;  // pinned: (epoch << 32 | progress) once drained
+  uint32_t *host_live;      // pinned: progress mirrored while running
+  tally_cover_rec *cover;   // device, may be null
+  uint32_t total;           // logical blocks in the grid
+  uint32_t limit;           // workers treat this as the end of the grid (== total normally)
+  uint32_t epoch;           // id of this launch segment (1, 2, ...)
+  uint32_t exit_target;     // value of *exited after the last worker of this segment leaves
+  uint32_t workers;
+  uint32_t chunk;           // task indices per fetch
+  uint32_t segment;         // 0-based segment number, for the coverage records
+  uint32_t gx, gy;          // logical grid extents (x fastest)
+};
+
+struct SliceCtl {
+  tally_cover_rec *cover;
+  uint32_t offset;          // first logical block of this sub-kernel
+  uint32_t gx, gy;
+  uint32_t segment;
+};
+
+__device__ __forceinline__ void delinearize(uint32_t idx, uint32_t gx, uint32_t gy, uint32_t &bx,
+                                            uint32_t &by, uint32_t &bz) {
+  bx = idx % gx;
+  uint32_t r = idx / gx;
+  by = r % gy;
+  bz = r / gy;
+}
+
+__device__ __forceinline__ void record(tally_cover_rec *cover, uint32_t idx, uint32_t bx,
+                                       uint32_t by, uint32_t bz, uint32_t segment,
+                                       uint32_t worker) {
+  if (cover != nullptr && threadIdx.x == 0) {
+    tally_cover_rec *r = cover + idx;
+    atomicAdd(&r->count, 1u);
+    r->bx = bx; r->by = by; r->bz = bz; r->segment = segment; r->worker = worker;
+  }
+}
+
+// ---- original form -------------------------------------------------------------------
+template <class Body>
+__global__ __launch_bounds__(Body::THREADS) void native_kernel(typename Body::Args args) {
+  Body::run(args, blockIdx.x, blockIdx.y, blockIdx.z);
+}
+
+// ---- sliced form: logical block = offset + blockIdx (Section 4.1, slicing) -----------
+template <class Body>
+__global__ __launch_bounds__(Body::THREADS) void sliced_kernel(typename Body::Args args,
+                                                               SliceCtl ctl) {
+  uint32_t idx = ctl.offset + blockIdx.x, bx, by, bz;
+  delinearize(idx, ctl.gx, ctl.gy, bx, by, bz);
+  Body::run(args, bx, by, bz);
+  record(ctl.cover, idx, bx, by, bz, ctl.segment, blockIdx.x);
+}
+
+// ---- persistent-worker form (Section 4.1, preemption) --------------------------------
+// Workgroup 0 is not a worker: one lane of it relays the host's preemption request from
+// pinned host memory (cheap for the host to write, slow to poll) into a device-memory
+// flag (cheap for hundreds of workers to poll), and mirrors progress back to the host.
+// It leaves as soon as the request is relayed or every worker has exited.
+__device__ __forceinline__ void relay_loop(const PtbCtl &c) {
+  if (threadIdx.x != 0) return;
+  for (;;) {
+    uint32_t want = __hip_atomic_load(c.host_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    if (want == c.epoch) {
+      __hip_atomic_store(c.dev_flag, c.epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      return;
+    }
+    uint32_t gone = __hip_atomic_load(c.exited, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (gone == c.exit_target) return;
+    uint32_t ctr = __hip_atomic_load(c.counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(c.host_live, ctr < c.limit ? ctr : c.limit, __ATOMIC_RELAXED,
+                       __HIP_MEMORY_SCOPE_SYSTEM);
+  }
+}
+
+template <class Body>
+__global__ __launch_bounds__(Body::THREADS) void ptb_kernel(typename Body::Args args, PtbCtl c) {
+  if (blockIdx.x == 0) {
+    relay_loop(c);
+    return;
+  }
+  __shared__ uint32_t s_idx;
+  const uint32_t worker = blockIdx.x - 1;
+  for (;;) {
+    // start of an iteration: check the flag, THEN fetch; a fetched index is always run
+    if (threadIdx.x == 0) {
+      uint32_t f = __hip_atomic_load(c.dev_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      s_idx = (f == c.epoch) ? kStop
+                             : __hip_atomic_fetch_add(c.counter, c.chunk, __ATOMIC_RELAXED,
+                                                      __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __syncthreads();
+    const uint32_t first = s_idx;
+    if (first >= c.limit) break;  // uniform across the workgroup
+    const uint32_t last = (c.limit - first < c.chunk) ? c.limit : first + c.chunk;
+    for (uint32_t idx = first; idx < last; ++idx) {
+      uint32_t bx, by, bz;
+      delinearize(idx, c.gx, c.gy, bx, by, bz);
+      Body::run(args, bx, by, bz);
+      record(c.cover, idx, bx, by, bz, c.segment, worker);
+      __syncthreads();  // one logical block at a time per worker
+    }
+  }
+  // leave: the last worker of the segment publishes the progress to the host
+  if (threadIdx.x == 0) {
+    uint32_t old = __hip_atomic_fetch_add(c.exited, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+    if (old + 1 == c.exit_target) {
+      uint32_t ctr = __hip_atomic_load(c.counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      uint32_t progress = ctr < c.limit ? ctr : c.limit;
+      __hip_atomic_store(c.host_live, progress, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+      __hip_atomic_store(c.host_status, ((unsigned long long)c.epoch << 32) | progress,
+                         __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+    }
+  }
+}
+
+// Marker: stores a value into a pinned host word once earlier work on the stream is done.
+__global__ void marker_kernel(uint32_t *word, uint32_t value) {
+  if (threadIdx.x == 0)
+    __hip_atomic_store(word, value, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+}
+
+__global__ void set_word_kernel(uint32_t *word, uint32_t value) {
+  if (threadIdx.x == 0)
+    __hip_atomic_store(word, value, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+}  // namespace tally

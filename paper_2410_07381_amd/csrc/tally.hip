@@ -1,0 +1,911 @@
+// C ABI of the block-level kernel scheduling library (see include/tally.h).
+//
+// Host side of: native / sliced / persistent-worker launches (Section 4.1), preempt /
+// drain / resume (Section 4.1), profile-guided configuration choice (Section 4.2, Eq. 1)
+// and the two-stream priority scheduling loop (Section 4.2, Figure 4).
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <string.h>
+
+#include <atomic>
+#include <chrono>
+#include <map>
+#include <mutex>
+#include <new>
+#include <tuple>
+#include <vector>
+
+#include "../../include/tally.h"
+#include "kernels_attn.h"
+#include "kernels_gemm.h"
+#include "kernels_stream.h"
+#include "launch_forms.h"
+
+using namespace tally;
+
+namespace {
+
+thread_local int g_last_hip = 0;
+#define HIPCHK(expr)                                \
+  do {                                              \
+    hipError_t e_ = (expr);                         \
+    if (e_ != hipSuccess) {                         \
+      g_last_hip = (int)e_;                         \
+      return TALLY_ERR_HIP;                         \
+    }                                               \
+  } while (0)
+
+double now_us() {
+  return std::chrono::duration<double, std::micro>(
+             std::chrono::steady_clock::now().time_since_epoch())
+      .count();
+}
+
+uint32_t cdiv(uint64_t a, uint64_t b) { return (uint32_t)((a + b - 1) / b); }
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// ---------------------------------------------------------------------------- registry
+struct KernelOps {
+  const char *name;
+  size_t args_size;
+  bool transformable;  // false: native form only
+  int (*grid)(const void *args, tally_dim3 *g, tally_dim3 *b);
+  hipError_t (*native)(hipStream_t, const void *args, tally_dim3 g);
+  hipError_t (*sliced)(hipStream_t, const void *args, uint32_t nblocks, const SliceCtl &);
+  hipError_t (*ptb)(hipStream_t, const void *args, const PtbCtl &);
+  hipError_t (*init)();
+  int (*occupancy)(int *blocks_per_cu);
+};
+
+template <class Body>
+hipError_t launch_native_t(hipStream_t s, const void *args, tally_dim3 g) {
+  typename Body::Args a;
+  memcpy(&a, args, sizeof(a));
+  hipLaunchKernelGGL(native_kernel<Body>, dim3(g.x, g.y, g.z), dim3(Body::THREADS), Body::DYN_LDS,
+                     s, a);
+  return hipGetLastError();
+}
+template <class Body>
+hipError_t launch_sliced_t(hipStream_t s, const void *args, uint32_t nblocks, const SliceCtl &c) {
+  typename Body::Args a;
+  memcpy(&a, args, sizeof(a));
+  hipLaunchKernelGGL(sliced_kernel<Body>, dim3(nblocks), dim3(Body::THREADS), Body::DYN_LDS, s, a,
+                     c);
+  return hipGetLastError();
+}
+template <class Body>
+hipError_t launch_ptb_t(hipStream_t s, const void *args, const PtbCtl &c) {
+  typename Body::Args a;
+  memcpy(&a, args, sizeof(a));
+  hipLaunchKernelGGL(ptb_kernel<Body>, dim3(c.workers + 1), dim3(Body::THREADS), Body::DYN_LDS, s,
+                     a, c);
+  return hipGetLastError();
+}
+template <class Body>
+hipError_t init_t() {
+  if (Body::DYN_LDS > 64 * 1024) {
+    hipError_t e;
+    e = hipFuncSetAttribute((const void *)native_kernel<Body>,
+                            hipFuncAttributeMaxDynamicSharedMemorySize, Body::DYN_LDS);
+    if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute((const void *)sliced_kernel<Body>,
+                            hipFuncAttributeMaxDynamicSharedMemorySize, Body::DYN_LDS);
+    if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute((const void *)ptb_kernel<Body>,
+                            hipFuncAttributeMaxDynamicSharedMemorySize, Body::DYN_LDS);
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
+}
+template <class Body>
+int occupancy_t(int *blocks_per_cu) {
+  HIPCHK(hipOccupancyMaxActiveBlocksPerMultiprocessor(blocks_per_cu, ptb_kernel<Body>,
+                                                      Body::THREADS, Body::DYN_LDS));
+  return TALLY_OK;
+}
+
+const tally_dim3 kBlock256 = {256, 1, 1};
+
+int grid_saxpy(const void *p, tally_dim3 *g, tally_dim3 *b) {
+  auto *a = static_cast<const tally_saxpy_args *>(p);
+  if (!a->x || !a->y || a->n == 0) return TALLY_ERR_INVALID_ARG;
+  *g = {cdiv(a->n, 256), 1, 1};
+  *b = kBlock256;
+  return TALLY_OK;
+}
+int grid_reduce_sum(const void *p, tally_dim3 *g, tally_dim3 *b) {
+  auto *a = static_cast<const tally_reduce_sum_args *>(p);
+  if (!a->x || !a->partial || a->n == 0 || !aligned16(a->x)) return TALLY_ERR_INVALID_ARG;
+  if (a->n > 4096ull * 0x7FFFFFFFull) return TALLY_ERR_INVALID_ARG;
+  *g = {cdiv(a->n, 4096), 1, 1};
+  *b = kBlock256;
+  return TALLY_OK;
+}
+int grid_reduce_final(const void *p, tally_dim3 *g, tally_dim3 *b) {
+  auto *a = static_cast<const tally_reduce_final_args *>(p);
+  if (!a->partial || !a->total || a->count == 0) return TALLY_ERR_INVALID_ARG;
+  *g = {1, 1, 1};
+  *b = kBlock256;
+  return TALLY_OK;
+}
+int grid_gemm_common(const tally_gemm_bf16_args *a) {
+  if (!a->A || !a->Bt || !a->C || !a->m || !a->n || !a->k || !a->batch) return TALLY_ERR_INVALID_ARG;
+  if (!aligned16(a->A) || !aligned16(a->Bt) || (a->stride_a % 8) || (a->stride_b % 8))
+    return TALLY_ERR_INVALID_ARG;
+  if (a->batch > 1 && (a->stride_a < (uint64_t)a->m * a->k || a->stride_b < (uint64_t)a->n * a->k ||
+                       a->stride_c < (uint64_t)a->m * a->n))
+    return TALLY_ERR_INVALID_ARG;
+  return TALLY_OK;
+}
+int grid_gemm(const void *p, tally_dim3 *g, tally_dim3 *b) {
+  auto *a = static_cast<const tally_gemm_bf16_args *>(p);
+  int rc = grid_gemm_common(a);
+  if (rc) return rc;
+  if ((a->m % 256) || (a->n % 256) || (a->k % 64)) return TALLY_ERR_INVALID_ARG;
+  *g = {a->n / 256, a->m / 256, a->batch};
+  *b = kBlock256;
+  return TALLY_OK;
+}
+int grid_gemm_small(const void *p, tally_dim3 *g, tally_dim3 *b) {
+  auto *a = static_cast<const tally_gemm_bf16_args *>(p);
+  int rc = grid_gemm_common(a);
+  if (rc) return rc;
+  if (a->k % 32) return TALLY_ERR_INVALID_ARG;
+  *g = {cdiv(a->n, 64), cdiv(a->m, 64), a->batch};
+  *b = kBlock256;
+  return TALLY_OK;
+}
+int grid_gemv(const void *p, tally_dim3 *g, tally_dim3 *b) {
+  auto *a = static_cast<const tally_gemv_bf16_args *>(p);
+  if (!a->x || !a->W || !a->y || !a->n || !a->k || (a->k % 8) || !aligned16(a->x) || !aligned16(a->W))
+    return TALLY_ERR_INVALID_ARG;
+  *g = {cdiv(a->n, 4), 1, 1};
+  *b = kBlock256;
+  return TALLY_OK;
+}
+int grid_softmax(const void *p, tally_dim3 *g, tally_dim3 *b) {
+  auto *a = static_cast<const tally_softmax_f32_args *>(p);
+  if (!a->x || !a->y || !a->rows || !a->cols || (a->cols % 4) || a->cols > 8192 || !aligned16(a->x) ||
+      !aligned16(a->y))
+    return TALLY_ERR_INVALID_ARG;
+  *g = {cdiv(a->rows, 4), 1, 1};
+  *b = kBlock256;
+  return TALLY_OK;
+}
+int grid_layernorm(const void *p, tally_dim3 *g, tally_dim3 *b) {
+  auto *a = static_cast<const tally_layernorm_f32_args *>(p);
+  if (!a->x || !a->y || !a->gamma || !a->beta || !a->rows || !a->cols || (a->cols % 4) ||
+      a->cols > 8192 || !aligned16(a->x) || !aligned16(a->y) || !aligned16(a->gamma) ||
+      !aligned16(a->beta))
+    return TALLY_ERR_INVALID_ARG;
+  *g = {cdiv(a->rows, 4), 1, 1};
+  *b = kBlock256;
+  return TALLY_OK;
+}
+int grid_attn(const void *p, tally_dim3 *g, tally_dim3 *b) {
+  auto *a = static_cast<const tally_attn_decode_args *>(p);
+  if (!a->q || !a->K || !a->V || !a->out || !a->scratch || !a->tokens || !a->heads || a->dim != 128 ||
+      a->tokens > kAttnSplits * kAttnMaxChunk ||
+      !aligned16(a->q) || !aligned16(a->K) || !aligned16(a->V))
+    return TALLY_ERR_INVALID_ARG;
+  *g = {a->heads, 1, 1};
+  *b = kBlock256;
+  return TALLY_OK;
+}
+
+#define OPS(Body, nm, gridfn)                                                              \
+  {nm, sizeof(Body::Args), true, gridfn, launch_native_t<Body>, launch_sliced_t<Body>,     \
+   launch_ptb_t<Body>, init_t<Body>, occupancy_t<Body>}
+
+const KernelOps kOps[TALLY_K_COUNT] = {
+    OPS(SaxpyBody, "saxpy", grid_saxpy),
+    OPS(ReduceSumBody, "reduce_sum", grid_reduce_sum),
+    OPS(ReduceFinalBody, "reduce_final", grid_reduce_final),
+    OPS(GemmBody, "gemm_bf16", grid_gemm),
+    OPS(GemvBody, "gemv_bf16", grid_gemv),
+    OPS(SoftmaxBody, "softmax_f32", grid_softmax),
+    OPS(LayerNormBody, "layernorm_f32", grid_layernorm),
+    {"attn_decode_bf16", sizeof(tally_attn_decode_args), false, grid_attn, launch_attn_decode,
+     nullptr, nullptr, nullptr, nullptr},
+    OPS(GemmSmallBody, "gemm_bf16_small", grid_gemm_small),
+};
+
+constexpr size_t kMaxArgs = 96;
+constexpr int kSlots = 64;
+constexpr size_t kDevSlotBytes = 512;   // counter | dev_flag | exited, 128 B apart
+constexpr size_t kHostSlotBytes = 256;  // host_flag | status,live | slice_done
+
+enum JobKind { KIND_PTB = 0, KIND_SLICED = 1, KIND_NATIVE = 2 };
+
+}  // namespace
+
+struct tally_ctx {
+  hipStream_t hi, be;
+  unsigned char *dev_pool;   // device
+  unsigned char *host_pool;  // pinned host
+  unsigned char *host_pool_dev;
+  bool slot_used[kSlots];
+  int next_slot;
+  uint32_t *marker_host;     // pinned: [0] hi, [32] be (separate lines)
+  uint32_t *marker_dev;
+  uint32_t num_cus;
+  int live_jobs;
+  std::map<std::tuple<uint32_t, uint32_t, uint32_t, uint32_t, uint32_t>, tally_config> chosen;
+};
+
+struct tally_job {
+  tally_ctx *ctx;
+  const KernelOps *ops;
+  alignas(16) unsigned char args[kMaxArgs];
+  tally_dim3 grid;
+  uint32_t total;
+  int kind;
+  int slot;
+  tally_cover_rec *cover;
+  std::atomic<int> state;
+  std::atomic<uint32_t> progress;
+  // persistent workers
+  uint32_t workers, chunk, epoch, limit;
+  bool counter_dirty;        // counter overshot a stop_at limit and must be rewound
+  // sliced
+  uint32_t slice_blocks, max_in_flight, next_off, issued, retired, segment;
+  std::atomic<bool> stop_issuing;
+  // preemption latency
+  std::atomic<double> t_preempt;
+  double preempt_latency_us;
+
+  uint32_t *d_counter() { return (uint32_t *)(ctx->dev_pool + slot * kDevSlotBytes); }
+  uint32_t *d_flag() { return (uint32_t *)(ctx->dev_pool + slot * kDevSlotBytes + 128); }
+  uint32_t *d_exited() { return (uint32_t *)(ctx->dev_pool + slot * kDevSlotBytes + 256); }
+  unsigned char *h_base() { return ctx->host_pool + slot * kHostSlotBytes; }
+  unsigned char *h_base_dev() { return ctx->host_pool_dev + slot * kHostSlotBytes; }
+  uint32_t *h_flag() { return (uint32_t *)h_base(); }
+  unsigned long long *h_status() { return (unsigned long long *)(h_base() + 64); }
+  uint32_t *h_live() { return (uint32_t *)(h_base() + 72); }
+  uint32_t *h_slice_done() { return (uint32_t *)(h_base() + 128); }
+};
+
+namespace {
+
+int check_desc(const tally_kernel_desc *d, const KernelOps **ops_out, tally_dim3 *grid) {
+  if (!d || !d->args || d->kernel_id >= TALLY_K_COUNT) return TALLY_ERR_INVALID_ARG;
+  const KernelOps *ops = &kOps[d->kernel_id];
+  if (d->args_size != ops->args_size || ops->args_size > kMaxArgs) return TALLY_ERR_INVALID_ARG;
+  tally_dim3 g, b;
+  int rc = ops->grid(d->args, &g, &b);
+  if (rc) return rc;
+  if (d->grid.x != g.x || d->grid.y != g.y || d->grid.z != g.z || d->block.x != b.x ||
+      d->block.y != b.y || d->block.z != b.z)
+    return TALLY_ERR_INVALID_ARG;
+  if ((uint64_t)g.x * g.y * g.z > 0x7FFFFFFFull) return TALLY_ERR_INVALID_ARG;
+  *ops_out = ops;
+  *grid = g;
+  return TALLY_OK;
+}
+
+int new_job(tally_ctx *ctx, const tally_kernel_desc *desc, int kind, int coverage, tally_job **out) {
+  const KernelOps *ops;
+  tally_dim3 g;
+  int rc = check_desc(desc, &ops, &g);
+  if (rc) return rc;
+  if (kind != KIND_NATIVE && !ops->transformable) return TALLY_ERR_UNSUPPORTED;
+  // slots are handed out round-robin so that a freed slot rests before it is reused
+  int slot = -1;
+  for (int i = 0; i < kSlots; ++i) {
+    int s = (ctx->next_slot + i) % kSlots;
+    if (!ctx->slot_used[s]) { slot = s; break; }
+  }
+  if (slot < 0) return TALLY_ERR_NOMEM;
+  ctx->next_slot = (slot + 1) % kSlots;
+  tally_job *j = new (std::nothrow) tally_job();
+  if (!j) return TALLY_ERR_NOMEM;
+  j->ctx = ctx;
+  j->ops = ops;
+  memcpy(j->args, desc->args, ops->args_size);
+  j->grid = g;
+  j->total = g.x * g.y * g.z;
+  j->kind = kind;
+  j->slot = slot;
+  j->cover = nullptr;
+  j->state = TALLY_JOB_QUEUED;
+  j->progress = 0;
+  j->workers = j->chunk = j->epoch = 0;
+  j->limit = j->total;
+  j->counter_dirty = false;
+  j->slice_blocks = j->max_in_flight = j->next_off = j->issued = j->retired = j->segment = 0;
+  j->stop_issuing = false;
+  j->t_preempt = 0.0;
+  j->preempt_latency_us = -1.0;
+  hipError_t e = hipMemsetAsync(ctx->dev_pool + slot * kDevSlotBytes, 0, kDevSlotBytes, ctx->be);
+  if (e == hipSuccess && coverage) {
+    e = hipMalloc((void **)&j->cover, sizeof(tally_cover_rec) * (size_t)j->total);
+    if (e == hipSuccess)
+      e = hipMemsetAsync(j->cover, 0, sizeof(tally_cover_rec) * (size_t)j->total, ctx->be);
+  }
+  if (e != hipSuccess) {
+    g_last_hip = (int)e;
+    if (j->cover) (void)hipFree(j->cover);
+    delete j;
+    return e == hipErrorOutOfMemory ? TALLY_ERR_NOMEM : TALLY_ERR_HIP;
+  }
+  memset(j->h_base(), 0, kHostSlotBytes);
+  ctx->slot_used[slot] = true;
+  ctx->live_jobs++;
+  *out = j;
+  return TALLY_OK;
+}
+
+int ptb_launch_segment(tally_job *j, uint32_t limit) {
+  tally_ctx *ctx = j->ctx;
+  if (j->counter_dirty) {
+    hipLaunchKernelGGL(set_word_kernel, dim3(1), dim3(64), 0, ctx->be, j->d_counter(),
+                       j->progress.load());
+    HIPCHK(hipGetLastError());
+    j->counter_dirty = false;
+  }
+  j->epoch += 1;
+  j->limit = limit < j->total ? limit : j->total;
+  PtbCtl c;
+  c.counter = j->d_counter();
+  c.dev_flag = j->d_flag();
+  c.exited = j->d_exited();
+  c.host_flag = (const uint32_t *)j->h_base_dev();
+  c.host_status = (unsigned long long *)(j->h_base_dev() + 64);
+  c.host_live = (uint32_t *)(j->h_base_dev() + 72);
+  c.cover = j->cover;
+  c.total = j->total;
+  c.limit = j->limit;
+  c.epoch = j->epoch;
+  c.exit_target = j->workers * j->epoch;
+  c.workers = j->workers;
+  c.chunk = j->chunk;
+  c.segment = j->epoch - 1;
+  c.gx = j->grid.x;
+  c.gy = j->grid.y;
+  j->t_preempt = 0.0;
+  j->state = TALLY_JOB_RUNNING;
+  HIPCHK(j->ops->ptb(ctx->be, j->args, c));
+  return TALLY_OK;
+}
+
+int sliced_issue(tally_job *j) {
+  tally_ctx *ctx = j->ctx;
+  while (!j->stop_issuing.load() && j->next_off < j->total &&
+         j->issued - j->retired < j->max_in_flight) {
+    uint32_t n = j->total - j->next_off;
+    if (n > j->slice_blocks) n = j->slice_blocks;
+    SliceCtl c;
+    c.cover = j->cover;
+    c.offset = j->next_off;
+    c.gx = j->grid.x;
+    c.gy = j->grid.y;
+    c.segment = j->segment;
+    HIPCHK(j->ops->sliced(ctx->be, j->args, n, c));
+    j->issued += 1;
+    j->next_off += n;
+    hipLaunchKernelGGL(marker_kernel, dim3(1), dim3(64), 0, ctx->be,
+                       (uint32_t *)(j->h_base_dev() + 128), j->issued);
+    HIPCHK(hipGetLastError());
+  }
+  return TALLY_OK;
+}
+
+// Bring the host-side state up to date with what the device has published.
+void refresh(tally_job *j) {
+  if (j->state.load() != TALLY_JOB_RUNNING) return;
+  if (j->kind == KIND_PTB) {
+    unsigned long long st = __atomic_load_n(j->h_status(), __ATOMIC_ACQUIRE);
+    if ((uint32_t)(st >> 32) == j->epoch) {
+      uint32_t p = (uint32_t)st;
+      j->progress = p;
+      double tp = j->t_preempt.load();
+      j->preempt_latency_us = (tp > 0.0 && p < j->total) ? now_us() - tp : -1.0;
+      if (j->limit < j->total) j->counter_dirty = true;
+      j->state = (p >= j->total) ? TALLY_JOB_COMPLETE : TALLY_JOB_STOPPED;
+    } else {
+      uint32_t live = __atomic_load_n(j->h_live(), __ATOMIC_RELAXED);
+      if (live > j->progress.load()) j->progress = live;
+    }
+  } else {
+    uint32_t done = __atomic_load_n(j->h_slice_done(), __ATOMIC_ACQUIRE);
+    j->retired = done;
+    if (j->kind == KIND_NATIVE) {
+      if (done >= 1) { j->progress = j->total; j->state = TALLY_JOB_COMPLETE; }
+      return;
+    }
+    uint64_t p = (uint64_t)done * j->slice_blocks;
+    if (p > j->total) p = j->total;
+    j->progress = (uint32_t)p;
+    if (p >= j->total) {
+      j->state = TALLY_JOB_COMPLETE;
+    } else if (j->stop_issuing.load() && j->retired == j->issued) {
+      double tp = j->t_preempt.load();
+      j->preempt_latency_us = tp > 0.0 ? now_us() - tp : -1.0;
+      j->state = TALLY_JOB_STOPPED;
+    }
+  }
+}
+
+int launch_be_item(tally_ctx *ctx, const tally_be_item *it, tally_job **out);
+
+}  // namespace
+
+// ================================================================================ C ABI
+extern "C" {
+
+int tally_create(tally_ctx **out, void *hip_stream_hi, void *hip_stream_be) {
+  if (!out) return TALLY_ERR_INVALID_ARG;
+  tally_ctx *c = new (std::nothrow) tally_ctx();
+  if (!c) return TALLY_ERR_NOMEM;
+  c->hi = (hipStream_t)hip_stream_hi;
+  c->be = (hipStream_t)hip_stream_be;
+  c->dev_pool = nullptr;
+  c->host_pool = nullptr;
+  c->marker_host = nullptr;
+  memset(c->slot_used, 0, sizeof(c->slot_used));
+  c->live_jobs = 0;
+  c->next_slot = 0;
+  hipError_t e;
+  int dev = 0;
+  hipDeviceProp_t prop;
+  if ((e = hipGetDevice(&dev)) != hipSuccess || (e = hipGetDeviceProperties(&prop, dev)) != hipSuccess ||
+      (e = hipMalloc((void **)&c->dev_pool, kSlots * kDevSlotBytes)) != hipSuccess ||
+      (e = hipMemset(c->dev_pool, 0, kSlots * kDevSlotBytes)) != hipSuccess ||
+      (e = hipHostMalloc((void **)&c->host_pool, kSlots * kHostSlotBytes, hipHostMallocDefault)) != hipSuccess ||
+      (e = hipHostGetDevicePointer((void **)&c->host_pool_dev, c->host_pool, 0)) != hipSuccess ||
+      (e = hipHostMalloc((void **)&c->marker_host, 256, hipHostMallocDefault)) != hipSuccess ||
+      (e = hipHostGetDevicePointer((void **)&c->marker_dev, c->marker_host, 0)) != hipSuccess) {
+    g_last_hip = (int)e;
+    if (c->dev_pool) (void)hipFree(c->dev_pool);
+    if (c->host_pool) (void)hipHostFree(c->host_pool);
+    if (c->marker_host) (void)hipHostFree(c->marker_host);
+    delete c;
+    return TALLY_ERR_HIP;
+  }
+  memset(c->host_pool, 0, kSlots * kHostSlotBytes);
+  memset(c->marker_host, 0, 256);
+  c->num_cus = (uint32_t)prop.multiProcessorCount;
+  for (int k = 0; k < TALLY_K_COUNT; ++k)
+    if (kOps[k].init && (e = kOps[k].init()) != hipSuccess) {
+      g_last_hip = (int)e;
+      tally_destroy(c);
+      return TALLY_ERR_HIP;
+    }
+  if ((e = attn_decode_init()) != hipSuccess) {
+    g_last_hip = (int)e;
+    tally_destroy(c);
+    return TALLY_ERR_HIP;
+  }
+  *out = c;
+  return TALLY_OK;
+}
+
+int tally_destroy(tally_ctx *ctx) {
+  if (!ctx) return TALLY_ERR_INVALID_ARG;
+  if (ctx->live_jobs != 0) return TALLY_ERR_BAD_STATE;
+  (void)hipStreamSynchronize(ctx->hi);
+  (void)hipStreamSynchronize(ctx->be);
+  (void)hipFree(ctx->dev_pool);
+  (void)hipHostFree(ctx->host_pool);
+  (void)hipHostFree(ctx->marker_host);
+  delete ctx;
+  return TALLY_OK;
+}
+
+int tally_logical_grid(uint32_t kernel_id, const void *args, size_t args_size, tally_dim3 *grid,
+                       tally_dim3 *block) {
+  if (kernel_id >= TALLY_K_COUNT || !args || !grid || !block) return TALLY_ERR_INVALID_ARG;
+  if (args_size != kOps[kernel_id].args_size) return TALLY_ERR_INVALID_ARG;
+  tally_dim3 g, b;
+  int rc = kOps[kernel_id].grid(args, &g, &b);
+  if (rc) return rc;
+  *grid = g;
+  *block = b;
+  return TALLY_OK;
+}
+
+size_t tally_attn_decode_scratch_bytes(uint32_t heads) { return attn_decode_scratch_bytes(heads); }
+
+int tally_launch_native(tally_ctx *ctx, const tally_kernel_desc *desc, int on_hi_stream) {
+  if (!ctx) return TALLY_ERR_INVALID_ARG;
+  const KernelOps *ops;
+  tally_dim3 g;
+  int rc = check_desc(desc, &ops, &g);
+  if (rc) return rc;
+  HIPCHK(ops->native(on_hi_stream ? ctx->hi : ctx->be, desc->args, g));
+  return TALLY_OK;
+}
+
+int tally_launch_sliced(tally_ctx *ctx, const tally_kernel_desc *desc, uint32_t slice_blocks,
+                        uint32_t max_in_flight, int coverage, tally_job **out) {
+  if (!ctx || !out || slice_blocks == 0 || max_in_flight == 0) return TALLY_ERR_INVALID_ARG;
+  tally_job *j;
+  int rc = new_job(ctx, desc, KIND_SLICED, coverage, &j);
+  if (rc) return rc;
+  j->slice_blocks = slice_blocks;
+  j->max_in_flight = max_in_flight;
+  j->state = TALLY_JOB_RUNNING;
+  rc = sliced_issue(j);
+  if (rc) { tally_job_free(j); return rc; }
+  *out = j;
+  return TALLY_OK;
+}
+
+int tally_launch_ptb_until(tally_ctx *ctx, const tally_kernel_desc *desc, uint32_t num_workers,
+                           uint32_t chunk, uint64_t stop_at, int coverage, tally_job **out) {
+  if (!ctx || !out || num_workers == 0 || chunk == 0) return TALLY_ERR_INVALID_ARG;
+  if (num_workers > (1u << 20) || chunk > (1u << 16)) return TALLY_ERR_INVALID_ARG;
+  tally_job *j;
+  int rc = new_job(ctx, desc, KIND_PTB, coverage, &j);
+  if (rc) return rc;
+  j->workers = num_workers;
+  j->chunk = chunk;
+  rc = ptb_launch_segment(j, stop_at > j->total ? j->total : (uint32_t)stop_at);
+  if (rc) { tally_job_free(j); return rc; }
+  *out = j;
+  return TALLY_OK;
+}
+
+int tally_launch_ptb(tally_ctx *ctx, const tally_kernel_desc *desc, uint32_t num_workers,
+                     uint32_t chunk, int coverage, tally_job **out) {
+  return tally_launch_ptb_until(ctx, desc, num_workers, chunk, ~0ull, coverage, out);
+}
+
+int tally_preempt(tally_job *job) {
+  if (!job) return TALLY_ERR_INVALID_ARG;
+  if (job->state.load() != TALLY_JOB_RUNNING) return TALLY_OK;
+  if (job->t_preempt.load() == 0.0) job->t_preempt = now_us();
+  if (job->kind == KIND_PTB)
+    __atomic_store_n(job->h_flag(), job->epoch, __ATOMIC_RELEASE);
+  else if (job->kind == KIND_SLICED)
+    job->stop_issuing = true;
+  return TALLY_OK;
+}
+
+int tally_resume_until(tally_job *job, uint64_t stop_at) {
+  if (!job) return TALLY_ERR_INVALID_ARG;
+  refresh(job);
+  int st = job->state.load();
+  if (st == TALLY_JOB_COMPLETE) return TALLY_OK;
+  if (st != TALLY_JOB_STOPPED) return TALLY_ERR_BAD_STATE;
+  if (job->kind == KIND_PTB) {
+    if (stop_at < job->progress.load()) return TALLY_ERR_INVALID_ARG;
+    return ptb_launch_segment(job, stop_at > job->total ? job->total : (uint32_t)stop_at);
+  }
+  job->stop_issuing = false;
+  job->segment += 1;
+  job->t_preempt = 0.0;
+  job->state = TALLY_JOB_RUNNING;
+  return sliced_issue(job);
+}
+
+int tally_resume(tally_job *job) { return tally_resume_until(job, ~0ull); }
+
+int tally_progress(tally_job *job, uint64_t *done_blocks, uint64_t *total_blocks, int *state) {
+  if (!job) return TALLY_ERR_INVALID_ARG;
+  // read-only view: safe from any thread (the owning thread advances the state)
+  uint64_t p = job->progress.load();
+  int st = job->state.load();
+  if (st == TALLY_JOB_RUNNING && job->kind == KIND_PTB) {
+    uint32_t live = __atomic_load_n(job->h_live(), __ATOMIC_RELAXED);
+    if (live > p) p = live;
+  }
+  if (done_blocks) *done_blocks = p;
+  if (total_blocks) *total_blocks = job->total;
+  if (state) *state = st;
+  return TALLY_OK;
+}
+
+int tally_pump(tally_job *job) {
+  if (!job) return TALLY_ERR_INVALID_ARG;
+  refresh(job);
+  if (job->state.load() == TALLY_JOB_RUNNING && job->kind == KIND_SLICED) return sliced_issue(job);
+  return TALLY_OK;
+}
+
+int tally_wait(tally_job *job, int *state) {
+  if (!job) return TALLY_ERR_INVALID_ARG;
+  for (uint32_t spins = 1;; ++spins) {
+    int rc = tally_pump(job);
+    if (rc) return rc;
+    int st = job->state.load();
+    if (st == TALLY_JOB_STOPPED || st == TALLY_JOB_COMPLETE) break;
+    // a kernel that failed after enqueue would leave the status word unwritten for ever
+    if ((spins & 0xFFFFu) == 0) {
+      hipError_t q = hipStreamQuery(job->ctx->be);
+      if (q != hipSuccess && q != hipErrorNotReady) { g_last_hip = (int)q; return TALLY_ERR_HIP; }
+    }
+  }
+  HIPCHK(hipStreamSynchronize(job->ctx->be));
+  if (state) *state = job->state.load();
+  return TALLY_OK;
+}
+
+int tally_job_free(tally_job *job) {
+  if (!job) return TALLY_ERR_INVALID_ARG;
+  tally_ctx *ctx = job->ctx;
+  if (job->state.load() == TALLY_JOB_RUNNING) {
+    job->stop_issuing = true;
+    (void)hipStreamSynchronize(ctx->be);
+  }
+  if (job->cover) {
+    (void)hipStreamSynchronize(ctx->be);
+    (void)hipFree(job->cover);
+  }
+  ctx->slot_used[job->slot] = false;
+  ctx->live_jobs--;
+  delete job;
+  return TALLY_OK;
+}
+
+int tally_coverage(tally_job *job, void *host_records, size_t bytes) {
+  if (!job || !host_records || !job->cover) return TALLY_ERR_INVALID_ARG;
+  if (bytes != sizeof(tally_cover_rec) * (size_t)job->total) return TALLY_ERR_INVALID_ARG;
+  refresh(job);
+  if (job->state.load() == TALLY_JOB_RUNNING) return TALLY_ERR_BAD_STATE;
+  HIPCHK(hipStreamSynchronize(job->ctx->be));
+  HIPCHK(hipMemcpy(host_records, job->cover, bytes, hipMemcpyDeviceToHost));
+  return TALLY_OK;
+}
+
+int tally_marker(tally_ctx *ctx, int on_hi_stream, uint32_t value) {
+  if (!ctx) return TALLY_ERR_INVALID_ARG;
+  hipLaunchKernelGGL(marker_kernel, dim3(1), dim3(64), 0, on_hi_stream ? ctx->hi : ctx->be,
+                     ctx->marker_dev + (on_hi_stream ? 0 : 32), value);
+  HIPCHK(hipGetLastError());
+  return TALLY_OK;
+}
+
+int tally_marker_read(tally_ctx *ctx, int on_hi_stream, uint32_t *value) {
+  if (!ctx || !value) return TALLY_ERR_INVALID_ARG;
+  *value = __atomic_load_n(ctx->marker_host + (on_hi_stream ? 0 : 32), __ATOMIC_ACQUIRE);
+  return TALLY_OK;
+}
+
+int tally_last_preempt_latency_us(tally_job *job, double *us) {
+  if (!job || !us) return TALLY_ERR_INVALID_ARG;
+  *us = job->preempt_latency_us;
+  return TALLY_OK;
+}
+
+int tally_last_hip_error(void) { return g_last_hip; }
+
+const char *tally_strerror(int status) {
+  switch (status) {
+    case TALLY_OK: return "ok";
+    case TALLY_ERR_INVALID_ARG: return "invalid argument";
+    case TALLY_ERR_BAD_STATE: return "operation not valid in the job's current state";
+    case TALLY_ERR_HIP: return "HIP call failed";
+    case TALLY_ERR_NOMEM: return "out of memory or job slots";
+    case TALLY_ERR_UNSUPPORTED: return "kernel cannot be sliced or preempted";
+    default: return "unknown status";
+  }
+}
+
+int tally_device_info(uint32_t *num_cus, uint32_t *lds_bytes_per_cu, uint32_t *wave_size) {
+  int dev = 0;
+  hipDeviceProp_t prop;
+  HIPCHK(hipGetDevice(&dev));
+  HIPCHK(hipGetDeviceProperties(&prop, dev));
+  if (num_cus) *num_cus = (uint32_t)prop.multiProcessorCount;
+  if (lds_bytes_per_cu) *lds_bytes_per_cu = (uint32_t)prop.maxSharedMemoryPerMultiProcessor;
+  if (wave_size) *wave_size = (uint32_t)prop.warpSize;
+  return TALLY_OK;
+}
+
+// ------------------------------------------------------------------ configuration choice
+double tally_ptb_turnaround_ms(double kernel_latency_ms, uint32_t worker_blocks, uint32_t chunk,
+                               uint64_t total_blocks) {
+  if (total_blocks == 0) return 0.0;
+  return kernel_latency_ms * (double)worker_blocks * (double)(chunk ? chunk : 1) /
+         (double)total_blocks;
+}
+
+int tally_select_config(const tally_config *c, uint32_t n, double threshold_ms) {
+  if (!c || n == 0) return TALLY_ERR_INVALID_ARG;
+  // order of preference among equals: persistent workers first, then fewer workers,
+  // then larger slices
+  auto better_tie = [&](const tally_config &x, const tally_config &y) {
+    if (x.kind != y.kind) return x.kind < y.kind;
+    return x.kind == 0 ? x.param < y.param : x.param > y.param;
+  };
+  int best = -1;
+  for (uint32_t i = 0; i < n; ++i) {
+    if (c[i].turnaround_ms > threshold_ms) continue;
+    if (best < 0 || c[i].latency_ms < c[best].latency_ms ||
+        (c[i].latency_ms == c[best].latency_ms && better_tie(c[i], c[best])))
+      best = (int)i;
+  }
+  if (best >= 0) return best;
+  best = 0;
+  for (uint32_t i = 1; i < n; ++i)
+    if (c[i].turnaround_ms < c[best].turnaround_ms ||
+        (c[i].turnaround_ms == c[best].turnaround_ms && better_tie(c[i], c[best])))
+      best = (int)i;
+  return best;
+}
+
+int tally_profile(tally_ctx *ctx, const tally_kernel_desc *desc, tally_config *cands, uint32_t n,
+                  uint32_t runs, double threshold_ms, uint32_t *chosen) {
+  if (!ctx || !desc || !cands || n == 0 || runs == 0) return TALLY_ERR_INVALID_ARG;
+  const KernelOps *ops;
+  tally_dim3 g;
+  int rc = check_desc(desc, &ops, &g);
+  if (rc) return rc;
+  const uint64_t total = (uint64_t)g.x * g.y * g.z;
+  for (uint32_t i = 0; i < n; ++i) {
+    if (cands[i].kind > 1 || cands[i].param == 0) return TALLY_ERR_INVALID_ARG;
+    double sum = 0.0;
+    for (uint32_t r = 0; r <= runs; ++r) {  // run 0 is the warm-up
+      tally_be_item it = {desc, cands[i]};
+      tally_job *j;
+      HIPCHK(hipStreamSynchronize(ctx->be));
+      double t0 = now_us();
+      rc = launch_be_item(ctx, &it, &j);
+      if (rc) return rc;
+      int st;
+      rc = tally_wait(j, &st);
+      double t1 = now_us();
+      tally_job_free(j);
+      if (rc) return rc;
+      if (r > 0) sum += t1 - t0;
+    }
+    cands[i].latency_ms = (float)(sum / runs / 1000.0);
+    if (cands[i].kind == 0) {
+      cands[i].turnaround_ms = (float)tally_ptb_turnaround_ms(
+          cands[i].latency_ms, cands[i].param, cands[i].chunk ? cands[i].chunk : 1, total);
+    } else {
+      uint64_t slices = (total + cands[i].param - 1) / cands[i].param;
+      cands[i].turnaround_ms = (float)(cands[i].latency_ms / (double)slices);
+    }
+  }
+  int pick = tally_select_config(cands, n, threshold_ms);
+  if (pick < 0) return pick;
+  ctx->chosen[std::make_tuple(desc->kernel_id, g.x, g.y, g.z, desc->block.x)] = cands[pick];
+  if (chosen) *chosen = (uint32_t)pick;
+  return TALLY_OK;
+}
+
+int tally_lookup_config(tally_ctx *ctx, const tally_kernel_desc *desc, tally_config *out) {
+  if (!ctx || !desc || !out) return TALLY_ERR_INVALID_ARG;
+  auto it = ctx->chosen.find(
+      std::make_tuple(desc->kernel_id, desc->grid.x, desc->grid.y, desc->grid.z, desc->block.x));
+  if (it == ctx->chosen.end()) return TALLY_ERR_BAD_STATE;
+  *out = it->second;
+  return TALLY_OK;
+}
+
+}  // extern "C"
+
+namespace {
+
+int launch_be_item(tally_ctx *ctx, const tally_be_item *it, tally_job **out) {
+  const tally_config &c = it->config;
+  if (c.kind == 0) return tally_launch_ptb(ctx, it->kernel, c.param, c.chunk ? c.chunk : 1, 0, out);
+  if (c.kind == 1) return tally_launch_sliced(ctx, it->kernel, c.param, 1, 0, out);
+  if (c.kind != 2) return TALLY_ERR_INVALID_ARG;
+  tally_job *j;
+  int rc = new_job(ctx, it->kernel, KIND_NATIVE, 0, &j);
+  if (rc) return rc;
+  j->state = TALLY_JOB_RUNNING;
+  hipError_t e = j->ops->native(ctx->be, j->args, j->grid);
+  if (e == hipSuccess) {
+    hipLaunchKernelGGL(marker_kernel, dim3(1), dim3(64), 0, ctx->be,
+                       (uint32_t *)(j->h_base_dev() + 128), 1u);
+    e = hipGetLastError();
+  }
+  if (e != hipSuccess) {
+    g_last_hip = (int)e;
+    tally_job_free(j);
+    return TALLY_ERR_HIP;
+  }
+  *out = j;
+  return TALLY_OK;
+}
+
+}  // namespace
+
+// --------------------------------------------------------------- priority scheduling loop
+extern "C" int tally_sched_run(tally_ctx *ctx, tally_sched_run_t *run) {
+  if (!ctx || !run) return TALLY_ERR_INVALID_ARG;
+  if (run->n_arrivals && (!run->arrivals_us || !run->latency_us || !run->hi_kernels ||
+                          !run->n_hi_kernels))
+    return TALLY_ERR_INVALID_ARG;
+  if (run->n_be_items && !run->be_items) return TALLY_ERR_INVALID_ARG;
+  if (run->policy > 2) return TALLY_ERR_INVALID_ARG;
+  // validate every descriptor before anything is launched
+  for (uint32_t i = 0; i < run->n_hi_kernels && run->n_arrivals; ++i) {
+    const KernelOps *ops;
+    tally_dim3 g;
+    int rc = check_desc(&run->hi_kernels[i], &ops, &g);
+    if (rc) return rc;
+  }
+  HIPCHK(hipStreamSynchronize(ctx->hi));
+  HIPCHK(hipStreamSynchronize(ctx->be));
+
+  uint32_t hi_seq = 0;
+  (void)tally_marker_read(ctx, 1, &hi_seq);
+  uint32_t next_arrival = 0, cur = 0, completed = 0;
+  bool hi_inflight = false;
+  tally_job *be = nullptr;
+  uint32_t be_idx = 0;
+  bool be_preempt_pending = false;
+  run->n_preempts = 0;
+  run->be_kernels_done = 0;
+  run->be_steps_done = 0;
+  const double last_arrival = run->n_arrivals ? run->arrivals_us[run->n_arrivals - 1] : 0.0;
+  const double t_end = last_arrival + run->tail_us;
+  int rc = TALLY_OK;
+  const double t0 = now_us();
+
+  for (;;) {
+    double now = now_us() - t0;
+    // ---- high-priority client ---------------------------------------------------------
+    if (hi_inflight) {
+      uint32_t seen;
+      (void)tally_marker_read(ctx, 1, &seen);
+      if (seen == hi_seq) {
+        run->latency_us[cur] = (now_us() - t0) - run->arrivals_us[cur];
+        hi_inflight = false;
+        completed++;
+      }
+    }
+    if (!hi_inflight && next_arrival < run->n_arrivals && run->arrivals_us[next_arrival] <= now) {
+      cur = next_arrival++;
+      if (run->policy == 0 && be && be->state.load() == TALLY_JOB_RUNNING) {
+        (void)tally_preempt(be);
+        be_preempt_pending = true;
+      }
+      for (uint32_t i = 0; i < run->n_hi_kernels && rc == TALLY_OK; ++i)
+        rc = tally_launch_native(ctx, &run->hi_kernels[i], 1);
+      if (rc == TALLY_OK) rc = tally_marker(ctx, 1, ++hi_seq);
+      if (rc) break;
+      hi_inflight = true;
+    }
+    // ---- best-effort client -----------------------------------------------------------
+    if (be) {
+      refresh(be);
+      int st = be->state.load();
+      if (be_preempt_pending && st != TALLY_JOB_RUNNING) {
+        if (st == TALLY_JOB_STOPPED && be->preempt_latency_us >= 0.0) {
+          if (run->preempt_latency_us && run->n_preempts < run->preempt_cap)
+            run->preempt_latency_us[run->n_preempts] = be->preempt_latency_us;
+          run->n_preempts++;
+        }
+        be_preempt_pending = false;
+      }
+      if (st == TALLY_JOB_COMPLETE) {
+        tally_job_free(be);
+        be = nullptr;
+        run->be_kernels_done++;
+        if (++be_idx == run->n_be_items) { be_idx = 0; run->be_steps_done++; }
+      }
+    }
+    const bool window_open = (now < t_end) || completed < run->n_arrivals || hi_inflight;
+    if (!window_open && !be) break;
+    if (hi_inflight && run->policy != 2) continue;  // best-effort clients are not visited
+    if (be) {
+      int st = be->state.load();
+      if (st == TALLY_JOB_STOPPED) {
+        if (window_open) rc = tally_resume(be);
+        else { tally_job_free(be); be = nullptr; }
+      } else if (st == TALLY_JOB_RUNNING && be->kind == KIND_SLICED) {
+        if (!window_open) (void)tally_preempt(be);
+        rc = sliced_issue(be);
+      } else if (st == TALLY_JOB_RUNNING && !window_open && be->kind == KIND_PTB) {
+        (void)tally_preempt(be);
+      }
+      if (rc) break;
+    } else if (run->n_be_items && window_open && now < t_end) {
+      rc = launch_be_item(ctx, &run->be_items[be_idx], &be);
+      if (rc) break;
+    } else if (!run->n_be_items && !window_open) {
+      break;
+    }
+  }
+  run->window_us = now_us() - t0;
+  if (be) tally_job_free(be);
+  (void)hipStreamSynchronize(ctx->hi);
+  (void)hipStreamSynchronize(ctx->be);
+  return rc;
+}

@@ -1,0 +1,192 @@
+"""GPU parity of the workload kernels (GEMM, GEMV, softmax, LayerNorm, decode attention) in
+their native and transformed forms against the CPU oracle, element by element, and on
+sampled tiles at the full benchmark sizes."""
+import numpy as np
+import pytest
+
+import tally_inputs as TI
+from oracle import kernels as OK
+from oracle import schedules as OS
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def env():
+    import torch
+    import paper_2410_07381_amd.binding as B
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    hi, be = torch.cuda.Stream(), torch.cuda.Stream()
+    ctx = B.Context(hi, be)
+    yield B, ctx, torch
+    ctx.close()
+
+
+def _run_form(B, ctx, torch, kernel, form):
+    if form == "native":
+        ctx.launch_native(kernel)
+    elif form == "native_hi":
+        ctx.launch_native(kernel, hi=True)
+    else:
+        if form == "sliced":
+            job = ctx.launch_sliced(kernel, 3)
+        elif form == "ptb":
+            job = ctx.launch_ptb(kernel, 5)
+        else:                                             # preempted half way, then resumed
+            job = ctx.launch_ptb(kernel, 3, chunk=2, stop_at=max(1, kernel.total_blocks // 2))
+            job.wait()
+            job.resume()
+        assert job.wait() == B.JOB_COMPLETE
+        job.free()
+    torch.cuda.synchronize()
+
+
+FORMS = ["native", "sliced", "ptb", "ptb_preempted"]
+
+
+# ------------------------------------------------------------------ GEMM, 256-wide tiles
+@pytest.mark.parametrize("form", FORMS)
+def test_gemm_bf16_forms(env, form):
+    B, ctx, torch = env
+    from gpu_util import dev, host, assert_bf16_close
+    m, n, k, batch = 512, 768, 320, 2                    # 3 x 2 x 2 tiles, 5 k-steps
+    g = TI.gemm_inputs(m, n, k, config_index=1, batch=batch)
+    a = dict(g, C=np.zeros((batch, m, n), np.uint16))
+    OS.run_native("gemm_bf16", OK.grid_of("gemm_bf16", a), a)
+    A, Bt, Cd = dev(g["A"]), dev(g["Bt"]), dev(np.zeros((batch, m, n), np.uint16))
+    torch.cuda.synchronize()
+    kern = B.gemm_bf16(A, Bt, Cd)
+    assert kern.grid == (3, 2, 2)
+    _run_form(B, ctx, torch, kern, form)
+    assert_bf16_close(host(Cd), a["C"])
+
+
+def test_gemm_identity_is_exact(env):
+    B, ctx, torch = env
+    from gpu_util import dev, host
+    eye = TI.to_bf16_bits(np.eye(256, dtype=np.float32))[None]
+    Bt = TI.normal_bf16(np.random.default_rng(5), (1, 512, 256), 1 / 64)
+    A, Btd, Cd = dev(eye), dev(Bt), dev(np.zeros((1, 256, 512), np.uint16))
+    torch.cuda.synchronize()
+    ctx.launch_native(B.gemm_bf16(A, Btd, Cd))
+    torch.cuda.synchronize()
+    assert (host(Cd)[0] == Bt[0].T).all()                # I . B = B bit for bit
+
+
+def test_gemm_cfg1_full_size_sampled_tiles(env):
+    """M = N = K = 4096 in persistent-worker form with 256 workers (the benchmark's launch
+    configuration); the oracle recomputes a seeded sample of whole 256x256 tiles."""
+    B, ctx, torch = env
+    from gpu_util import dev, host, assert_bf16_close
+    g = TI.gemm_inputs(4096, 4096, 4096, config_index=1)
+    A, Bt = dev(g["A"]), dev(g["Bt"])
+    Cd = torch.zeros((1, 4096, 4096), dtype=torch.int16, device="cuda")
+    torch.cuda.synchronize()
+    kern = B.gemm_bf16(A, Bt, Cd)
+    assert kern.grid == (16, 16, 1)
+    job = ctx.launch_ptb(kern, 256, coverage=True)
+    assert job.wait() == B.JOB_COMPLETE
+    rec = job.coverage()
+    job.free()
+    assert (rec["count"] == 1).all()
+    idx = np.arange(256)
+    assert (rec["bx"] == idx % 16).all() and (rec["by"] == idx // 16).all()
+    got = host(Cd)
+    rng = np.random.default_rng(11)
+    for t in [0, 255] + [int(v) for v in rng.integers(1, 255, 3)]:
+        bx, by = t % 16, t // 16
+        a = dict(g, C=np.zeros((1, 4096, 4096), np.uint16))
+        OK.exec_block("gemm_bf16", (bx, by, 0), (16, 16, 1), a)
+        r, c = slice(by * 256, by * 256 + 256), slice(bx * 256, bx * 256 + 256)
+        assert_bf16_close(got[0, r, c], a["C"][0, r, c])
+    # all-ones / 64: every output is exactly 1 (property that holds at any size)
+    ones = TI.to_bf16_bits(np.full((1, 4096, 4096), 1 / 64, np.float32))
+    A1 = dev(ones)
+    torch.cuda.synchronize()
+    ctx.launch_native(B.gemm_bf16(A1, A1, Cd))
+    torch.cuda.synchronize()
+    assert (host(Cd) == 0x3F80).all()
+
+
+# ------------------------------------------------------------------ GEMM, 64-wide ragged tiles
+@pytest.mark.parametrize("form", FORMS)
+def test_gemm_small_forms(env, form):
+    B, ctx, torch = env
+    from gpu_util import dev, host, assert_bf16_close
+    m, n, k, batch = 300, 520, 96, 2
+    g = TI.gemm_inputs(m, n, k, config_index=3, batch=batch)
+    a = dict(g, C=np.zeros((batch, m, n), np.uint16))
+    OS.run_native("gemm_bf16_small", OK.grid_of("gemm_bf16_small", a), a)
+    A, Bt, Cd = dev(g["A"]), dev(g["Bt"]), dev(np.zeros((batch, m, n), np.uint16))
+    torch.cuda.synchronize()
+    _run_form(B, ctx, torch, B.gemm_bf16(A, Bt, Cd, small=True), form)
+    assert_bf16_close(host(Cd), a["C"])
+
+
+# ------------------------------------------------------------------ GEMV
+@pytest.mark.parametrize("n,k,form", [(130, 96, "native"), (130, 96, "ptb_preempted"),
+                                      (4096, 4096, "native_hi"), (4096, 11008, "native_hi"),
+                                      (11008, 4096, "native_hi"), (1000, 2056, "sliced")])
+def test_gemv(env, n, k, form):
+    B, ctx, torch = env
+    from gpu_util import dev, host, assert_bf16_close
+    g = TI.gemv_inputs(n=n, k=k, scale=1 / 64 if k == 4096 and n == 4096 else 0.02, config_index=1)
+    a = dict(g, y=np.zeros(n, np.uint16))
+    OS.run_native("gemv_bf16", OK.grid_of("gemv_bf16", a), a)
+    x, W, y = dev(g["x"]), dev(g["W"]), dev(np.zeros(n, np.uint16))
+    torch.cuda.synchronize()
+    _run_form(B, ctx, torch, B.gemv_bf16(x, W, y), form)
+    assert_bf16_close(host(y), a["y"])
+
+
+# ------------------------------------------------------------------ softmax / LayerNorm
+@pytest.mark.parametrize("rows,cols,form", [(37, 2048, "native"), (37, 2048, "ptb_preempted"),
+                                            (37, 2048, "sliced"), (1536, 128, "native_hi"),
+                                            (9, 8192, "ptb"), (5, 100, "native"),
+                                            (3, 4096, "native")])
+def test_softmax(env, rows, cols, form):
+    B, ctx, torch = env
+    from gpu_util import dev, host, assert_close_rel
+    xs = TI.rows_f32(rows, cols, scale=2.0, config_index=3)
+    xs[0, :] = 0.25                                       # constant row
+    xs[rows - 1, 0] = 60.0                                # one dominant entry
+    a = {"x": xs, "y": np.zeros_like(xs), "rows": rows, "cols": cols}
+    OS.run_native("softmax_f32", OK.grid_of("softmax_f32", a), a)
+    x, y = dev(xs), dev(np.zeros_like(xs))
+    torch.cuda.synchronize()
+    _run_form(B, ctx, torch, B.softmax_f32(x, y), form)
+    got = host(y)
+    assert_close_rel(got, a["y"], 1e-5, 1e-7)
+    assert np.allclose(got.sum(axis=1, dtype=np.float64), 1.0, atol=1e-5)
+
+
+@pytest.mark.parametrize("rows,cols,form", [(41, 4096, "native"), (41, 4096, "ptb_preempted"),
+                                            (41, 4096, "sliced"), (128, 768, "native_hi"),
+                                            (6, 8192, "ptb"), (5, 100, "native")])
+def test_layernorm(env, rows, cols, form):
+    B, ctx, torch = env
+    from gpu_util import dev, host, assert_close_rel
+    li = TI.layernorm_inputs(rows, cols, scale=1.0)
+    a = dict(li, y=np.zeros_like(li["x"]))
+    OS.run_native("layernorm_f32", OK.grid_of("layernorm_f32", a), a)
+    x, g, b, y = dev(li["x"]), dev(li["gamma"]), dev(li["beta"]), dev(np.zeros_like(li["x"]))
+    torch.cuda.synchronize()
+    _run_form(B, ctx, torch, B.layernorm_f32(x, g, b, y, li["eps"]), form)
+    assert_close_rel(host(y), a["y"], 1e-5, 2e-6)
+
+
+# ------------------------------------------------------------------ decode attention
+@pytest.mark.parametrize("tokens,heads,scale", [(2048, 32, 0.02), (777, 3, 1.0), (5, 2, 1.0)])
+def test_attn_decode(env, tokens, heads, scale):
+    B, ctx, torch = env
+    from gpu_util import dev, host, assert_bf16_close
+    at = TI.attn_decode_inputs(tokens, heads, 128, scale=scale)
+    a = dict(at, out=np.zeros((heads, 128), np.uint16))
+    OS.run_native("attn_decode_bf16", OK.grid_of("attn_decode_bf16", a), a)
+    q, Kc, Vc = dev(at["q"]), dev(at["K"]), dev(at["V"])
+    out = dev(np.zeros((heads, 128), np.uint16))
+    scratch = torch.zeros(B.attn_decode_scratch_bytes(heads), dtype=torch.uint8, device="cuda")
+    torch.cuda.synchronize()
+    ctx.launch_native(B.attn_decode_bf16(q, Kc, Vc, out, scratch), hi=True)
+    torch.cuda.synchronize()
+    assert_bf16_close(host(out), a["out"])

@@ -77,14 +77,15 @@ def test_slice_remainder_and_resume_offsets():
 
 
 # ------------------------------------------------------------------ brute force
-def _explore(total, workers, order, max_preempts):
+def _explore(total, workers, order, max_preempts, chunk=1):
     """Walk EVERY interleaving of worker micro-steps and EVERY moment at which the flag
     may be raised (up to max_preempts times).  Returns a dict of findings."""
     found = {"lost": False, "dup": False, "prefix_broken": False, "finals": 0, "max_depth": 0}
     seen = set()
 
     def key(m, counts, used):
-        return (m.counter, m.flag, tuple(m.state), tuple(m.held), counts, used, m.segment)
+        return (m.counter, m.flag, tuple(m.state), tuple(m.held), tuple(m.held_end), counts, used,
+                m.segment)
 
     def rec(m, counts, used, depth):
         k = key(m, counts, used)
@@ -124,7 +125,7 @@ def _explore(total, workers, order, max_preempts):
             m2.on_exec = None
             rec(m2, c2, used, depth + 1)
 
-    rec(S.PtbMachine(total, workers, order=order), (0,) * total, 0, 0)
+    rec(S.PtbMachine(total, workers, order=order, chunk=chunk), (0,) * total, 0, 0)
     found["states"] = len(seen)
     return found
 
@@ -134,6 +135,23 @@ def test_exactly_once_under_every_interleaving_and_preemption_point(total, worke
     f = _explore(total, workers, "check_then_fetch", max_preempts=2)
     assert f["finals"] > 0
     assert not f["lost"] and not f["dup"] and not f["prefix_broken"]
+
+
+@pytest.mark.parametrize("total,workers,chunk", [(5, 2, 2), (6, 3, 2), (7, 2, 3), (3, 2, 4)])
+def test_exactly_once_with_chunked_fetch(total, workers, chunk):
+    # taking several consecutive task indices per fetch keeps exactly-once and the prefix
+    # property as long as every fetched index is run before the worker leaves
+    f = _explore(total, workers, "check_then_fetch", max_preempts=2, chunk=chunk)
+    assert f["finals"] > 0
+    assert not f["lost"] and not f["dup"] and not f["prefix_broken"]
+
+
+def test_chunked_fetch_drains_on_a_chunk_boundary():
+    cov, log = S.run_ptb(None, (37, 1, 1), {}, 3, preempt_points=[5, 18], seed=2, chunk=4)
+    assert cov.exactly_once()
+    assert log == [8, 20, 37]
+    assert (cov.segment[:8] == 0).all() and (cov.segment[8:20] == 1).all()
+    assert (cov.segment[20:] == 2).all()
 
 
 def test_brute_force_detects_the_wrong_order():
@@ -148,6 +166,7 @@ def test_brute_force_detects_the_wrong_order():
     ((6, 5, 2), 7, [1, 59]),
     ((33, 1, 1), 64, [10]),           # more workers than blocks
     ((16, 1, 1), 4, [0]),             # preempted before the first fetch: empty segment
+    ((16, 1, 1), 3, [6, 6, 9]),       # flag seen again before any new fetch: empty segment
 ])
 def test_seeded_ptb_runs(grid, workers, pts):
     total = G.total_blocks(grid)
