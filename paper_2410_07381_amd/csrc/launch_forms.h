@@ -27,11 +27,13 @@ struct PtbCtl {
   const uint32_t *host_flag;  // pinned host memory: epoch the host wants preempted
   unsigned long long *host_status;  // pinned: (epoch << 32 | progress) once drained
   uint32_t *host_live;      // pinned: progress mirrored while running
+  uint32_t *host_raw;       // pinned: raw counter value at the drain (written before status)
   tally_cover_rec *cover;   // device, may be null
   uint32_t total;           // logical blocks in the grid
   uint32_t limit;           // workers treat this as the end of the grid (== total normally)
-  uint32_t epoch;           // id of this launch segment (1, 2, ...)
+  uint32_t epoch;           // id of this launch segment, unique for the life of the slot
   uint32_t exit_target;     // value of *exited after the last worker of this segment leaves
+  uint32_t counter_base;    // raw counter value that stands for task index 0 of this job
   uint32_t workers;
   uint32_t chunk;           // task indices per fetch
   uint32_t segment;         // 0-based segment number, for the coverage records
@@ -69,22 +71,31 @@ __global__ __launch_bounds__(Body::THREADS) void native_kernel(typename Body::Ar
   Body::run(args, blockIdx.x, blockIdx.y, blockIdx.z);
 }
 
+
+
 // ---- sliced form: logical block = offset + blockIdx (Section 4.1, slicing) -----------
 template <class Body>
-__global__ __launch_bounds__(Body::THREADS) void sliced_kernel(typename Body::Args args,
-                                                               SliceCtl ctl) {
+__device__ __forceinline__ void sliced_body(const typename Body::Args &args, const SliceCtl &ctl) {
   uint32_t idx = ctl.offset + blockIdx.x, bx, by, bz;
   delinearize(idx, ctl.gx, ctl.gy, bx, by, bz);
   Body::run(args, bx, by, bz);
   record(ctl.cover, idx, bx, by, bz, ctl.segment, blockIdx.x);
 }
+template <class Body>
+__global__ __launch_bounds__(Body::THREADS) void sliced_kernel(typename Body::Args args,
+                                                               SliceCtl ctl) {
+  sliced_body<Body>(args, ctl);
+}
 
 // ---- persistent-worker form (Section 4.1, preemption) --------------------------------
-// Workgroup 0 is not a worker: one lane of it relays the host's preemption request from
-// pinned host memory (cheap for the host to write, slow to poll) into a device-memory
-// flag (cheap for hundreds of workers to poll), and mirrors progress back to the host.
-// It leaves as soon as the request is relayed or every worker has exited.
-__device__ __forceinline__ void relay_loop(const PtbCtl &c) {
+// The host raises the flag with one store to pinned host memory (cheap to write, but a
+// load from it crosses PCIe, far too slow for hundreds of workers to poll every
+// iteration).  A one-wave relay kernel, launched beside the workers on a stream of its
+// own, polls that word, copies a request into a device-memory flag the workers can poll
+// cheaply, and mirrors the progress back to the host.  It leaves as soon as the request
+// is relayed or every worker of the segment has exited, so its lifetime is bounded by
+// the workers', which depend on nothing.
+__global__ __launch_bounds__(64) void relay_kernel(PtbCtl c) {
   if (threadIdx.x != 0) return;
   for (;;) {
     uint32_t want = __hip_atomic_load(c.host_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
@@ -92,29 +103,28 @@ __device__ __forceinline__ void relay_loop(const PtbCtl &c) {
       __hip_atomic_store(c.dev_flag, c.epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       return;
     }
+    // the counters of a slot only ever grow (they are never reset), so a relay that
+    // starts late, even after its workers are long gone, still sees the target passed
     uint32_t gone = __hip_atomic_load(c.exited, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if (gone == c.exit_target) return;
-    uint32_t ctr = __hip_atomic_load(c.counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if ((int32_t)(gone - c.exit_target) >= 0) return;
+    uint32_t ctr = __hip_atomic_load(c.counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) -
+                   c.counter_base;
     __hip_atomic_store(c.host_live, ctr < c.limit ? ctr : c.limit, __ATOMIC_RELAXED,
                        __HIP_MEMORY_SCOPE_SYSTEM);
   }
 }
 
 template <class Body>
-__global__ __launch_bounds__(Body::THREADS) void ptb_kernel(typename Body::Args args, PtbCtl c) {
-  if (blockIdx.x == 0) {
-    relay_loop(c);
-    return;
-  }
+__device__ __forceinline__ void ptb_body(const typename Body::Args &args, const PtbCtl &c) {
   __shared__ uint32_t s_idx;
-  const uint32_t worker = blockIdx.x - 1;
+  const uint32_t worker = blockIdx.x;
   for (;;) {
     // start of an iteration: check the flag, THEN fetch; a fetched index is always run
     if (threadIdx.x == 0) {
       uint32_t f = __hip_atomic_load(c.dev_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       s_idx = (f == c.epoch) ? kStop
                              : __hip_atomic_fetch_add(c.counter, c.chunk, __ATOMIC_RELAXED,
-                                                      __HIP_MEMORY_SCOPE_AGENT);
+                                                      __HIP_MEMORY_SCOPE_AGENT) - c.counter_base;
     }
     __syncthreads();
     const uint32_t first = s_idx;
@@ -132,13 +142,19 @@ __global__ __launch_bounds__(Body::THREADS) void ptb_kernel(typename Body::Args 
   if (threadIdx.x == 0) {
     uint32_t old = __hip_atomic_fetch_add(c.exited, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
     if (old + 1 == c.exit_target) {
-      uint32_t ctr = __hip_atomic_load(c.counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      uint32_t raw = __hip_atomic_load(c.counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      uint32_t ctr = raw - c.counter_base;
       uint32_t progress = ctr < c.limit ? ctr : c.limit;
+      __hip_atomic_store(c.host_raw, raw, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
       __hip_atomic_store(c.host_live, progress, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
       __hip_atomic_store(c.host_status, ((unsigned long long)c.epoch << 32) | progress,
                          __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
     }
   }
+}
+template <class Body>
+__global__ __launch_bounds__(Body::THREADS) void ptb_kernel(typename Body::Args args, PtbCtl c) {
+  ptb_body<Body>(args, c);
 }
 
 // Marker: stores a value into a pinned host word once earlier work on the stream is done.

@@ -77,7 +77,7 @@ template <class Body>
 hipError_t launch_ptb_t(hipStream_t s, const void *args, const PtbCtl &c) {
   typename Body::Args a;
   memcpy(&a, args, sizeof(a));
-  hipLaunchKernelGGL(ptb_kernel<Body>, dim3(c.workers + 1), dim3(Body::THREADS), Body::DYN_LDS, s,
+  hipLaunchKernelGGL(ptb_kernel<Body>, dim3(c.workers), dim3(Body::THREADS), Body::DYN_LDS, s,
                      a, c);
   return hipGetLastError();
 }
@@ -221,11 +221,14 @@ enum JobKind { KIND_PTB = 0, KIND_SLICED = 1, KIND_NATIVE = 2 };
 
 struct tally_ctx {
   hipStream_t hi, be;
+  hipStream_t ctl;           // owned: carries the relay kernels, default priority
   unsigned char *dev_pool;   // device
   unsigned char *host_pool;  // pinned host
   unsigned char *host_pool_dev;
   bool slot_used[kSlots];
   int next_slot;
+  // device words of a slot are never reset: the host tracks their current values instead
+  uint32_t slot_counter[kSlots], slot_exited[kSlots], slot_epoch[kSlots];
   uint32_t *marker_host;     // pinned: [0] hi, [32] be (separate lines)
   uint32_t *marker_dev;
   uint32_t num_cus;
@@ -246,6 +249,8 @@ struct tally_job {
   std::atomic<uint32_t> progress;
   // persistent workers
   uint32_t workers, chunk, epoch, limit;
+  uint32_t counter_base;     // raw counter value standing for task index 0
+  uint32_t segments;         // launch segments so far
   bool counter_dirty;        // counter overshot a stop_at limit and must be rewound
   // sliced
   uint32_t slice_blocks, max_in_flight, next_off, issued, retired, segment;
@@ -262,6 +267,7 @@ struct tally_job {
   uint32_t *h_flag() { return (uint32_t *)h_base(); }
   unsigned long long *h_status() { return (unsigned long long *)(h_base() + 64); }
   uint32_t *h_live() { return (uint32_t *)(h_base() + 72); }
+  uint32_t *h_raw() { return (uint32_t *)(h_base() + 76); }
   uint32_t *h_slice_done() { return (uint32_t *)(h_base() + 128); }
 };
 
@@ -309,15 +315,16 @@ int new_job(tally_ctx *ctx, const tally_kernel_desc *desc, int kind, int coverag
   j->cover = nullptr;
   j->state = TALLY_JOB_QUEUED;
   j->progress = 0;
-  j->workers = j->chunk = j->epoch = 0;
+  j->workers = j->chunk = j->epoch = j->segments = 0;
+  j->counter_base = ctx->slot_counter[slot];
   j->limit = j->total;
   j->counter_dirty = false;
   j->slice_blocks = j->max_in_flight = j->next_off = j->issued = j->retired = j->segment = 0;
   j->stop_issuing = false;
   j->t_preempt = 0.0;
   j->preempt_latency_us = -1.0;
-  hipError_t e = hipMemsetAsync(ctx->dev_pool + slot * kDevSlotBytes, 0, kDevSlotBytes, ctx->be);
-  if (e == hipSuccess && coverage) {
+  hipError_t e = hipSuccess;
+  if (coverage) {
     e = hipMalloc((void **)&j->cover, sizeof(tally_cover_rec) * (size_t)j->total);
     if (e == hipSuccess)
       e = hipMemsetAsync(j->cover, 0, sizeof(tally_cover_rec) * (size_t)j->total, ctx->be);
@@ -337,13 +344,15 @@ int new_job(tally_ctx *ctx, const tally_kernel_desc *desc, int kind, int coverag
 
 int ptb_launch_segment(tally_job *j, uint32_t limit) {
   tally_ctx *ctx = j->ctx;
+  const int slot = j->slot;
   if (j->counter_dirty) {
-    hipLaunchKernelGGL(set_word_kernel, dim3(1), dim3(64), 0, ctx->be, j->d_counter(),
-                       j->progress.load());
+    uint32_t raw = j->counter_base + j->progress.load();
+    hipLaunchKernelGGL(set_word_kernel, dim3(1), dim3(64), 0, ctx->be, j->d_counter(), raw);
     HIPCHK(hipGetLastError());
+    ctx->slot_counter[slot] = raw;
     j->counter_dirty = false;
   }
-  j->epoch += 1;
+  j->epoch = ctx->slot_epoch[slot] + 1;
   j->limit = limit < j->total ? limit : j->total;
   PtbCtl c;
   c.counter = j->d_counter();
@@ -352,19 +361,36 @@ int ptb_launch_segment(tally_job *j, uint32_t limit) {
   c.host_flag = (const uint32_t *)j->h_base_dev();
   c.host_status = (unsigned long long *)(j->h_base_dev() + 64);
   c.host_live = (uint32_t *)(j->h_base_dev() + 72);
+  c.host_raw = (uint32_t *)(j->h_base_dev() + 76);
   c.cover = j->cover;
   c.total = j->total;
   c.limit = j->limit;
   c.epoch = j->epoch;
-  c.exit_target = j->workers * j->epoch;
+  c.exit_target = ctx->slot_exited[slot] + j->workers;
+  c.counter_base = j->counter_base;
   c.workers = j->workers;
   c.chunk = j->chunk;
-  c.segment = j->epoch - 1;
+  c.segment = j->segments;
   c.gx = j->grid.x;
   c.gy = j->grid.y;
+  hipError_t e = j->ops->ptb(ctx->be, j->args, c);
+  if (e != hipSuccess) {  // nothing was enqueued: the slot's bookkeeping is unchanged
+    g_last_hip = (int)e;
+    return TALLY_ERR_HIP;
+  }
+  ctx->slot_epoch[slot] = j->epoch;
+  ctx->slot_exited[slot] = c.exit_target;
+  j->segments += 1;
   j->t_preempt = 0.0;
   j->state = TALLY_JOB_RUNNING;
-  HIPCHK(j->ops->ptb(ctx->be, j->args, c));
+  // the relay runs beside the workers on its own stream and ends with them; without it
+  // the job still completes but cannot be preempted
+  hipLaunchKernelGGL(relay_kernel, dim3(1), dim3(64), 0, ctx->ctl, c);
+  e = hipGetLastError();
+  if (e != hipSuccess) {
+    g_last_hip = (int)e;
+    return TALLY_ERR_HIP;
+  }
   return TALLY_OK;
 }
 
@@ -398,6 +424,7 @@ void refresh(tally_job *j) {
     if ((uint32_t)(st >> 32) == j->epoch) {
       uint32_t p = (uint32_t)st;
       j->progress = p;
+      j->ctx->slot_counter[j->slot] = __atomic_load_n(j->h_raw(), __ATOMIC_RELAXED);
       double tp = j->t_preempt.load();
       j->preempt_latency_us = (tp > 0.0 && p < j->total) ? now_us() - tp : -1.0;
       if (j->limit < j->total) j->counter_dirty = true;
@@ -439,16 +466,21 @@ int tally_create(tally_ctx **out, void *hip_stream_hi, void *hip_stream_be) {
   if (!c) return TALLY_ERR_NOMEM;
   c->hi = (hipStream_t)hip_stream_hi;
   c->be = (hipStream_t)hip_stream_be;
+  c->ctl = nullptr;
   c->dev_pool = nullptr;
   c->host_pool = nullptr;
   c->marker_host = nullptr;
   memset(c->slot_used, 0, sizeof(c->slot_used));
+  memset(c->slot_counter, 0, sizeof(c->slot_counter));
+  memset(c->slot_exited, 0, sizeof(c->slot_exited));
+  memset(c->slot_epoch, 0, sizeof(c->slot_epoch));
   c->live_jobs = 0;
   c->next_slot = 0;
   hipError_t e;
   int dev = 0;
   hipDeviceProp_t prop;
   if ((e = hipGetDevice(&dev)) != hipSuccess || (e = hipGetDeviceProperties(&prop, dev)) != hipSuccess ||
+      (e = hipStreamCreateWithFlags(&c->ctl, hipStreamNonBlocking)) != hipSuccess ||
       (e = hipMalloc((void **)&c->dev_pool, kSlots * kDevSlotBytes)) != hipSuccess ||
       (e = hipMemset(c->dev_pool, 0, kSlots * kDevSlotBytes)) != hipSuccess ||
       (e = hipHostMalloc((void **)&c->host_pool, kSlots * kHostSlotBytes, hipHostMallocDefault)) != hipSuccess ||
@@ -456,6 +488,7 @@ int tally_create(tally_ctx **out, void *hip_stream_hi, void *hip_stream_be) {
       (e = hipHostMalloc((void **)&c->marker_host, 256, hipHostMallocDefault)) != hipSuccess ||
       (e = hipHostGetDevicePointer((void **)&c->marker_dev, c->marker_host, 0)) != hipSuccess) {
     g_last_hip = (int)e;
+    if (c->ctl) (void)hipStreamDestroy(c->ctl);
     if (c->dev_pool) (void)hipFree(c->dev_pool);
     if (c->host_pool) (void)hipHostFree(c->host_pool);
     if (c->marker_host) (void)hipHostFree(c->marker_host);
@@ -485,6 +518,8 @@ int tally_destroy(tally_ctx *ctx) {
   if (ctx->live_jobs != 0) return TALLY_ERR_BAD_STATE;
   (void)hipStreamSynchronize(ctx->hi);
   (void)hipStreamSynchronize(ctx->be);
+  (void)hipStreamSynchronize(ctx->ctl);
+  (void)hipStreamDestroy(ctx->ctl);
   (void)hipFree(ctx->dev_pool);
   (void)hipHostFree(ctx->host_pool);
   (void)hipHostFree(ctx->marker_host);
@@ -632,6 +667,7 @@ int tally_job_free(tally_job *job) {
     (void)hipStreamSynchronize(ctx->be);
     (void)hipFree(job->cover);
   }
+  if (job->kind == KIND_PTB) refresh(job);  // learn the counter's final value for the slot
   ctx->slot_used[job->slot] = false;
   ctx->live_jobs--;
   delete job;
