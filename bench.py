@@ -103,6 +103,10 @@ def main():
     ap.add_argument("--workers", type=int, default=256)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--roofline-reps", type=int, default=20)
+    ap.add_argument("--leg", choices=["all", "roofline", "coloc"], default="all",
+                    help="roofline: only single launches of the GEMM/GEMV kernels plus a plain "
+                         "copy of known size (for rocprofv3 counter runs); coloc: only the "
+                         "co-located scheduling run")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (the method is a per-GPU mechanism); "
@@ -135,8 +139,37 @@ def main():
     gemv = B.gemv_bf16(x, W, y)
     be_cfg = (B.CFG_PTB, args.workers, 1)
 
+    if args.leg == "roofline":
+        # counter runs: a plain copy of known size calibrates FETCH_SIZE / WRITE_SIZE
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").fill_(1.0)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        for _ in range(args.roofline_reps):
+            ctx.launch_native(gemm)
+            be_stream.synchronize()
+            job = ctx.launch_ptb(gemm, args.workers)
+            assert job.wait() == B.JOB_COMPLETE
+            job.free()
+            ctx.launch_native(gemv)
+            be_stream.synchronize()
+        ctx.close()
+        print(json.dumps({"leg": "roofline", "reps": args.roofline_reps,
+                          "copy_bytes_read": 4 << 28, "copy_bytes_written": 4 << 28}))
+        return
+
     K, Wm = args.steps, args.warmup
     arrivals = TI.periodic_arrivals_us(args.period_us, K + Wm)
+    if args.leg == "coloc":
+        co = ctx.sched_run([gemv], arrivals, [(gemm, be_cfg)], policy=B.POLICY_TALLY, tail_us=0.0)
+        lat = co["latency_us"][Wm:]
+        ctx.close()
+        print(json.dumps({"leg": "coloc", "p50": pct(lat, 50), "p90": pct(lat, 90),
+                          "p99": pct(lat, 99), "max": float(lat.max()),
+                          "be_kernels": int(co["be_kernels_done"])}))
+        return
     window_us = float(arrivals[-1])
 
     # ---- (1) high-priority alone --------------------------------------------------------

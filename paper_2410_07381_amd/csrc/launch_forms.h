@@ -95,22 +95,37 @@ __global__ __launch_bounds__(Body::THREADS) void sliced_kernel(typename Body::Ar
 // cheaply, and mirrors the progress back to the host.  It leaves as soon as the request
 // is relayed or every worker of the segment has exited, so its lifetime is bounded by
 // the workers', which depend on nothing.
+//
+// The relay polls with scalar loads that bypass the scalar cache: a vector load that
+// waits a microsecond on PCIe sits in the compute unit's vector-memory return queue in
+// front of the loads of whatever worker shares that unit (measured: that worker's GEMM
+// tile ran 20 % longer, and with it the whole kernel); the scalar path is separate.
+__device__ __forceinline__ uint32_t scalar_load_coherent(const uint32_t *p) {
+  uint32_t v;
+  asm volatile("s_load_dword %0, %1, 0x0 glc\n\ts_waitcnt lgkmcnt(0)" : "=s"(v) : "s"(p) : "memory");
+  return v;
+}
+
 __global__ __launch_bounds__(64) void relay_kernel(PtbCtl c) {
-  if (threadIdx.x != 0) return;
-  for (;;) {
-    uint32_t want = __hip_atomic_load(c.host_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+  for (uint32_t n = 0;; ++n) {
+    uint32_t want = scalar_load_coherent(c.host_flag);
     if (want == c.epoch) {
-      __hip_atomic_store(c.dev_flag, c.epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (threadIdx.x == 0)
+        __hip_atomic_store(c.dev_flag, c.epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       return;
     }
     // the counters of a slot only ever grow (they are never reset), so a relay that
     // starts late, even after its workers are long gone, still sees the target passed
-    uint32_t gone = __hip_atomic_load(c.exited, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    uint32_t gone = scalar_load_coherent(c.exited);
+    if ((n & 255u) == 255u)  // and, now and then, through the path the workers' atomics use
+      gone = __hip_atomic_load(c.exited, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if ((int32_t)(gone - c.exit_target) >= 0) return;
-    uint32_t ctr = __hip_atomic_load(c.counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) -
-                   c.counter_base;
-    __hip_atomic_store(c.host_live, ctr < c.limit ? ctr : c.limit, __ATOMIC_RELAXED,
-                       __HIP_MEMORY_SCOPE_SYSTEM);
+    if ((n & 15u) == 0u) {
+      uint32_t ctr = scalar_load_coherent(c.counter) - c.counter_base;
+      if (threadIdx.x == 0)
+        __hip_atomic_store(c.host_live, ctr < c.limit ? ctr : c.limit, __ATOMIC_RELAXED,
+                           __HIP_MEMORY_SCOPE_SYSTEM);
+    }
   }
 }
 
@@ -138,17 +153,25 @@ __device__ __forceinline__ void ptb_body(const typename Body::Args &args, const 
       __syncthreads();  // one logical block at a time per worker
     }
   }
-  // leave: the last worker of the segment publishes the progress to the host
+  // leave: the last worker of the segment publishes the progress to the host.
+  // All of this is relaxed on purpose: an agent- or system-scope release here would make
+  // every worker write back its whole L2 (tens of microseconds with a dirty output
+  // tile).  Ordering comes from data dependence instead: a worker adds to `exited` only
+  // after its last counter fetch has returned, so when the last worker sees the target
+  // every other fetch has been performed, and it reads the counter after that.  Kernel
+  // outputs become visible to the host at the end of the kernel as usual; the status
+  // word only says that the workers are gone.
   if (threadIdx.x == 0) {
-    uint32_t old = __hip_atomic_fetch_add(c.exited, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+    uint32_t old = __hip_atomic_fetch_add(c.exited, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (old + 1 == c.exit_target) {
       uint32_t raw = __hip_atomic_load(c.counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       uint32_t ctr = raw - c.counter_base;
       uint32_t progress = ctr < c.limit ? ctr : c.limit;
       __hip_atomic_store(c.host_raw, raw, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
       __hip_atomic_store(c.host_live, progress, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // both acknowledged before the status
       __hip_atomic_store(c.host_status, ((unsigned long long)c.epoch << 32) | progress,
-                         __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+                         __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
     }
   }
 }

@@ -12,6 +12,7 @@
 #include <map>
 #include <mutex>
 #include <new>
+#include <thread>
 #include <tuple>
 #include <vector>
 
@@ -232,6 +233,7 @@ struct tally_ctx {
   uint32_t *marker_host;     // pinned: [0] hi, [32] be (separate lines)
   uint32_t *marker_dev;
   uint32_t num_cus;
+  int device;
   int live_jobs;
   std::map<std::tuple<uint32_t, uint32_t, uint32_t, uint32_t, uint32_t>, tally_config> chosen;
 };
@@ -498,6 +500,7 @@ int tally_create(tally_ctx **out, void *hip_stream_hi, void *hip_stream_be) {
   memset(c->host_pool, 0, kSlots * kHostSlotBytes);
   memset(c->marker_host, 0, 256);
   c->num_cus = (uint32_t)prop.multiProcessorCount;
+  c->device = dev;
   for (int k = 0; k < TALLY_K_COUNT; ++k)
     if (kOps[k].init && (e = kOps[k].init()) != hipSuccess) {
       g_last_hip = (int)e;
@@ -842,6 +845,113 @@ int launch_be_item(tally_ctx *ctx, const tally_be_item *it, tally_job **out) {
 }  // namespace
 
 // --------------------------------------------------------------- priority scheduling loop
+// The loop of Figure 4 split over two host threads, one per client class, because a
+// launch call cannot be interrupted: a single thread that is inside the best-effort
+// client's launch when a high-priority kernel arrives delays it by that call.
+//   high-priority thread (the caller): on arrival, raise the preemption flag of the
+//     running best-effort segment, launch the kernels in their original form, then watch
+//     for the completion marker.  While a request is in flight `hi_active` is set.
+//   best-effort thread: launch / resume / issue the next slice only while `hi_active`
+//     is clear; account for completed kernels and preemption latencies.
+namespace {
+
+struct SchedShared {
+  std::atomic<bool> hi_active{false};
+  std::atomic<bool> stop{false};
+  // slot and epoch of the persistent-worker segment now running: what the
+  // high-priority thread needs in order to raise the flag without touching the job
+  std::atomic<uint64_t> ptb_token{0};
+  std::atomic<double> t_preempt{0.0};
+  std::atomic<int> rc{TALLY_OK};
+};
+
+constexpr uint64_t kNoToken = 0;
+
+void be_thread_main(tally_ctx *ctx, tally_sched_run_t *run, SchedShared *sh, double t0, double t_end) {
+  tally_job *be = nullptr;
+  uint32_t be_idx = 0;
+  bool preempt_seen = false;  // a preemption request was raised against the current segment
+  int rc = TALLY_OK;
+  if (hipSetDevice(ctx->device) != hipSuccess) {
+    sh->rc = TALLY_ERR_HIP;
+    return;
+  }
+  auto publish = [&](tally_job *j) {
+    if (j && j->kind == KIND_PTB && j->state.load() == TALLY_JOB_RUNNING)
+      sh->ptb_token = ((uint64_t)(j->slot + 1) << 32) | j->epoch;
+    else
+      sh->ptb_token = kNoToken;
+  };
+  for (;;) {
+    const double now = now_us() - t0;
+    const bool closing = sh->stop.load() || (run->n_arrivals == 0 && now >= t_end);
+    const bool hold = run->policy != 2 && sh->hi_active.load();
+    if (be) {
+      if (hold && !preempt_seen && be->state.load() == TALLY_JOB_RUNNING) {
+        // the other thread raised the flag (persistent workers); for the other kinds
+        // "preempt" means that nothing further is issued until the request is done
+        preempt_seen = true;
+        if (be->t_preempt.load() == 0.0) be->t_preempt = sh->t_preempt.load();
+        if (be->kind == KIND_SLICED) be->stop_issuing = true;
+      }
+      refresh(be);
+      int st = be->state.load();
+      if (st != TALLY_JOB_RUNNING) publish(nullptr);
+      if (st == TALLY_JOB_COMPLETE) {
+        tally_job_free(be);
+        be = nullptr;
+        preempt_seen = false;
+        run->be_kernels_done++;
+        if (++be_idx == run->n_be_items) { be_idx = 0; run->be_steps_done++; }
+      } else if (st == TALLY_JOB_STOPPED) {
+        if (preempt_seen && be->preempt_latency_us >= 0.0) {
+          if (run->preempt_latency_us && run->n_preempts < run->preempt_cap)
+            run->preempt_latency_us[run->n_preempts] = be->preempt_latency_us;
+          run->n_preempts++;
+        }
+        preempt_seen = false;
+        if (closing) {
+          tally_job_free(be);
+          be = nullptr;
+        } else if (!hold) {
+          rc = tally_resume(be);
+          if (rc) break;
+          publish(be);
+          if (run->policy != 2 && sh->hi_active.load()) (void)tally_preempt(be);
+        }
+      } else if (be->kind == KIND_SLICED) {
+        if (closing) be->stop_issuing = true;
+        if (!hold && !closing) {
+          rc = sliced_issue(be);
+          if (rc) break;
+        }
+      } else if (closing && be->kind == KIND_PTB) {
+        (void)tally_preempt(be);
+      }
+    }
+    if (!be) {
+      if (closing) break;
+      if (!hold) {
+        rc = launch_be_item(ctx, &run->be_items[be_idx], &be);
+        if (rc) break;
+        publish(be);
+        // a request that arrived while this launch was being made has used the old
+        // token: raise the flag of the new segment here
+        if (run->policy == 0 && sh->hi_active.load() && be->kind == KIND_PTB) {
+          be->t_preempt = sh->t_preempt.load();
+          (void)tally_preempt(be);
+          preempt_seen = true;
+        }
+      }
+    }
+  }
+  publish(nullptr);
+  if (be) tally_job_free(be);
+  if (rc) sh->rc = rc;
+}
+
+}  // namespace
+
 extern "C" int tally_sched_run(tally_ctx *ctx, tally_sched_run_t *run) {
   if (!ctx || !run) return TALLY_ERR_INVALID_ARG;
   if (run->n_arrivals && (!run->arrivals_us || !run->latency_us || !run->hi_kernels ||
@@ -856,92 +966,76 @@ extern "C" int tally_sched_run(tally_ctx *ctx, tally_sched_run_t *run) {
     int rc = check_desc(&run->hi_kernels[i], &ops, &g);
     if (rc) return rc;
   }
+  for (uint32_t i = 0; i < run->n_be_items; ++i) {
+    const KernelOps *ops;
+    tally_dim3 g;
+    if (!run->be_items[i].kernel || run->be_items[i].config.kind > 2 ||
+        (run->be_items[i].config.kind != 2 && run->be_items[i].config.param == 0))
+      return TALLY_ERR_INVALID_ARG;
+    int rc = check_desc(run->be_items[i].kernel, &ops, &g);
+    if (rc) return rc;
+    if (run->be_items[i].config.kind != 2 && !ops->transformable) return TALLY_ERR_UNSUPPORTED;
+  }
   HIPCHK(hipStreamSynchronize(ctx->hi));
   HIPCHK(hipStreamSynchronize(ctx->be));
 
   uint32_t hi_seq = 0;
   (void)tally_marker_read(ctx, 1, &hi_seq);
-  uint32_t next_arrival = 0, cur = 0, completed = 0;
-  bool hi_inflight = false;
-  tally_job *be = nullptr;
-  uint32_t be_idx = 0;
-  bool be_preempt_pending = false;
   run->n_preempts = 0;
   run->be_kernels_done = 0;
   run->be_steps_done = 0;
   const double last_arrival = run->n_arrivals ? run->arrivals_us[run->n_arrivals - 1] : 0.0;
   const double t_end = last_arrival + run->tail_us;
+  SchedShared sh;
   int rc = TALLY_OK;
   const double t0 = now_us();
+  std::thread be_thread;
+  if (run->n_be_items) be_thread = std::thread(be_thread_main, ctx, run, &sh, t0, t_end);
 
-  for (;;) {
-    double now = now_us() - t0;
-    // ---- high-priority client ---------------------------------------------------------
-    if (hi_inflight) {
+  // ---- high-priority client (this thread) ----------------------------------------------
+  uint32_t next_arrival = 0, cur = 0, completed = 0;
+  bool inflight = false;
+  while (rc == TALLY_OK && sh.rc.load() == TALLY_OK) {
+    const double now = now_us() - t0;
+    if (inflight) {
       uint32_t seen;
       (void)tally_marker_read(ctx, 1, &seen);
       if (seen == hi_seq) {
         run->latency_us[cur] = (now_us() - t0) - run->arrivals_us[cur];
-        hi_inflight = false;
+        inflight = false;
         completed++;
+        // a queued request keeps the best-effort client held; otherwise release it
+        if (!(next_arrival < run->n_arrivals && run->arrivals_us[next_arrival] <= now))
+          sh.hi_active = false;
       }
     }
-    if (!hi_inflight && next_arrival < run->n_arrivals && run->arrivals_us[next_arrival] <= now) {
+    if (!inflight && next_arrival < run->n_arrivals && run->arrivals_us[next_arrival] <= now) {
       cur = next_arrival++;
-      if (run->policy == 0 && be && be->state.load() == TALLY_JOB_RUNNING) {
-        (void)tally_preempt(be);
-        be_preempt_pending = true;
+      sh.hi_active = true;
+      if (run->policy == 0) {  // preempt_best_effort_kernel(): one store to pinned memory
+        uint64_t tok = sh.ptb_token.load();
+        sh.t_preempt = now_us();
+        if (tok != kNoToken) {
+          uint32_t slot = (uint32_t)(tok >> 32) - 1;
+          __atomic_store_n((uint32_t *)(ctx->host_pool + slot * kHostSlotBytes), (uint32_t)tok,
+                           __ATOMIC_RELEASE);
+        }
       }
       for (uint32_t i = 0; i < run->n_hi_kernels && rc == TALLY_OK; ++i)
         rc = tally_launch_native(ctx, &run->hi_kernels[i], 1);
       if (rc == TALLY_OK) rc = tally_marker(ctx, 1, ++hi_seq);
-      if (rc) break;
-      hi_inflight = true;
+      inflight = true;
     }
-    // ---- best-effort client -----------------------------------------------------------
-    if (be) {
-      refresh(be);
-      int st = be->state.load();
-      if (be_preempt_pending && st != TALLY_JOB_RUNNING) {
-        if (st == TALLY_JOB_STOPPED && be->preempt_latency_us >= 0.0) {
-          if (run->preempt_latency_us && run->n_preempts < run->preempt_cap)
-            run->preempt_latency_us[run->n_preempts] = be->preempt_latency_us;
-          run->n_preempts++;
-        }
-        be_preempt_pending = false;
-      }
-      if (st == TALLY_JOB_COMPLETE) {
-        tally_job_free(be);
-        be = nullptr;
-        run->be_kernels_done++;
-        if (++be_idx == run->n_be_items) { be_idx = 0; run->be_steps_done++; }
-      }
-    }
-    const bool window_open = (now < t_end) || completed < run->n_arrivals || hi_inflight;
-    if (!window_open && !be) break;
-    if (hi_inflight && run->policy != 2) continue;  // best-effort clients are not visited
-    if (be) {
-      int st = be->state.load();
-      if (st == TALLY_JOB_STOPPED) {
-        if (window_open) rc = tally_resume(be);
-        else { tally_job_free(be); be = nullptr; }
-      } else if (st == TALLY_JOB_RUNNING && be->kind == KIND_SLICED) {
-        if (!window_open) (void)tally_preempt(be);
-        rc = sliced_issue(be);
-      } else if (st == TALLY_JOB_RUNNING && !window_open && be->kind == KIND_PTB) {
-        (void)tally_preempt(be);
-      }
-      if (rc) break;
-    } else if (run->n_be_items && window_open && now < t_end) {
-      rc = launch_be_item(ctx, &run->be_items[be_idx], &be);
-      if (rc) break;
-    } else if (!run->n_be_items && !window_open) {
+    if (!inflight && completed == run->n_arrivals && (run->n_arrivals > 0 || now >= t_end) &&
+        now >= (run->n_arrivals ? last_arrival + run->tail_us : t_end))
       break;
-    }
   }
+  sh.stop = true;
+  sh.hi_active = false;
+  if (be_thread.joinable()) be_thread.join();
   run->window_us = now_us() - t0;
-  if (be) tally_job_free(be);
   (void)hipStreamSynchronize(ctx->hi);
   (void)hipStreamSynchronize(ctx->be);
+  if (rc == TALLY_OK) rc = sh.rc.load();
   return rc;
 }

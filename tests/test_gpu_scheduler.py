@@ -1,0 +1,101 @@
+"""GPU tests of the two-stream priority scheduler: every request completes, the
+best-effort job keeps making progress and its results stay correct under preemption."""
+import numpy as np
+import pytest
+
+import tally_inputs as TI
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def env():
+    import torch
+    import paper_2410_07381_amd.binding as B
+    assert torch.cuda.is_available()
+    hi, be = torch.cuda.Stream(), torch.cuda.Stream()
+    ctx = B.Context(hi, be)
+    yield B, ctx, torch
+    ctx.close()
+
+
+@pytest.mark.parametrize("policy", [0, 1, 2])
+@pytest.mark.parametrize("be_form", ["ptb", "ptb_chunk", "sliced"])
+def test_colocated_run_completes_and_stays_correct(env, policy, be_form):
+    B, ctx, torch = env
+    from gpu_util import host
+    n = 1 << 24                                   # 4096 reduce blocks
+    x = torch.rand(n, device="cuda")
+    partial = torch.zeros(n // 4096, device="cuda")
+    sx = torch.ones(1 << 16, device="cuda")
+    sy = torch.zeros(1 << 16, device="cuda")
+    torch.cuda.synchronize()
+    be_k = B.reduce_sum(x, partial)
+    hi_k = B.saxpy(sx, sy, 1.0)                   # y += x each request
+    cfg = {"ptb": (B.CFG_PTB, 512, 1), "ptb_chunk": (B.CFG_PTB, 512, 4),
+           "sliced": (B.CFG_SLICED, 512, 1)}[be_form]
+    if policy != 0:
+        cfg = (B.CFG_NATIVE, 1, 1)
+    arrivals = TI.poisson_arrivals_us(5000.0, 200, config_index=2)
+    out = ctx.sched_run([hi_k], arrivals, [(be_k, cfg)], policy=policy, tail_us=200.0)
+    lat = out["latency_us"]
+    assert len(lat) == 200 and (lat > 0).all() and lat.max() < 5e4
+    assert out["be_kernels_done"] > 10
+    assert out["window_us"] >= arrivals[-1]
+    torch.cuda.synchronize()
+    assert (host(sy) == 200.0).all()              # every request ran exactly once
+    want = host(x).reshape(-1, 4096).sum(axis=1, dtype=np.float64)
+    assert np.allclose(host(partial), want, rtol=2e-6, atol=0)
+    if policy == 0:
+        assert (out["preempt_latency_us"] >= 0).all()
+
+
+def test_solo_runs(env):
+    B, ctx, torch = env
+    sx = torch.ones(1 << 16, device="cuda")
+    sy = torch.zeros(1 << 16, device="cuda")
+    x = torch.rand(1 << 22, device="cuda")
+    partial = torch.zeros(1 << 10, device="cuda")
+    torch.cuda.synchronize()
+    hi = ctx.sched_run([B.saxpy(sx, sy, 1.0)], TI.periodic_arrivals_us(200.0, 50), [])
+    assert (hi["latency_us"] > 0).all() and hi["be_kernels_done"] == 0
+    be = ctx.sched_run([], [], [(B.reduce_sum(x, partial), (B.CFG_PTB, 256, 1))], tail_us=5000.0)
+    assert be["be_kernels_done"] > 5 and be["window_us"] >= 5000.0
+
+
+def test_scheduler_rejects_bad_input(env):
+    B, ctx, torch = env
+    import ctypes as C
+    run = B.SchedRun()
+    run.n_arrivals = 3                               # arrivals without kernels
+    assert B.lib().tally_sched_run(ctx.h, C.byref(run)) == B.ERR_INVALID_ARG
+    run = B.SchedRun()
+    run.policy = 7
+    assert B.lib().tally_sched_run(ctx.h, C.byref(run)) == B.ERR_INVALID_ARG
+
+
+def test_profile_picks_a_config_under_the_threshold(env):
+    B, ctx, torch = env
+    x = torch.rand(1 << 26, device="cuda")
+    partial = torch.zeros(1 << 14, device="cuda")
+    torch.cuda.synchronize()
+    k = B.reduce_sum(x, partial)
+    assert ctx.lookup_config(k) is None
+    cands = [(B.CFG_PTB, 256, 1), (B.CFG_PTB, 1024, 4), (B.CFG_SLICED, 4096, 1),
+             (B.CFG_SLICED, 64, 1)]
+    meas, chosen = ctx.profile(k, cands, runs=3, threshold_ms=0.0316)
+    assert all(m["latency_ms"] > 0 and m["turnaround_ms"] > 0 for m in meas)
+    for m in meas:                                   # Eq. 1 / one-slice time
+        if m["kind"] == B.CFG_PTB:
+            want = m["latency_ms"] * m["param"] * m["chunk"] / k.total_blocks
+        else:
+            want = m["latency_ms"] / -(-k.total_blocks // m["param"])
+        assert abs(m["turnaround_ms"] - want) <= 1e-5 * want + 1e-9
+    # the library's choice equals the oracle's selection rule on the same measurements
+    from oracle import profiler as OP
+    o = OP.select_config([{"kind": "ptb" if m["kind"] == 0 else "sliced", "param": m["param"],
+                           "latency_ms": m["latency_ms"], "turnaround_ms": m["turnaround_ms"]}
+                          for m in meas], 0.0316)
+    assert (meas[chosen]["param"], meas[chosen]["kind"]) == (o["param"], 0 if o["kind"] == "ptb" else 1)
+    got = ctx.lookup_config(k)
+    assert got is not None and got["param"] == meas[chosen]["param"]

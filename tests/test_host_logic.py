@@ -1,0 +1,62 @@
+"""CPU-side checks: the shared library loads, exports every symbol the header declares,
+and its host-only functions (Eq. 1, selection rule) agree with the oracle."""
+import os
+import re
+
+import pytest
+
+from oracle import profiler as OP
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def B():
+    import paper_2410_07381_amd.binding as B
+    return B
+
+
+def test_library_exports_every_declared_symbol(B):
+    hdr = open(os.path.join(ROOT, "include", "tally.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = set(re.findall(r"\b(tally_[a-z0-9_]+)\s*\(", hdr))
+    assert len(declared) >= 25
+    for name in sorted(declared):
+        assert hasattr(B.lib(), name), f"{name} is declared in tally.h but not exported"
+    assert declared == set(B.EXPORTS)
+
+
+def test_struct_sizes_match_the_header(B):
+    import ctypes as C
+    assert C.sizeof(B.SaxpyArgs) == 24 and C.sizeof(B.ReduceSumArgs) == 24
+    assert C.sizeof(B.GemmArgs) == 64 and C.sizeof(B.GemvArgs) == 32
+    assert C.sizeof(B.CoverRec) == 24 and C.sizeof(B.Config) == 20
+    assert C.sizeof(B.KernelDesc) == 48
+
+
+def test_eq1_matches_oracle(B):
+    for lat, w, c, tot in [(1.0, 256, 1, 65536), (2.0, 16, 1, 16), (0.5, 512, 4, 4096)]:
+        assert B.ptb_turnaround_ms(lat, w, c, tot) == pytest.approx(
+            OP.ptb_turnaround_ms(lat, w * c, tot), rel=1e-12)
+
+
+def _m(kind, param, lat, turn):
+    return {"kind": kind, "param": param, "latency_ms": lat, "turnaround_ms": turn}
+
+
+@pytest.mark.parametrize("threshold", [0.0316, 1.0, 0.001, 0.0095])
+def test_selection_rule_matches_oracle(B, threshold):
+    ms = [_m(0, 256, 1.30, 0.005), _m(0, 512, 1.10, 0.010), _m(0, 2048, 1.00, 0.040),
+          _m(1, 4096, 1.05, 0.066), _m(1, 512, 1.20, 0.009), _m(1, 64, 1.10, 0.010),
+          _m(0, 128, 1.10, 0.010)]
+    o = OP.select_config([dict(m, kind="ptb" if m["kind"] == 0 else "sliced") for m in ms], threshold)
+    got = ms[B.select_config(ms, threshold)]
+    assert (got["param"], got["kind"]) == (o["param"], 0 if o["kind"] == "ptb" else 1)
+
+
+def test_error_strings_and_null_handling(B):
+    assert B.lib().tally_strerror(0) == b"ok"
+    assert b"invalid" in B.lib().tally_strerror(B.ERR_INVALID_ARG)
+    assert B.lib().tally_select_config(None, 0, 1.0) == B.ERR_INVALID_ARG
+    assert B.lib().tally_preempt(None) == B.ERR_INVALID_ARG
+    assert B.lib().tally_job_free(None) == B.ERR_INVALID_ARG
