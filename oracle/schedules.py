@@ -115,7 +115,9 @@ class PtbMachine:
         self.total = int(total)
         self.W = int(workers)
         self.order = order
-        self.chunk = int(chunk)          # task indices taken per fetch; 1 is the paper's form
+        # task indices taken per fetch (1 is the paper's form): an int, or a function of the
+        # number of indices not yet handed out, for schedules that shrink towards the end
+        self.chunk = chunk if callable(chunk) else int(chunk)
         self.held_end = [-1] * self.W
         self.counter = 0
         self.flag = False
@@ -149,6 +151,11 @@ class PtbMachine:
     def complete(self):
         return self.drained() and self.progress() == self.total
 
+    def _ask(self):
+        if callable(self.chunk):
+            return max(1, int(self.chunk(max(self.total - self.counter, 0))))
+        return self.chunk
+
     # -- transitions --------------------------------------------------------------------
     def raise_flag(self):
         self.flag = True
@@ -163,20 +170,22 @@ class PtbMachine:
                     self.state[w] = EXITED
                     return
                 idx = self.counter
-                self.counter += self.chunk
+                n = self._ask()
+                self.counter += n
                 if idx >= self.total:
                     self.state[w] = EXITED
                     return
                 self.state[w], self.held[w] = FETCHED, idx
-                self.held_end[w] = min(idx + self.chunk, self.total)
+                self.held_end[w] = min(idx + n, self.total)
             else:  # wrong order: fetch first, then honour the flag and drop the index
                 idx = self.counter
-                self.counter += self.chunk
+                n = self._ask()
+                self.counter += n
                 if idx >= self.total or self.flag:
                     self.state[w] = EXITED
                     return
                 self.state[w], self.held[w] = FETCHED, idx
-                self.held_end[w] = min(idx + self.chunk, self.total)
+                self.held_end[w] = min(idx + n, self.total)
         else:  # FETCHED: run one held block, reach the barrier; loop when none is left
             idx = self.held[w]
             if self.on_exec is not None:

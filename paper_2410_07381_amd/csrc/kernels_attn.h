@@ -30,7 +30,9 @@ __device__ __forceinline__ void unpack8(uint4 u, float (&f)[8]) {
   f[4] = bf16_lo(u.z); f[5] = bf16_hi(u.z); f[6] = bf16_lo(u.w); f[7] = bf16_hi(u.w);
 }
 
-__global__ __launch_bounds__(256) void attn_decode_partial(tally_attn_decode_args a, uint32_t chunk) {
+__global__ __launch_bounds__(256) void attn_decode_partial(tally_attn_decode_args a, uint32_t chunk,
+                                                           uint32_t urgent) {
+  if (urgent) __builtin_amdgcn_s_setprio(3);
   __shared__ float s_score[kAttnMaxChunk];
   __shared__ float s_red[4];
   __shared__ float s_acc[4][kAttnDim];
@@ -125,13 +127,14 @@ __global__ __launch_bounds__(128) void attn_decode_combine(tally_attn_decode_arg
 
 inline hipError_t attn_decode_init() { return hipSuccess; }
 
-inline hipError_t launch_attn_decode(hipStream_t s, const void *args, tally_dim3) {
+inline hipError_t launch_attn_decode(hipStream_t s, const void *args, tally_dim3, uint32_t urgent) {
   tally_attn_decode_args a;
   memcpy(&a, args, sizeof(a));
   uint32_t chunk = (a.tokens + kAttnSplits - 1) / kAttnSplits;
   chunk = (chunk + 15u) & ~15u;
   if (chunk > kAttnMaxChunk) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(attn_decode_partial, dim3(kAttnSplits, a.heads), dim3(256), 0, s, a, chunk);
+  hipLaunchKernelGGL(attn_decode_partial, dim3(kAttnSplits, a.heads), dim3(256), 0, s, a, chunk,
+                     urgent);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(attn_decode_combine, dim3(a.heads), dim3(128), 0, s, a);

@@ -35,10 +35,14 @@ typedef __attribute__((address_space(3))) void *lptr_t;
 struct GemmBody {
   using Args = tally_gemm_bf16_args;
   static constexpr int THREADS = 256;
+  static constexpr int MIN_WAVES = 1;
   static constexpr int TILE = 256;
   static constexpr int BK = 64;
   static constexpr int BUF = TILE * BK;                   // one operand buffer, in bf16 (32 KB)
   static constexpr unsigned DYN_LDS = 4u * BUF * 2u;      // A0 A1 B0 B1 = 128 KB
+  // every k-step ends with a barrier after its LDS reads, so the next tile's first loads
+  // cannot overtake a reader of this tile
+  static constexpr bool END_BARRIER = false;
 
   static __device__ __forceinline__ void run(const Args &a, uint32_t bx, uint32_t by, uint32_t bz) {
     extern __shared__ __align__(1024) unsigned char tally_dyn_lds[];
@@ -140,8 +144,10 @@ struct GemmBody {
 struct GemmSmallBody {
   using Args = tally_gemm_bf16_args;
   static constexpr int THREADS = 256;
+  static constexpr int MIN_WAVES = 2;
   static constexpr int TILE = 64;
   static constexpr unsigned DYN_LDS = 0;
+  static constexpr bool END_BARRIER = false;
 
   static __device__ __forceinline__ void run(const Args &a, uint32_t bx, uint32_t by, uint32_t bz) {
     const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;

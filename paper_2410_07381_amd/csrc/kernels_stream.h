@@ -35,7 +35,9 @@ __device__ __forceinline__ uint16_t f32_to_bf16(float f) {
 struct SaxpyBody {
   using Args = tally_saxpy_args;
   static constexpr int THREADS = kThreads;
+  static constexpr int MIN_WAVES = 4;
   static constexpr unsigned DYN_LDS = 0;
+  static constexpr bool END_BARRIER = false;
   static __device__ __forceinline__ void run(const Args &a, uint32_t bx, uint32_t, uint32_t) {
     uint32_t i = bx * kThreads + threadIdx.x;
     if (i < a.n) a.y[i] = __builtin_fmaf(a.a, a.x[i], a.y[i]);
@@ -46,10 +48,16 @@ struct SaxpyBody {
 struct ReduceSumBody {
   using Args = tally_reduce_sum_args;
   static constexpr int THREADS = kThreads;
+  static constexpr int MIN_WAVES = 4;
   static constexpr unsigned DYN_LDS = 0;
+  static constexpr bool END_BARRIER = false;
   static constexpr uint32_t PER_BLOCK = 4096;
   static __device__ __forceinline__ void run(const Args &a, uint32_t bx, uint32_t, uint32_t) {
-    __shared__ float s_part[kThreads / kWave];
+    // two sets of wave partials, alternating with the block index: a worker that runs
+    // consecutive blocks back to back then needs no barrier between them (the barrier
+    // below already keeps any wave at most one block ahead of the reader)
+    __shared__ float s_part2[2][kThreads / kWave];
+    float *s_part = s_part2[bx & 1];
     const uint64_t base = (uint64_t)bx * PER_BLOCK;
     float s = 0.f;
     if (base + PER_BLOCK <= a.n) {
@@ -62,8 +70,6 @@ struct ReduceSumBody {
       for (uint64_t i = base + threadIdx.x; i < a.n; i += kThreads) s += a.x[i];
     }
     s = wave_sum(s);
-    // the previous logical block's readers of s_part are past the barrier that ends
-    // every iteration of the persistent-worker loop, or belong to another launch
     if ((threadIdx.x & (kWave - 1)) == 0) s_part[threadIdx.x / kWave] = s;
     __syncthreads();
     if (threadIdx.x == 0) a.partial[bx] = (s_part[0] + s_part[1]) + (s_part[2] + s_part[3]);
@@ -73,7 +79,9 @@ struct ReduceSumBody {
 struct ReduceFinalBody {
   using Args = tally_reduce_final_args;
   static constexpr int THREADS = kThreads;
+  static constexpr int MIN_WAVES = 4;
   static constexpr unsigned DYN_LDS = 0;
+  static constexpr bool END_BARRIER = true;   // s_d is reused by the next block
   static __device__ __forceinline__ void run(const Args &a, uint32_t, uint32_t, uint32_t) {
     __shared__ double s_d[kThreads];
     double s = 0.0;
@@ -92,7 +100,9 @@ struct ReduceFinalBody {
 struct GemvBody {
   using Args = tally_gemv_bf16_args;
   static constexpr int THREADS = kThreads;
+  static constexpr int MIN_WAVES = 4;
   static constexpr unsigned DYN_LDS = 0;
+  static constexpr bool END_BARRIER = false;
   static __device__ __forceinline__ float dot8(uint4 w, uint4 x) {
     float s = bf16_lo(w.x) * bf16_lo(x.x);
     s = __builtin_fmaf(bf16_hi(w.x), bf16_hi(x.x), s);
@@ -164,10 +174,37 @@ __device__ __forceinline__ void softmax_row(const float *x, float *y, uint32_t c
   }
 }
 
+// Rows wider than 4096 would need more than 64 registers per lane to stay resident, and
+// the widest instantiation sets the register allocation (hence the occupancy) of the
+// whole kernel; such rows are walked three times instead and come from cache after the
+// first pass.
+__device__ __forceinline__ void softmax_row_streamed(const float *x, float *y, uint32_t cols,
+                                                     uint32_t lane) {
+  float m = -INFINITY;
+  for (uint32_t c = lane * 4; c < cols; c += kWave * 4) {
+    float4 v = *reinterpret_cast<const float4 *>(x + c);
+    m = fmaxf(m, fmaxf(fmaxf(v.x, v.y), fmaxf(v.z, v.w)));
+  }
+  m = wave_max(m);
+  float s = 0.f;
+  for (uint32_t c = lane * 4; c < cols; c += kWave * 4) {
+    float4 v = *reinterpret_cast<const float4 *>(x + c);
+    s += (__expf(v.x - m) + __expf(v.y - m)) + (__expf(v.z - m) + __expf(v.w - m));
+  }
+  const float inv = 1.0f / wave_sum(s);
+  for (uint32_t c = lane * 4; c < cols; c += kWave * 4) {
+    float4 v = *reinterpret_cast<const float4 *>(x + c);
+    *reinterpret_cast<float4 *>(y + c) = make_float4(__expf(v.x - m) * inv, __expf(v.y - m) * inv,
+                                                     __expf(v.z - m) * inv, __expf(v.w - m) * inv);
+  }
+}
+
 struct SoftmaxBody {
   using Args = tally_softmax_f32_args;
   static constexpr int THREADS = kThreads;
+  static constexpr int MIN_WAVES = 4;
   static constexpr unsigned DYN_LDS = 0;
+  static constexpr bool END_BARRIER = false;
   static __device__ __forceinline__ void run(const Args &a, uint32_t bx, uint32_t, uint32_t) {
     const uint32_t lane = threadIdx.x & (kWave - 1);
     const uint32_t row = bx * 4 + threadIdx.x / kWave;
@@ -179,7 +216,7 @@ struct SoftmaxBody {
     else if (a.cols <= 1024) softmax_row<4>(x, y, a.cols, lane);
     else if (a.cols <= 2048) softmax_row<8>(x, y, a.cols, lane);
     else if (a.cols <= 4096) softmax_row<16>(x, y, a.cols, lane);
-    else softmax_row<32>(x, y, a.cols, lane);
+    else softmax_row_streamed(x, y, a.cols, lane);
   }
 };
 
@@ -217,10 +254,40 @@ __device__ __forceinline__ void layernorm_row(const float *x, const float *g, co
   }
 }
 
+__device__ __forceinline__ void layernorm_row_streamed(const float *x, const float *g,
+                                                       const float *b, float *y, uint32_t cols,
+                                                       float eps, uint32_t lane) {
+  float s = 0.f;
+  for (uint32_t c = lane * 4; c < cols; c += kWave * 4) {
+    float4 v = *reinterpret_cast<const float4 *>(x + c);
+    s += (v.x + v.y) + (v.z + v.w);
+  }
+  const float mu = wave_sum(s) / (float)cols;
+  float q = 0.f;
+  for (uint32_t c = lane * 4; c < cols; c += kWave * 4) {
+    float4 v = *reinterpret_cast<const float4 *>(x + c);
+    float dx = v.x - mu, dy = v.y - mu, dz = v.z - mu, dw = v.w - mu;
+    q += (dx * dx + dy * dy) + (dz * dz + dw * dw);
+  }
+  const float rstd = 1.0f / sqrtf(wave_sum(q) / (float)cols + eps);
+  for (uint32_t c = lane * 4; c < cols; c += kWave * 4) {
+    float4 v = *reinterpret_cast<const float4 *>(x + c);
+    float4 gg = *reinterpret_cast<const float4 *>(g + c);
+    float4 bb = *reinterpret_cast<const float4 *>(b + c);
+    *reinterpret_cast<float4 *>(y + c) =
+        make_float4(__builtin_fmaf((v.x - mu) * rstd, gg.x, bb.x),
+                    __builtin_fmaf((v.y - mu) * rstd, gg.y, bb.y),
+                    __builtin_fmaf((v.z - mu) * rstd, gg.z, bb.z),
+                    __builtin_fmaf((v.w - mu) * rstd, gg.w, bb.w));
+  }
+}
+
 struct LayerNormBody {
   using Args = tally_layernorm_f32_args;
   static constexpr int THREADS = kThreads;
+  static constexpr int MIN_WAVES = 2;
   static constexpr unsigned DYN_LDS = 0;
+  static constexpr bool END_BARRIER = false;
   static __device__ __forceinline__ void run(const Args &a, uint32_t bx, uint32_t, uint32_t) {
     const uint32_t lane = threadIdx.x & (kWave - 1);
     const uint32_t row = bx * 4 + threadIdx.x / kWave;
@@ -232,7 +299,7 @@ struct LayerNormBody {
     else if (a.cols <= 1024) layernorm_row<4>(x, a.gamma, a.beta, y, a.cols, a.eps, lane);
     else if (a.cols <= 2048) layernorm_row<8>(x, a.gamma, a.beta, y, a.cols, a.eps, lane);
     else if (a.cols <= 4096) layernorm_row<16>(x, a.gamma, a.beta, y, a.cols, a.eps, lane);
-    else layernorm_row<32>(x, a.gamma, a.beta, y, a.cols, a.eps, lane);
+    else layernorm_row_streamed(x, a.gamma, a.beta, y, a.cols, a.eps, lane);
   }
 };
 

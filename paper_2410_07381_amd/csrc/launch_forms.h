@@ -3,7 +3,10 @@
 // A Body is a struct with
 //   using Args = <POD passed by value to the kernel>;
 //   static constexpr int THREADS;            threads per logical block
+//   static constexpr int MIN_WAVES;          waves per SIMD the compiler must leave room for
 //   static constexpr unsigned DYN_LDS;       dynamic LDS bytes the body needs
+//   static constexpr bool END_BARRIER;       true if consecutive blocks run by one workgroup
+//                                            would race on workgroup-shared state
 //   static __device__ void run(const Args&, uint32_t bx, uint32_t by, uint32_t bz);
 // run() performs the work of original block (bx,by,bz); every thread of the workgroup
 // calls it and returns from it (no early exit), so the workgroup-wide barriers of the
@@ -22,7 +25,8 @@ constexpr uint32_t kStop = 0xFFFFFFFFu;
 // Device-side control block of one persistent-worker launch segment.
 struct PtbCtl {
   uint32_t *counter;        // device: global task counter (next task index)
-  uint32_t *dev_flag;       // device: holds the epoch of the last preemption seen by the relay
+  uint32_t *dev_flag;       // device, 8-byte aligned: [0] epoch of the last preemption relayed,
+                            // [1] epoch of the last segment whose grid was exhausted
   uint32_t *exited;         // device: workers that have exited, summed over all segments
   const uint32_t *host_flag;  // pinned host memory: epoch the host wants preempted
   unsigned long long *host_status;  // pinned: (epoch << 32 | progress) once drained
@@ -66,8 +70,13 @@ __device__ __forceinline__ void record(tally_cover_rec *cover, uint32_t idx, uin
 }
 
 // ---- original form -------------------------------------------------------------------
+// `urgent` marks a launch on the high-priority stream: its waves raise their own issue
+// priority so that, where they share a SIMD with a best-effort wave that is still
+// finishing its block, the arbiter picks their instructions first.
 template <class Body>
-__global__ __launch_bounds__(Body::THREADS) void native_kernel(typename Body::Args args) {
+__global__ __launch_bounds__(Body::THREADS, Body::MIN_WAVES) void native_kernel(typename Body::Args args,
+                                                               uint32_t urgent) {
+  if (urgent) __builtin_amdgcn_s_setprio(3);
   Body::run(args, blockIdx.x, blockIdx.y, blockIdx.z);
 }
 
@@ -82,7 +91,7 @@ __device__ __forceinline__ void sliced_body(const typename Body::Args &args, con
   record(ctl.cover, idx, bx, by, bz, ctl.segment, blockIdx.x);
 }
 template <class Body>
-__global__ __launch_bounds__(Body::THREADS) void sliced_kernel(typename Body::Args args,
+__global__ __launch_bounds__(Body::THREADS, Body::MIN_WAVES) void sliced_kernel(typename Body::Args args,
                                                                SliceCtl ctl) {
   sliced_body<Body>(args, ctl);
 }
@@ -131,18 +140,32 @@ __global__ __launch_bounds__(64) void relay_kernel(PtbCtl c) {
 
 template <class Body>
 __device__ __forceinline__ void ptb_body(const typename Body::Args &args, const PtbCtl &c) {
-  __shared__ uint32_t s_idx;
+  __shared__ uint32_t s_idx[2];
   const uint32_t worker = blockIdx.x;
-  for (;;) {
-    // start of an iteration: check the flag, THEN fetch; a fetched index is always run
+  // One lane reads flag and counter and broadcasts through LDS, so the exit decision is
+  // uniform over the workgroup.  Order as in the paper: check the flag, then fetch; a
+  // fetched index is always run.
+  //
+  // The word next to the flag says "grid exhausted": the worker whose fetch reaches the
+  // end of the grid sets it, and the others then leave without one more fetch-add.  The
+  // counter is one address that serves only ~88 M operations per second (loads included),
+  // so W failing fetches at the very end would add W x 11 ns to every kernel.
+  for (uint32_t it = 0;; ++it) {
     if (threadIdx.x == 0) {
-      uint32_t f = __hip_atomic_load(c.dev_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      s_idx = (f == c.epoch) ? kStop
-                             : __hip_atomic_fetch_add(c.counter, c.chunk, __ATOMIC_RELAXED,
-                                                      __HIP_MEMORY_SCOPE_AGENT) - c.counter_base;
+      const unsigned long long f = __hip_atomic_load(
+          reinterpret_cast<const unsigned long long *>(c.dev_flag), __ATOMIC_RELAXED,
+          __HIP_MEMORY_SCOPE_AGENT);
+      uint32_t first0 = kStop;
+      if ((uint32_t)f != c.epoch && (uint32_t)(f >> 32) != c.epoch) {
+        first0 = __hip_atomic_fetch_add(c.counter, c.chunk, __ATOMIC_RELAXED,
+                                        __HIP_MEMORY_SCOPE_AGENT) - c.counter_base;
+        if (first0 < c.limit && c.limit - first0 <= c.chunk)
+          __hip_atomic_store(c.dev_flag + 1, c.epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+      s_idx[it & 1] = first0;
     }
     __syncthreads();
-    const uint32_t first = s_idx;
+    const uint32_t first = s_idx[it & 1];
     if (first >= c.limit) break;  // uniform across the workgroup
     const uint32_t last = (c.limit - first < c.chunk) ? c.limit : first + c.chunk;
     for (uint32_t idx = first; idx < last; ++idx) {
@@ -150,7 +173,9 @@ __device__ __forceinline__ void ptb_body(const typename Body::Args &args, const 
       delinearize(idx, c.gx, c.gy, bx, by, bz);
       Body::run(args, bx, by, bz);
       record(c.cover, idx, bx, by, bz, c.segment, worker);
-      __syncthreads();  // one logical block at a time per worker
+      // the paper ends every iteration with a barrier so that a worker handles one block
+      // at a time; a body whose waves share no state across blocks does not need it
+      if (Body::END_BARRIER) __syncthreads();
     }
   }
   // leave: the last worker of the segment publishes the progress to the host.
@@ -176,7 +201,7 @@ __device__ __forceinline__ void ptb_body(const typename Body::Args &args, const 
   }
 }
 template <class Body>
-__global__ __launch_bounds__(Body::THREADS) void ptb_kernel(typename Body::Args args, PtbCtl c) {
+__global__ __launch_bounds__(Body::THREADS, Body::MIN_WAVES) void ptb_kernel(typename Body::Args args, PtbCtl c) {
   ptb_body<Body>(args, c);
 }
 

@@ -51,7 +51,7 @@ struct KernelOps {
   size_t args_size;
   bool transformable;  // false: native form only
   int (*grid)(const void *args, tally_dim3 *g, tally_dim3 *b);
-  hipError_t (*native)(hipStream_t, const void *args, tally_dim3 g);
+  hipError_t (*native)(hipStream_t, const void *args, tally_dim3 g, uint32_t urgent);
   hipError_t (*sliced)(hipStream_t, const void *args, uint32_t nblocks, const SliceCtl &);
   hipError_t (*ptb)(hipStream_t, const void *args, const PtbCtl &);
   hipError_t (*init)();
@@ -59,11 +59,11 @@ struct KernelOps {
 };
 
 template <class Body>
-hipError_t launch_native_t(hipStream_t s, const void *args, tally_dim3 g) {
+hipError_t launch_native_t(hipStream_t s, const void *args, tally_dim3 g, uint32_t urgent) {
   typename Body::Args a;
   memcpy(&a, args, sizeof(a));
   hipLaunchKernelGGL(native_kernel<Body>, dim3(g.x, g.y, g.z), dim3(Body::THREADS), Body::DYN_LDS,
-                     s, a);
+                     s, a, urgent);
   return hipGetLastError();
 }
 template <class Body>
@@ -550,7 +550,7 @@ int tally_launch_native(tally_ctx *ctx, const tally_kernel_desc *desc, int on_hi
   tally_dim3 g;
   int rc = check_desc(desc, &ops, &g);
   if (rc) return rc;
-  HIPCHK(ops->native(on_hi_stream ? ctx->hi : ctx->be, desc->args, g));
+  HIPCHK(ops->native(on_hi_stream ? ctx->hi : ctx->be, desc->args, g, on_hi_stream ? 1u : 0u));
   return TALLY_OK;
 }
 
@@ -827,7 +827,7 @@ int launch_be_item(tally_ctx *ctx, const tally_be_item *it, tally_job **out) {
   int rc = new_job(ctx, it->kernel, KIND_NATIVE, 0, &j);
   if (rc) return rc;
   j->state = TALLY_JOB_RUNNING;
-  hipError_t e = j->ops->native(ctx->be, j->args, j->grid);
+  hipError_t e = j->ops->native(ctx->be, j->args, j->grid, 0u);
   if (e == hipSuccess) {
     hipLaunchKernelGGL(marker_kernel, dim3(1), dim3(64), 0, ctx->be,
                        (uint32_t *)(j->h_base_dev() + 128), 1u);
