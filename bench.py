@@ -97,8 +97,11 @@ def cpu_baseline(g, gv, budget_s=15.0):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=2000)
-    ap.add_argument("--warmup", type=int, default=100)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=None)
+    ap.add_argument("--workload", choices=["cfg0", "cfg1", "cfg2", "cfg3", "cfg4"], default="cfg1",
+                    help="cfg1 is the headline workload; the others print one JSON line each "
+                         "with that configuration's figures")
     ap.add_argument("--period-us", type=float, default=1000.0)
     ap.add_argument("--workers", type=int, default=256)
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -108,6 +111,12 @@ def main():
                          "copy of known size (for rocprofv3 counter runs); coloc: only the "
                          "co-located scheduling run")
     args = ap.parse_args()
+    defaults = {"cfg0": (1, 0), "cfg1": (2000, 100), "cfg2": (1500, 100), "cfg3": (500, 50),
+                "cfg4": (1000, 100)}[args.workload]
+    if args.steps is None:
+        args.steps = defaults[0]
+    if args.warmup is None:
+        args.warmup = defaults[1]
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (the method is a per-GPU mechanism); "
               "run with --gpus 1", file=sys.stderr)
@@ -121,6 +130,14 @@ def main():
     torch.cuda.set_device(0)
     hi_stream, be_stream = torch.cuda.Stream(), torch.cuda.Stream()
     ctx = B.Context(hi_stream, be_stream)
+
+    if args.workload != "cfg1":
+        import bench_configs
+        out = bench_configs.WORKLOADS[args.workload](torch, B, ctx, be_stream, args)
+        out.update({"n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "data": "synthetic"})
+        ctx.close()
+        print(json.dumps(out))
+        return
 
     # ---- inputs, resident in HBM before any timed region --------------------------------
     g = TI.gemm_inputs(4096, 4096, 4096, config_index=1)
@@ -211,7 +228,11 @@ def main():
     roofline = {
         "bound": "mfma", "kernel": "ptb_kernel<GemmBody> (best-effort GEMM, persistent workers)",
         "achieved": tf_ptb, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-        "frac": tf_ptb / PEAK_BF16_TFLOPS, "traffic": None,
+        "frac": tf_ptb / PEAK_BF16_TFLOPS,
+        # HBM-side bytes per launch from the committed rocprofv3 counter runs
+        # (profiles/gemm_bf16_cfg1_roofline_counters.txt): FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0
+        "traffic": 160135.9 * 1024 * 2.0 + 32799.7 * 1024,
+        "traffic_unit": "bytes per launch (algorithmic: 100663296)",
         "avg_launch_ms": ms_ptb,
         "native": {"achieved": tf_nat, "frac": tf_nat / PEAK_BF16_TFLOPS, "avg_launch_ms": ms_nat},
         "transformed_over_native": tf_ptb / tf_nat,

@@ -1,0 +1,333 @@
+"""The benchmark configurations other than the headline one (`bench.py --workload cfgN`).
+
+cfg0  best-effort SAXPY alone: persistent workers, 3 seeded preemptions + resumes
+cfg2  sliced-launch sweep of a 2^28 fp32 sum against a Poisson 500/s hi-pri SAXPY
+cfg3  training-like best-effort step (transformer-layer GEMMs, softmax, LayerNorm) in
+      persistent-worker form against a 768-hidden inference-like layer, Poisson 100/s
+cfg4  the cfg3 step against decode-like kernels (two GEMVs + attention), Poisson 200/s
+
+Each returns a dict that bench.py prints as one JSON line.  All inputs are synthetic and
+resident in HBM before timing.  Kernels of a "step" are independent launches with the
+shapes of the layer (no data flows between them): the subject here is scheduling, and
+every kernel's numerics are checked separately against the oracle in tests/.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+PEAK_HBM_GBS = 8000.0
+PEAK_BF16_TFLOPS = 2500.0
+
+
+def pct(a, q):
+    s = np.sort(np.asarray(a))
+    if len(s) == 0:
+        return None
+    return float(s[max(int(np.ceil(q / 100.0 * len(s))) - 1, 0)])
+
+
+def _time(torch, B, stream, launch, reps=10, warm=2, wait_before_stop=False):
+    """Mean/min duration in us of one launch, HIP events on `stream`.  For host-driven
+    forms (sliced) the stop event is recorded after the job has completed."""
+    us = []
+    for i in range(reps + warm):
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        job = launch()
+        if job is not None and wait_before_stop:
+            job.wait()
+        e1.record(stream)
+        if job is not None:
+            assert job.wait() == B.JOB_COMPLETE
+            job.free()
+        stream.synchronize()
+        if i >= warm:
+            us.append(e0.elapsed_time(e1) * 1e3)
+    return float(np.mean(us)), float(np.min(us))
+
+
+def _bf16(torch, shape, scale):
+    return (torch.randn(shape, device="cuda") * scale).to(torch.bfloat16).view(torch.int16)
+
+
+# ------------------------------------------------------------------------------------ cfg0
+def cfg0(torch, B, ctx, be_stream, args):
+    import tally_inputs as TI
+    base = TI.saxpy_inputs(n=1 << 20, config_index=0)
+    pts = TI.preempt_points(4096, 3, config_index=0)
+    x, y = torch.from_numpy(base["x"]).cuda(), torch.from_numpy(base["y"]).cuda()
+    torch.cuda.synchronize()
+    k = B.saxpy(x, y, base["a"])
+    nbytes = 12 * (1 << 20)
+    nat = _time(torch, B, be_stream, lambda: (ctx.launch_native(k), None)[1])
+    ptb = _time(torch, B, be_stream, lambda: ctx.launch_ptb(k, 256))
+    ptb16 = _time(torch, B, be_stream, lambda: ctx.launch_ptb(k, 256, chunk=16))
+
+    def preempted_run():
+        job = ctx.launch_ptb(k, 256, stop_at=pts[0])
+        for nxt in pts[1:] + [None]:
+            job.wait()
+            job.resume(stop_at=nxt)
+        return job
+    pre = _time(torch, B, be_stream, preempted_run, wait_before_stop=True)
+    return {
+        "workload": "cfg0: fp32 SAXPY N=2^20, grid 4096x256, 256 persistent workers, 3 seeded "
+                    f"preemptions at counter values {pts} each followed by a resume",
+        "native_us": nat[0], "ptb_us": ptb[0], "ptb_chunk16_us": ptb16[0],
+        "ptb_3_preemptions_us": pre[0],
+        "native_GBps": nbytes / nat[0] / 1e3, "ptb_GBps": nbytes / ptb[0] / 1e3,
+        "note": "12 MB of traffic: launch- and latency-bound, not an HBM roofline case; one "
+                "fetch-add per 3 KB block on a counter that serves ~88 M operations/s",
+    }
+
+
+# ------------------------------------------------------------------------------------ cfg2
+def cfg2(torch, B, ctx, be_stream, args):
+    import tally_inputs as TI
+    n = 1 << 28
+    x = torch.rand(n, device="cuda")
+    partial = torch.zeros(n // 4096, device="cuda")
+    sx = torch.randn(1 << 20, device="cuda")
+    sy = torch.randn(1 << 20, device="cuda")
+    torch.cuda.synchronize()
+    red = B.reduce_sum(x, partial)
+    hi = B.saxpy(sx, sy, 1.5)
+    nbytes = 4 * n
+    count = args.steps
+    arrivals = TI.poisson_arrivals_us(500.0, count, config_index=2)
+    solo = ctx.sched_run([hi], arrivals, [])
+    p99_solo = pct(solo["latency_us"][args.warmup:], 99)
+    nat = _time(torch, B, be_stream, lambda: (ctx.launch_native(red), None)[1])
+    out = {
+        "workload": "cfg2: fp32 sum of 2^28 U(0,1) (65536 blocks x 256 threads) as sliced launches "
+                    "against a hi-pri 2^20 SAXPY, Poisson 500/s",
+        "native_us": nat[0], "native_GBps": nbytes / nat[0] / 1e3,
+        "native_hbm_frac": nbytes / nat[0] / 1e3 / PEAK_HBM_GBS,
+        "hi_solo_p50_us": pct(solo["latency_us"][args.warmup:], 50), "hi_solo_p99_us": p99_solo,
+        "slices": {},
+    }
+    for s in (4096, 512, 64, 8, 1):
+        nslices = 65536 // s
+        reps = 5 if s >= 64 else 1
+        t = _time(torch, B, be_stream, lambda: ctx.launch_sliced(red, s), reps=reps, warm=1,
+                  wait_before_stop=True)
+        co = ctx.sched_run([hi], arrivals, [(red, (B.CFG_SLICED, s, 1))], tail_us=0.0)
+        lat = co["latency_us"][args.warmup:]
+        out["slices"][str(s)] = {
+            "launches": nslices, "total_us": t[0],
+            "per_slice_overhead_us": (t[0] - nat[0]) / nslices,
+            "GBps": nbytes / t[0] / 1e3,
+            "hi_p50_us": pct(lat, 50), "hi_p99_us": pct(lat, 99),
+            "hi_p99_overhead_pct": (pct(lat, 99) - p99_solo) / p99_solo * 100.0,
+            "be_kernels_done": int(co["be_kernels_done"]),
+            "preempt_p50_us": pct(co["preempt_latency_us"], 50),
+        }
+    # the persistent-worker alternative the profiler weighs against slicing
+    for w, c in ((512, 32), (512, 8), (1024, 2)):
+        t = _time(torch, B, be_stream, lambda: ctx.launch_ptb(red, w, chunk=c))
+        co = ctx.sched_run([hi], arrivals, [(red, (B.CFG_PTB, w, c))], tail_us=0.0)
+        lat = co["latency_us"][args.warmup:]
+        pre = co["preempt_latency_us"]
+        out.setdefault("ptb", {})[f"W{w}_chunk{c}"] = {
+            "total_us": t[0], "GBps": nbytes / t[0] / 1e3, "of_native": nat[0] / t[0],
+            "eq1_turnaround_us": B.ptb_turnaround_ms(t[0] / 1e3, w, c, 65536) * 1e3,
+            "hi_p50_us": pct(lat, 50), "hi_p99_us": pct(lat, 99),
+            "hi_p99_overhead_pct": (pct(lat, 99) - p99_solo) / p99_solo * 100.0,
+            "n_preempts": int(co["n_preempts"]), "preempt_p50_us": pct(pre, 50),
+            "preempt_p99_us": pct(pre, 99), "be_kernels_done": int(co["be_kernels_done"]),
+        }
+    cands = [(B.CFG_PTB, 512, 32), (B.CFG_PTB, 512, 8), (B.CFG_PTB, 1024, 2), (B.CFG_PTB, 256, 1),
+             (B.CFG_SLICED, 4096, 1), (B.CFG_SLICED, 512, 1)]
+    meas, chosen = ctx.profile(red, cands, runs=10, threshold_ms=0.0316)
+    out["profile_guided_choice"] = {"threshold_ms": 0.0316, "chosen": meas[chosen],
+                                    "candidates": meas}
+    return out
+
+
+# ------------------------------------------------------------------------------ cfg3 / cfg4
+def _be_step(torch, B):
+    """Forward kernels of one transformer layer: hidden 4096, FFN 16384, seq 2048, batch 8,
+    32 heads x 128.  Returns [(name, Kernel, flops, bytes)]."""
+    T, H, F, S, NH, D, BATCH = 16384, 4096, 16384, 2048, 32, 128, 8
+    s = 0.02
+    X = _bf16(torch, (1, T, H), s)
+    Wqkv = _bf16(torch, (1, 3 * H, H), s)
+    QKV = torch.empty((1, T, 3 * H), dtype=torch.int16, device="cuda")
+    Q = _bf16(torch, (BATCH * NH, S, D), s)
+    Kh = _bf16(torch, (BATCH * NH, S, D), s)
+    SC = torch.empty((BATCH * NH, S, S), dtype=torch.int16, device="cuda")
+    P32 = torch.randn((BATCH * NH * S, S), device="cuda") * s
+    P32o = torch.empty_like(P32)
+    Pb = _bf16(torch, (BATCH * NH, S, S), s)
+    Vt = _bf16(torch, (BATCH * NH, D, S), s)
+    O = torch.empty((BATCH * NH, S, D), dtype=torch.int16, device="cuda")
+    Wo = _bf16(torch, (1, H, H), s)
+    AO = torch.empty((1, T, H), dtype=torch.int16, device="cuda")
+    L32 = torch.randn((T, H), device="cuda") * s
+    L32o = torch.empty_like(L32)
+    g = torch.ones(H, device="cuda")
+    b = torch.zeros(H, device="cuda")
+    W1 = _bf16(torch, (1, F, H), s)
+    H1 = torch.empty((1, T, F), dtype=torch.int16, device="cuda")
+    H1in = _bf16(torch, (1, T, F), s)
+    W2 = _bf16(torch, (1, H, F), s)
+    H2 = torch.empty((1, T, H), dtype=torch.int16, device="cuda")
+    torch.cuda.synchronize()
+    ks = [
+        ("qkv_gemm", B.gemm_bf16(X, Wqkv, QKV), 2.0 * T * 3 * H * H, 0),
+        ("scores_gemm", B.gemm_bf16(Q, Kh, SC), 2.0 * BATCH * NH * S * S * D, 0),
+        ("softmax", B.softmax_f32(P32, P32o), 0, 8.0 * P32.numel()),
+        ("pv_gemm", B.gemm_bf16(Pb, Vt, O, small=True), 2.0 * BATCH * NH * S * S * D, 0),
+        ("out_gemm", B.gemm_bf16(X, Wo, AO), 2.0 * T * H * H, 0),
+        ("layernorm1", B.layernorm_f32(L32, g, b, L32o, 1e-5), 0, 8.0 * L32.numel()),
+        ("ffn1_gemm", B.gemm_bf16(X, W1, H1), 2.0 * T * F * H, 0),
+        ("ffn2_gemm", B.gemm_bf16(H1in, W2, H2), 2.0 * T * H * F, 0),
+        ("layernorm2", B.layernorm_f32(L32, g, b, L32o, 1e-5), 0, 8.0 * L32.numel()),
+    ]
+    return ks
+
+
+def _hi_layer(torch, B):
+    """Inference-like layer: hidden 768, seq 128, batch 1, 12 heads x 64, FFN 3072."""
+    S, H, NH, D, F = 128, 768, 12, 64, 3072
+    s = 0.02
+    X = _bf16(torch, (1, S, H), s)
+    Wqkv = _bf16(torch, (1, 3 * H, H), s)
+    QKV = torch.empty((1, S, 3 * H), dtype=torch.int16, device="cuda")
+    Q = _bf16(torch, (NH, S, D), s)
+    Kh = _bf16(torch, (NH, S, D), s)
+    SC = torch.empty((NH, S, S), dtype=torch.int16, device="cuda")
+    P32 = torch.randn((NH * S, S), device="cuda")
+    P32o = torch.empty_like(P32)
+    Pb = _bf16(torch, (NH, S, S), s)
+    Vt = _bf16(torch, (NH, D, S), s)
+    O = torch.empty((NH, S, D), dtype=torch.int16, device="cuda")
+    Wo = _bf16(torch, (1, H, H), s)
+    AO = torch.empty((1, S, H), dtype=torch.int16, device="cuda")
+    L = torch.randn((S, H), device="cuda")
+    Lo = torch.empty_like(L)
+    g = torch.ones(H, device="cuda")
+    b = torch.zeros(H, device="cuda")
+    W1 = _bf16(torch, (1, F, H), s)
+    H1 = torch.empty((1, S, F), dtype=torch.int16, device="cuda")
+    H1in = _bf16(torch, (1, S, F), s)
+    W2 = _bf16(torch, (1, H, F), s)
+    H2 = torch.empty((1, S, H), dtype=torch.int16, device="cuda")
+    torch.cuda.synchronize()
+    return [
+        B.gemm_bf16(X, Wqkv, QKV, small=True), B.gemm_bf16(Q, Kh, SC, small=True),
+        B.softmax_f32(P32, P32o), B.gemm_bf16(Pb, Vt, O, small=True),
+        B.gemm_bf16(X, Wo, AO, small=True), B.layernorm_f32(L, g, b, Lo, 1e-5),
+        B.gemm_bf16(X, W1, H1, small=True), B.gemm_bf16(H1in, W2, H2, small=True),
+        B.layernorm_f32(L, g, b, Lo, 1e-5),
+    ]
+
+
+def _hi_decode(torch, B):
+    s = 0.02
+    x = _bf16(torch, (4096,), s)
+    Wup = _bf16(torch, (11008, 4096), s)
+    yup = torch.empty(11008, dtype=torch.int16, device="cuda")
+    xd = _bf16(torch, (11008,), s)
+    Wdn = _bf16(torch, (4096, 11008), s)
+    ydn = torch.empty(4096, dtype=torch.int16, device="cuda")
+    q = _bf16(torch, (32, 128), s)
+    Kc = _bf16(torch, (2048, 32, 128), s)
+    Vc = _bf16(torch, (2048, 32, 128), s)
+    out = torch.empty((32, 128), dtype=torch.int16, device="cuda")
+    scratch = torch.zeros(B.attn_decode_scratch_bytes(32), dtype=torch.uint8, device="cuda")
+    torch.cuda.synchronize()
+    return [B.attn_decode_bf16(q, Kc, Vc, out, scratch), B.gemv_bf16(x, Wup, yup),
+            B.gemv_bf16(xd, Wdn, ydn)]
+
+
+def _choose_configs(torch, B, ctx, be_stream, step, num_cus):
+    """Per kernel: native time, a few persistent-worker candidates, Eq.-1 selection."""
+    table, items = {}, []
+    for name, k, flops, nbytes in step:
+        nat = _time(torch, B, be_stream, lambda: (ctx.launch_native(k), None)[1], reps=3, warm=1)
+        tot = k.total_blocks
+        if "gemm" in name and k.kernel_id == B.K_GEMM_BF16:
+            cands = [(B.CFG_PTB, num_cus, 1)]
+        elif "gemm" in name:
+            cands = [(B.CFG_PTB, 4 * num_cus, 4), (B.CFG_PTB, 4 * num_cus, 16)]
+        else:
+            cands = [(B.CFG_PTB, 2 * num_cus, 4), (B.CFG_PTB, 4 * num_cus, 2),
+                     (B.CFG_PTB, 2 * num_cus, 16)]
+        meas, chosen = ctx.profile(k, cands, runs=3, threshold_ms=0.0316)
+        c = meas[chosen]
+        ptb = _time(torch, B, be_stream, lambda: ctx.launch_ptb(k, c["param"], chunk=c["chunk"]),
+                    reps=3, warm=1)
+        row = {"blocks": tot, "native_us": nat[0], "ptb_us": ptb[0], "of_native": nat[0] / ptb[0],
+               "workers": c["param"], "chunk": c["chunk"],
+               "eq1_turnaround_us": c["turnaround_ms"] * 1e3}
+        if flops:
+            row["native_TFLOPs"] = flops / nat[0] / 1e6
+            row["ptb_TFLOPs"] = flops / ptb[0] / 1e6
+            row["ptb_mfma_frac"] = row["ptb_TFLOPs"] / PEAK_BF16_TFLOPS
+        if nbytes:
+            row["native_GBps"] = nbytes / nat[0] / 1e3
+            row["ptb_GBps"] = nbytes / ptb[0] / 1e3
+            row["ptb_hbm_frac"] = row["ptb_GBps"] / PEAK_HBM_GBS
+        table[name] = row
+        items.append((k, (B.CFG_PTB, c["param"], c["chunk"])))
+    return table, items
+
+
+def _colocate(torch, B, ctx, be_stream, args, hi, rate, cfg_index, label):
+    import tally_inputs as TI
+    info = B.device_info()
+    step = _be_step(torch, B)
+    table, items = _choose_configs(torch, B, ctx, be_stream, step, info["num_cus"])
+    count = args.steps
+    arrivals = TI.poisson_arrivals_us(rate, count, config_index=cfg_index)
+    dur_us = float(arrivals[-1])
+    solo_hi = ctx.sched_run(hi, arrivals, [])
+    solo_be = ctx.sched_run([], [], items, tail_us=min(dur_us, 3e6))
+    co = ctx.sched_run(hi, arrivals, items, policy=B.POLICY_TALLY)
+    nat_items = [(k, (B.CFG_NATIVE, 1, 1)) for k, _ in items]
+    sub = arrivals[: max(count // 4, 100)]
+    nat = ctx.sched_run(hi, sub, nat_items, policy=B.POLICY_PRIORITY_NATIVE)
+    nos = ctx.sched_run(hi, sub, nat_items, policy=B.POLICY_NONE)
+    w = args.warmup
+    ls, lc = solo_hi["latency_us"][w:], co["latency_us"][w:]
+    tput_solo = solo_be["be_kernels_done"] / solo_be["window_us"]
+    tput_co = co["be_kernels_done"] / co["window_us"]
+    pre = co["preempt_latency_us"]
+    hist, edges = np.histogram(pre, bins=[0, 5, 10, 20, 40, 80, 160, 320, 1e9]) if len(pre) else ([], [])
+    flops = sum(f for _, _, f, _ in step)
+    return {
+        "workload": label,
+        "hi_pri_latency_us": {"solo_p50": pct(ls, 50), "solo_p99": pct(ls, 99),
+                              "coloc_p50": pct(lc, 50), "coloc_p99": pct(lc, 99), "n": len(lc)},
+        "p99_overhead_pct": (pct(lc, 99) - pct(ls, 99)) / pct(ls, 99) * 100.0,
+        "p50_overhead_pct": (pct(lc, 50) - pct(ls, 50)) / pct(ls, 50) * 100.0,
+        "be_tput_retained_pct": tput_co / tput_solo * 100.0,
+        "be_steps_per_s": {"solo": solo_be["be_steps_done"] / solo_be["window_us"] * 1e6,
+                           "coloc": co["be_steps_done"] / co["window_us"] * 1e6},
+        "be_step_TFLOPs_solo": flops * (solo_be["be_steps_done"] / solo_be["window_us"]) / 1e6,
+        "preempt_latency_us": {"n": int(co["n_preempts"]), "p50": pct(pre, 50), "p99": pct(pre, 99),
+                               "histogram_edges_us": [0, 5, 10, 20, 40, 80, 160, 320, "inf"],
+                               "histogram": [int(h) for h in hist]},
+        "decomposition_p99_us": {"ideal": pct(ls, 99), "full": pct(lc, 99),
+                                 "priority_native_be": pct(nat["latency_us"][min(w, 20):], 99),
+                                 "no_scheduling": pct(nos["latency_us"][min(w, 20):], 99)},
+        "be_kernels": table,
+    }
+
+
+def cfg3(torch, B, ctx, be_stream, args):
+    return _colocate(torch, B, ctx, be_stream, args, _hi_layer(torch, B), 100.0, 3,
+                     "cfg3: transformer-layer step (hidden 4096, FFN 16384, seq 2048, batch 8; "
+                     "forward GEMMs + fp32 softmax 2048-wide + LayerNorm 4096) as persistent "
+                     "workers vs a 768-hidden/seq-128 inference layer (9 kernels), Poisson 100/s")
+
+
+def cfg4(torch, B, ctx, be_stream, args):
+    return _colocate(torch, B, ctx, be_stream, args, _hi_decode(torch, B), 200.0, 4,
+                     "cfg4: the cfg3 best-effort step vs decode-like hi-pri kernels (attention "
+                     "over 2048x32x128 bf16 KV, GEMV 11008x4096 and 4096x11008), Poisson 200/s")
+
+
+WORKLOADS = {"cfg0": cfg0, "cfg2": cfg2, "cfg3": cfg3, "cfg4": cfg4}
