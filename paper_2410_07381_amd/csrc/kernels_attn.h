@@ -45,8 +45,7 @@ __global__ __launch_bounds__(256) void attn_decode_partial(tally_attn_decode_arg
   const uint64_t row = (uint64_t)a.heads * kAttnDim;       // elements between tokens
   const uint16_t *Kh = a.K + (uint64_t)h * kAttnDim + sub * 8;
   const uint16_t *Vh = a.V + (uint64_t)h * kAttnDim + sub * 8;
-  float q[8];
-  unpack8(*reinterpret_cast<const uint4 *>(a.q + (uint64_t)h * kAttnDim + sub * 8), q);
+  const uint4 qq = *reinterpret_cast<const uint4 *>(a.q + (uint64_t)h * kAttnDim + sub * 8);
   const float scale = 0.08838834764831845f;                // 1 / sqrt(128)
 
   // pass 1: scores of this workgroup's tokens
@@ -54,10 +53,8 @@ __global__ __launch_bounds__(256) void attn_decode_partial(tally_attn_decode_arg
   for (uint32_t t = wave * 4 + grp; t < chunk; t += 16) {  // uniform trip count per wave
     float s = 0.f;
     if (t < cnt) {
-      float k[8];
-      unpack8(*reinterpret_cast<const uint4 *>(Kh + (uint64_t)(t0 + t) * row), k);
-#pragma unroll
-      for (int e = 0; e < 8; ++e) s = __builtin_fmaf(q[e], k[e], s);
+      const uint4 kk = *reinterpret_cast<const uint4 *>(Kh + (uint64_t)(t0 + t) * row);
+      s = GemvBody::dot8(kk, qq, 0.f);
     }
     s += __shfl_xor(s, 8, kWave);
     s += __shfl_xor(s, 4, kWave);

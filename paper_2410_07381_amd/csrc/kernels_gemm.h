@@ -3,15 +3,21 @@
 // C = A * B with A (m x k) and Bt (n x k) both K-contiguous, so an MFMA operand fragment
 // (8 consecutive bf16 along K) is one 16-byte access for either matrix.  Four 64-lane
 // waves in a 2x2 arrangement each own a 128x128 sub-tile as 4x4 MFMA 32x32x16 blocks
-// (256 fp32 accumulators per lane, which the compiler keeps in accumulation registers).
-// K is walked in steps of 64 through two LDS buffers per operand (128 KB in all).
+// (256 fp32 accumulators per lane, which stay in accumulation registers).
+//
+// K is walked in steps of 32 through a ring of FOUR LDS stages (32 KB each, 128 KB in
+// all): the loads of step i+3 are issued while step i is multiplied, so a tile tolerates
+// about three step-times of memory latency.  With two stages of 64 the kernel spent more
+// than half its time waiting for the next stage (L2/Infinity-Cache latency under load is
+// longer than one step of MFMA work).
 //
 // Global memory goes straight to LDS (16 bytes per lane, no staging registers): a wave
-// load fills 1 KB of LDS contiguously, lane l supplying the 16-byte slot l.  Slot s of a
-// tile holds row s/8, k-chunk (s%8) xor (row%8); the xor makes the 8 lanes that an LDS
-// read serves together fall into 8 different 16-byte bank groups, without padding.  The
-// lane-to-address map of the global side is chosen to produce that layout; it still
-// reads whole 128-byte row segments.
+// load fills 1 KB of LDS contiguously, lane l supplying the 16-byte slot l.  A stage
+// holds 256 rows of 64 bytes; slot s holds row s/4, k-chunk (s%4) xor ((row/4)%4), which
+// makes the 16 lanes that a 128-bit LDS read serves together (64 banks, 256 bytes per
+// clock) fall into 16 different 16-byte bank groups, without padding; with the xor taken
+// from row/2 the bank-conflict counter showed every read served at half rate.  The lane-to-address map of the global side is chosen to
+// produce that layout.
 //
 // Register budget: the arithmetic VGPRs are kept low on purpose so that, with the 256
 // accumulators, a wave stays well under the 512 registers of its SIMD and waves of a
@@ -37,38 +43,56 @@ struct GemmBody {
   static constexpr int THREADS = 256;
   static constexpr int MIN_WAVES = 1;
   static constexpr int TILE = 256;
-  static constexpr int BK = 64;
-  static constexpr int BUF = TILE * BK;                   // one operand buffer, in bf16 (32 KB)
-  static constexpr unsigned DYN_LDS = 4u * BUF * 2u;      // A0 A1 B0 B1 = 128 KB
-  // every k-step ends with a barrier after its LDS reads, so the next tile's first loads
-  // cannot overtake a reader of this tile
+  static constexpr int BK = 32;
+  static constexpr int STAGES = 4;
+  static constexpr int OPB = TILE * BK * 2;               // bytes of one operand in one stage (16 KB)
+  static constexpr unsigned DYN_LDS = 2u * OPB * STAGES;  // 128 KB
+  // every k-step starts with a barrier that follows the LDS reads of the step before, so
+  // the next tile's first loads cannot overtake a reader of this tile
   static constexpr bool END_BARRIER = false;
 
   static __device__ __forceinline__ void run(const Args &a, uint32_t bx, uint32_t by, uint32_t bz) {
     extern __shared__ __align__(1024) unsigned char tally_dyn_lds[];
-    unsigned char *sA = tally_dyn_lds;
-    unsigned char *sB = tally_dyn_lds + 2 * BUF * 2;
+    unsigned char *sA = tally_dyn_lds;                    // STAGES x 16 KB
+    unsigned char *sB = tally_dyn_lds + STAGES * OPB;
 
     const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const uint32_t wm = wave >> 1, wn = wave & 1;
     const uint32_t K = a.k;
 
     // global side of the direct loads: wave w fills rows [64 w, 64 w + 64) of each operand
-    // tile with 8 loads of 8 rows; lane l supplies row l/8, k-chunk (l%8) xor (l/8)
-    const uint32_t ld_row = wave * 64 + (lane >> 3);
-    const uint32_t ld_kc = (lane & 7) ^ (lane >> 3);
-    const uint16_t *pA = a.A + bz * a.stride_a + (uint64_t)(by * TILE + ld_row) * K + ld_kc * 8;
-    const uint16_t *pB = a.Bt + bz * a.stride_b + (uint64_t)(bx * TILE + ld_row) * K + ld_kc * 8;
-    const uint32_t lds_wave = wave * 64 * BK * 2;           // byte offset of the wave's rows
-
-    auto issue_loads = [&](uint32_t kt, uint32_t buf) {
+    // with 4 loads of 16 rows; lane l supplies row l/4, k-chunk (l%4) xor ((l/16)%4).
+    // Addresses are split into a wave-uniform base that advances by 64 bytes per k-step
+    // (scalar registers) and per-lane byte offsets that never change (8 registers), so the
+    // loop spends no vector instructions on address arithmetic.  The four loads of an
+    // operand share one LDS base (M0) and differ by the instruction's immediate offset,
+    // which also moves the global address; the lane offsets compensate for that.
+    const uint32_t ld_row = wave * 64 + (lane >> 2);
+    const uint32_t ld_kc = (lane & 3) ^ ((lane >> 4) & 3);
+    const unsigned char *uA =
+        reinterpret_cast<const unsigned char *>(a.A + bz * a.stride_a + (uint64_t)(by * TILE) * K);
+    const unsigned char *uB =
+        reinterpret_cast<const unsigned char *>(a.Bt + bz * a.stride_b + (uint64_t)(bx * TILE) * K);
+    uint32_t voff[4];
 #pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        __builtin_amdgcn_global_load_lds((gptr_t)(pA + (uint64_t)(8 * j) * K + kt * BK),
-                                         (lptr_t)(sA + buf * BUF * 2 + lds_wave + j * 1024), 16, 0, 0);
-        __builtin_amdgcn_global_load_lds((gptr_t)(pB + (uint64_t)(8 * j) * K + kt * BK),
-                                         (lptr_t)(sB + buf * BUF * 2 + lds_wave + j * 1024), 16, 0, 0);
-      }
+    for (int j = 0; j < 4; ++j)
+      voff[j] = ((ld_row + 16 * j) * K + ld_kc * 8) * 2 - j * 1024;
+    const uint32_t lds_wave = wave * 64 * BK * 2;         // byte offset of the wave's rows
+
+    auto issue_loads = [&](uint32_t kt) {
+      const uint32_t st = kt & (STAGES - 1);
+      const unsigned char *gA = uA + (uint64_t)kt * (BK * 2);
+      const unsigned char *gB = uB + (uint64_t)kt * (BK * 2);
+      lptr_t lA = (lptr_t)(sA + st * OPB + lds_wave);
+      lptr_t lB = (lptr_t)(sB + st * OPB + lds_wave);
+      __builtin_amdgcn_global_load_lds((gptr_t)(gA + voff[0]), lA, 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((gptr_t)(gA + voff[1]), lA, 16, 1024, 0);
+      __builtin_amdgcn_global_load_lds((gptr_t)(gA + voff[2]), lA, 16, 2048, 0);
+      __builtin_amdgcn_global_load_lds((gptr_t)(gA + voff[3]), lA, 16, 3072, 0);
+      __builtin_amdgcn_global_load_lds((gptr_t)(gB + voff[0]), lB, 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((gptr_t)(gB + voff[1]), lB, 16, 1024, 0);
+      __builtin_amdgcn_global_load_lds((gptr_t)(gB + voff[2]), lB, 16, 2048, 0);
+      __builtin_amdgcn_global_load_lds((gptr_t)(gB + voff[3]), lB, 16, 3072, 0);
     };
 
     f32x16_t acc[4][4];
@@ -80,40 +104,96 @@ struct GemmBody {
         for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
     const uint32_t nk = K / BK;
-    issue_loads(0, 0);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    // a previous tile's waves may still be reading its last stage: fence them off before
+    // refilling the ring
     __syncthreads();
+    issue_loads(0);
+    if (nk > 1) issue_loads(1);
+    if (nk > 2) issue_loads(2);
 
-    // fragment reads: lane l takes row (l%32) of a 32-row block and k-chunk 2 ks + l/32;
-    // (row % 8) == (l % 8) because every 32-row block starts on a multiple of 8
-    const uint32_t f_row = lane & 31, f_half = lane >> 5, f_x = lane & 7;
+    // fragment reads: lane l takes row (l%32) of a 32-row block and k-chunk 2 ks + l/32
+    const uint32_t f_row = lane & 31, f_half = lane >> 5, f_x = (lane >> 2) & 3;
     const uint32_t fA = (wm * 128 + f_row) * (BK * 2);
     const uint32_t fB = (wn * 128 + f_row) * (BK * 2);
-    for (uint32_t kt = 0; kt < nk; ++kt) {
-      const uint32_t buf = kt & 1;
-      if (kt + 1 < nk) issue_loads(kt + 1, buf ^ 1);
-      const unsigned char *cA = sA + buf * BUF * 2 + fA;
-      const unsigned char *cB = sB + buf * BUF * 2 + fB;
+    const uint32_t koff0 = ((0u + f_half) ^ f_x) * 16, koff1 = ((2u + f_half) ^ f_x) * 16;
+
+    // Two fragment sets: the LDS reads of the next half-step are issued before the MFMAs of
+    // the current one, so the matrix pipe (one wave per SIMD, nothing else to switch to)
+    // does not sit idle for an LDS round trip sixteen MFMAs at a time.
+    bf16x8_t fa0[4], fb0[4], fa1[4], fb1[4];
+    auto lfrag = [&](bf16x8_t(&fa)[4], bf16x8_t(&fb)[4], uint32_t kt, uint32_t koff) {
+      const unsigned char *cA = sA + (kt & (STAGES - 1)) * OPB + fA + koff;
+      const unsigned char *cB = sB + (kt & (STAGES - 1)) * OPB + fB + koff;
 #pragma unroll
-      for (int ks = 0; ks < BK / 16; ++ks) {
-        const uint32_t koff = ((uint32_t)(2 * ks + f_half) ^ f_x) * 16;
-        bf16x8_t fa[4], fb[4];
-#pragma unroll
-        for (int t = 0; t < 4; ++t) {
-          fa[t] = *reinterpret_cast<const bf16x8_t *>(cA + t * 32 * BK * 2 + koff);
-          fb[t] = *reinterpret_cast<const bf16x8_t *>(cB + t * 32 * BK * 2 + koff);
-        }
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-          for (int j = 0; j < 4; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+      for (int t = 0; t < 4; ++t) {
+        fa[t] = *reinterpret_cast<const bf16x8_t *>(cA + t * 32 * BK * 2);
+        fb[t] = *reinterpret_cast<const bf16x8_t *>(cB + t * 32 * BK * 2);
       }
-      // the other buffer must be completely written, and this one completely read,
-      // before the next step swaps them
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-      __syncthreads();
+    };
+    auto mma = [&](const bf16x8_t(&fa)[4], const bf16x8_t(&fb)[4]) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+    };
+
+    // stage 0 has landed once only the two younger stages (8 loads each) are in flight
+    if (nk > 2) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+    else if (nk > 1) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    lfrag(fa0, fb0, 0, koff0);
+    lfrag(fa1, fb1, 0, koff1);
+    __builtin_amdgcn_sched_barrier(0);
+    mma(fa0, fb0);
+    __builtin_amdgcn_sched_barrier(0);
+    // Loop invariant at the top of iteration kt: the MFMAs of (kt, first half) are issued,
+    // set 1 holds (kt, second half).  An iteration opens with the barrier, so the one wait
+    // the compiler places conservatively (at a loop header) coincides with the wait a
+    // barrier needs anyway; all other waits sit inside a basic block and name exactly the
+    // reads they need.  The scheduling fences keep the early reads from being sunk back
+    // down to their first use.
+    uint32_t kt = 0;
+    // steady state: stages kt+1 and kt+2 are in flight, stage kt+3 is issued here
+    for (; kt + 3 < nk; ++kt) {
+      asm volatile("s_waitcnt vmcnt(8)" ::: "memory");  // stage kt+1 complete, kt+2 in flight
+      __syncthreads();  // stage kt+1 is in LDS for everyone; everyone is done with kt-1
+      issue_loads(kt + 3);
+      lfrag(fa0, fb0, kt + 1, koff0);
+      __builtin_amdgcn_sched_barrier(0);
+      mma(fa1, fb1);
+      __builtin_amdgcn_sched_barrier(0);
+      // set 0 was read sixteen MFMAs ago: waiting for it here, before the next reads are
+      // issued, is free, whereas the compiler's own wait in front of the MFMAs below would
+      // also cover the reads issued just above them
+      __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
+      lfrag(fa1, fb1, kt + 1, koff1);
+      __builtin_amdgcn_sched_barrier(0);
+      mma(fa0, fb0);
+      __builtin_amdgcn_sched_barrier(0);
     }
+    // the last steps drain the ring
+    for (; kt + 1 < nk; ++kt) {
+      if (kt + 2 < nk) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+      else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      __syncthreads();
+      lfrag(fa0, fb0, kt + 1, koff0);
+      __builtin_amdgcn_sched_barrier(0);
+      mma(fa1, fb1);
+      __builtin_amdgcn_sched_barrier(0);
+      lfrag(fa1, fb1, kt + 1, koff1);
+      __builtin_amdgcn_sched_barrier(0);
+      mma(fa0, fb0);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    mma(fa1, fb1);
+    // The accumulators are read below through inline assembly, which the compiler's
+    // hazard recogniser cannot see into: keep the last MFMAs from being interleaved with
+    // those reads and give the matrix pipe time to retire its last results first.
+    __builtin_amdgcn_sched_barrier(0);
+    asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
 
     // epilogue: lane l, register r of a 32x32 block holds row 8 (r/4) + 4 (l/32) + r%4,
     // column l%32

@@ -12,6 +12,7 @@ namespace tally {
 
 constexpr int kThreads = 256;
 constexpr int kWave = 64;
+typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2_t;
 
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
@@ -100,18 +101,21 @@ struct ReduceFinalBody {
 struct GemvBody {
   using Args = tally_gemv_bf16_args;
   static constexpr int THREADS = kThreads;
-  static constexpr int MIN_WAVES = 4;
+  static constexpr int MIN_WAVES = 8;   // <= 64 registers: two waves fit beside a GEMM tile
   static constexpr unsigned DYN_LDS = 0;
   static constexpr bool END_BARRIER = false;
-  static __device__ __forceinline__ float dot8(uint4 w, uint4 x) {
-    float s = bf16_lo(w.x) * bf16_lo(x.x);
-    s = __builtin_fmaf(bf16_hi(w.x), bf16_hi(x.x), s);
-    s = __builtin_fmaf(bf16_lo(w.y), bf16_lo(x.y), s);
-    s = __builtin_fmaf(bf16_hi(w.y), bf16_hi(x.y), s);
-    s = __builtin_fmaf(bf16_lo(w.z), bf16_lo(x.z), s);
-    s = __builtin_fmaf(bf16_hi(w.z), bf16_hi(x.z), s);
-    s = __builtin_fmaf(bf16_lo(w.w), bf16_lo(x.w), s);
-    s = __builtin_fmaf(bf16_hi(w.w), bf16_hi(x.w), s);
+  // 8 bf16 products per 16-byte pair with four packed dot-product instructions (fp32
+  // accumulate): a sixth of the vector-ALU work of unpack + fma, which matters because
+  // a high-priority GEMV may share its SIMDs with a best-effort GEMM's MFMA stream
+  static __device__ __forceinline__ float dot8(uint4 w, uint4 x, float s) {
+    s = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, w.x),
+                                        __builtin_bit_cast(bf16x2_t, x.x), s, false);
+    s = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, w.y),
+                                        __builtin_bit_cast(bf16x2_t, x.y), s, false);
+    s = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, w.z),
+                                        __builtin_bit_cast(bf16x2_t, x.z), s, false);
+    s = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, w.w),
+                                        __builtin_bit_cast(bf16x2_t, x.w), s, false);
     return s;
   }
   static __device__ __forceinline__ void run(const Args &a, uint32_t bx, uint32_t, uint32_t) {
@@ -125,12 +129,12 @@ struct GemvBody {
     uint32_t v = lane;
     for (; v + 3 * kWave < nvec; v += 4 * kWave) {
       uint4 w0 = w[v], w1 = w[v + kWave], w2 = w[v + 2 * kWave], w3 = w[v + 3 * kWave];
-      acc0 += dot8(w0, x[v]);
-      acc1 += dot8(w1, x[v + kWave]);
-      acc2 += dot8(w2, x[v + 2 * kWave]);
-      acc3 += dot8(w3, x[v + 3 * kWave]);
+      acc0 = dot8(w0, x[v], acc0);
+      acc1 = dot8(w1, x[v + kWave], acc1);
+      acc2 = dot8(w2, x[v + 2 * kWave], acc2);
+      acc3 = dot8(w3, x[v + 3 * kWave], acc3);
     }
-    for (; v < nvec; v += kWave) acc0 += dot8(w[v], x[v]);
+    for (; v < nvec; v += kWave) acc0 = dot8(w[v], x[v], acc0);
     float s = wave_sum((acc0 + acc1) + (acc2 + acc3));
     if (lane == 0) a.y[row] = f32_to_bf16(s);
   }

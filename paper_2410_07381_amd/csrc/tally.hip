@@ -142,7 +142,7 @@ int grid_gemm(const void *p, tally_dim3 *g, tally_dim3 *b) {
   auto *a = static_cast<const tally_gemm_bf16_args *>(p);
   int rc = grid_gemm_common(a);
   if (rc) return rc;
-  if ((a->m % 256) || (a->n % 256) || (a->k % 64)) return TALLY_ERR_INVALID_ARG;
+  if ((a->m % 256) || (a->n % 256) || (a->k % 32)) return TALLY_ERR_INVALID_ARG;
   *g = {a->n / 256, a->m / 256, a->batch};
   *b = kBlock256;
   return TALLY_OK;
