@@ -251,7 +251,7 @@ def _choose_configs(torch, B, ctx, be_stream, step, num_cus):
         if "gemm" in name and k.kernel_id == B.K_GEMM_BF16:
             cands = [(B.CFG_PTB, num_cus, 1)]
         elif "gemm" in name:
-            cands = [(B.CFG_PTB, 4 * num_cus, 4), (B.CFG_PTB, 4 * num_cus, 16)]
+            cands = [(B.CFG_PTB, 4 * num_cus, 1), (B.CFG_PTB, 4 * num_cus, 4)]
         else:
             cands = [(B.CFG_PTB, 2 * num_cus, 4), (B.CFG_PTB, 4 * num_cus, 2),
                      (B.CFG_PTB, 2 * num_cus, 16)]

@@ -167,9 +167,20 @@ int tally_launch_ptb(tally_ctx *ctx, const tally_kernel_desc *desc, uint32_t num
 int tally_preempt(tally_job *job);
 
 /* Continue a STOPPED job from its saved task counter / block offset (Section 4.1:
- * progress is held in the global task index).  BAD_STATE while RUNNING; no-op when
- * COMPLETE. */
+ * progress is held in the global task index).  On a persistent-worker job that is
+ * still RUNNING with a preemption request raised, the request is withdrawn instead
+ * (workers pausing inside a long block go on; see tally_set_yield_bound_us).  Otherwise
+ * BAD_STATE while RUNNING; no-op when COMPLETE. */
 int tally_resume(tally_job *job);
+
+/* Extension for blocks that last far longer than the turnaround threshold (a 256x256
+ * GEMM tile over a long K): while a preemption request stands, workers of such kernels
+ * pause INSIDE the block, keeping their registers and LDS, for at most `us`
+ * microseconds (default 1000; 0 disables), so that the high-priority kernel runs beside
+ * them undisturbed.  Workers between blocks still exit as in Section 4.1.  The bound
+ * keeps a high-priority kernel that does not fit beside the paused workers from waiting
+ * for ever. */
+int tally_set_yield_bound_us(tally_ctx *ctx, uint32_t us);
 
 /* Non-blocking snapshot.  done_blocks = min(counter, total) as last published by the
  * device; exact once the job is STOPPED or COMPLETE.  Any out pointer may be null. */

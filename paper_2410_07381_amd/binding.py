@@ -30,7 +30,7 @@ EXPORTS = [
     "tally_launch_ptb_until", "tally_resume_until", "tally_coverage", "tally_marker",
     "tally_marker_read", "tally_last_preempt_latency_us", "tally_last_hip_error",
     "tally_strerror", "tally_device_info", "tally_ptb_turnaround_ms", "tally_select_config",
-    "tally_profile", "tally_lookup_config", "tally_sched_run",
+    "tally_profile", "tally_lookup_config", "tally_sched_run", "tally_set_yield_bound_us",
 ]
 
 
@@ -155,6 +155,7 @@ def _load():
         "tally_profile": ([vp, P(KernelDesc), P(Config), u32, u32, dbl, P(u32)], i32),
         "tally_lookup_config": ([vp, P(KernelDesc), P(Config)], i32),
         "tally_sched_run": ([vp, P(SchedRun)], i32),
+        "tally_set_yield_bound_us": ([vp, u32], i32),
     }
     for name, (argtypes, restype) in sig.items():
         fn = getattr(lib, name)
@@ -344,6 +345,9 @@ class Context:
                                                int(stop_at), int(coverage), C.byref(j)),
                    "tally_launch_ptb_until")
         return Job(j, kernel)
+
+    def set_yield_bound_us(self, us):
+        _check(_lib.tally_set_yield_bound_us(self.h, int(us)), "tally_set_yield_bound_us")
 
     def marker(self, value, hi=True):
         _check(_lib.tally_marker(self.h, 1 if hi else 0, value), "tally_marker")

@@ -28,6 +28,7 @@
 
 #include "../../include/tally.h"
 #include "kernels_stream.h"
+#include "launch_forms.h"
 
 namespace tally {
 
@@ -50,8 +51,15 @@ struct GemmBody {
   // every k-step starts with a barrier that follows the LDS reads of the step before, so
   // the next tile's first loads cannot overtake a reader of this tile
   static constexpr bool END_BARRIER = false;
+  static constexpr bool YIELDS = true;
+  static constexpr uint32_t YIELD_EVERY = 16;             // k-steps between flag checks (~10 us)
 
   static __device__ __forceinline__ void run(const Args &a, uint32_t bx, uint32_t by, uint32_t bz) {
+    run_yielding(a, bx, by, bz, YieldCtl{nullptr, 0, 0});
+  }
+
+  static __device__ __forceinline__ void run_yielding(const Args &a, uint32_t bx, uint32_t by,
+                                                      uint32_t bz, const YieldCtl ctl) {
     extern __shared__ __align__(1024) unsigned char tally_dyn_lds[];
     unsigned char *sA = tally_dyn_lds;                    // STAGES x 16 KB
     unsigned char *sB = tally_dyn_lds + STAGES * OPB;
@@ -157,6 +165,9 @@ struct GemmBody {
     uint32_t kt = 0;
     // steady state: stages kt+1 and kt+2 are in flight, stage kt+3 is issued here
     for (; kt + 3 < nk; ++kt) {
+      // one wave polls; the others meet it at the barrier below
+      if (ctl.ticks != 0 && wave == 0 && (kt & (YIELD_EVERY - 1)) == YIELD_EVERY - 1)
+        yield_while_preempted(ctl);
       asm volatile("s_waitcnt vmcnt(8)" ::: "memory");  // stage kt+1 complete, kt+2 in flight
       __syncthreads();  // stage kt+1 is in LDS for everyone; everyone is done with kt-1
       issue_loads(kt + 3);
@@ -227,6 +238,7 @@ struct GemmSmallBody {
   static constexpr int MIN_WAVES = 2;
   static constexpr int TILE = 64;
   static constexpr unsigned DYN_LDS = 0;
+  static constexpr bool YIELDS = false;
   static constexpr bool END_BARRIER = false;
 
   static __device__ __forceinline__ void run(const Args &a, uint32_t bx, uint32_t by, uint32_t bz) {
@@ -242,9 +254,26 @@ struct GemmSmallBody {
 #pragma unroll
     for (int r = 0; r < 16; ++r) { acc0[r] = 0.f; acc1[r] = 0.f; }
     const uint4 zero = make_uint4(0, 0, 0, 0);
-    // operands straight from global/L2: each 16-byte fragment is used by this wave only
-    // once per k step, and the 2x2 waves of a block share rows through the L1
-    for (uint32_t k0 = 0; k0 < K; k0 += 32) {
+    // operands straight from global/L2 (the 2x2 waves of a block share rows through the
+    // L1).  The loop is latency-bound, so 128 elements of K (eight 16-byte loads per
+    // operand) are requested before the first of their MFMAs is issued.
+    uint32_t k0 = 0;
+    for (; k0 + 128 <= K; k0 += 128) {
+      uint4 av[8], bv[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        av[u] = aok ? *reinterpret_cast<const uint4 *>(pA + k0 + 16 * u) : zero;
+        bv[u] = bok ? *reinterpret_cast<const uint4 *>(pB + k0 + 16 * u) : zero;
+      }
+#pragma unroll
+      for (int u = 0; u < 8; u += 2) {
+        acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, av[u]),
+                                                       __builtin_bit_cast(bf16x8_t, bv[u]), acc0, 0, 0, 0);
+        acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, av[u + 1]),
+                                                       __builtin_bit_cast(bf16x8_t, bv[u + 1]), acc1, 0, 0, 0);
+      }
+    }
+    for (; k0 < K; k0 += 32) {
       uint4 a0 = aok ? *reinterpret_cast<const uint4 *>(pA + k0) : zero;
       uint4 b0 = bok ? *reinterpret_cast<const uint4 *>(pB + k0) : zero;
       uint4 a1 = aok ? *reinterpret_cast<const uint4 *>(pA + k0 + 16) : zero;

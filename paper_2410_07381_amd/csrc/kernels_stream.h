@@ -38,6 +38,7 @@ struct SaxpyBody {
   static constexpr int THREADS = kThreads;
   static constexpr int MIN_WAVES = 4;
   static constexpr unsigned DYN_LDS = 0;
+  static constexpr bool YIELDS = false;
   static constexpr bool END_BARRIER = false;
   static __device__ __forceinline__ void run(const Args &a, uint32_t bx, uint32_t, uint32_t) {
     uint32_t i = bx * kThreads + threadIdx.x;
@@ -51,6 +52,7 @@ struct ReduceSumBody {
   static constexpr int THREADS = kThreads;
   static constexpr int MIN_WAVES = 4;
   static constexpr unsigned DYN_LDS = 0;
+  static constexpr bool YIELDS = false;
   static constexpr bool END_BARRIER = false;
   static constexpr uint32_t PER_BLOCK = 4096;
   static __device__ __forceinline__ void run(const Args &a, uint32_t bx, uint32_t, uint32_t) {
@@ -82,6 +84,7 @@ struct ReduceFinalBody {
   static constexpr int THREADS = kThreads;
   static constexpr int MIN_WAVES = 4;
   static constexpr unsigned DYN_LDS = 0;
+  static constexpr bool YIELDS = false;
   static constexpr bool END_BARRIER = true;   // s_d is reused by the next block
   static __device__ __forceinline__ void run(const Args &a, uint32_t, uint32_t, uint32_t) {
     __shared__ double s_d[kThreads];
@@ -103,6 +106,7 @@ struct GemvBody {
   static constexpr int THREADS = kThreads;
   static constexpr int MIN_WAVES = 8;   // <= 64 registers: two waves fit beside a GEMM tile
   static constexpr unsigned DYN_LDS = 0;
+  static constexpr bool YIELDS = false;
   static constexpr bool END_BARRIER = false;
   // 8 bf16 products per 16-byte pair with four packed dot-product instructions (fp32
   // accumulate): a sixth of the vector-ALU work of unpack + fma, which matters because
@@ -208,6 +212,7 @@ struct SoftmaxBody {
   static constexpr int THREADS = kThreads;
   static constexpr int MIN_WAVES = 4;
   static constexpr unsigned DYN_LDS = 0;
+  static constexpr bool YIELDS = false;
   static constexpr bool END_BARRIER = false;
   static __device__ __forceinline__ void run(const Args &a, uint32_t bx, uint32_t, uint32_t) {
     const uint32_t lane = threadIdx.x & (kWave - 1);
@@ -291,6 +296,7 @@ struct LayerNormBody {
   static constexpr int THREADS = kThreads;
   static constexpr int MIN_WAVES = 2;
   static constexpr unsigned DYN_LDS = 0;
+  static constexpr bool YIELDS = false;
   static constexpr bool END_BARRIER = false;
   static __device__ __forceinline__ void run(const Args &a, uint32_t bx, uint32_t, uint32_t) {
     const uint32_t lane = threadIdx.x & (kWave - 1);

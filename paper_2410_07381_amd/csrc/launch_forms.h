@@ -7,6 +7,8 @@
 //   static constexpr unsigned DYN_LDS;       dynamic LDS bytes the body needs
 //   static constexpr bool END_BARRIER;       true if consecutive blocks run by one workgroup
 //                                            would race on workgroup-shared state
+//   static constexpr bool YIELDS;            true if the body offers run_yielding(), which
+//                                            pauses inside the block while preempted
 //   static __device__ void run(const Args&, uint32_t bx, uint32_t by, uint32_t bz);
 // run() performs the work of original block (bx,by,bz); every thread of the workgroup
 // calls it and returns from it (no early exit), so the workgroup-wide barriers of the
@@ -42,7 +44,13 @@ struct PtbCtl {
   uint32_t chunk;           // task indices per fetch
   uint32_t segment;         // 0-based segment number, for the coverage records
   uint32_t gx, gy;          // logical grid extents (x fastest)
+  uint32_t yield_ticks;     // longest pause inside a block, in 10 ns wall-clock ticks (0: never)
+  uint32_t *flag_copies;    // device: kFlagCopies copies of dev_flag[0], 128 B apart, for the
+                            // mid-block polls (one address serves only ~80 M coherent scalar
+                            // loads per second, whoever asks)
 };
+constexpr uint32_t kFlagCopies = 64;
+constexpr uint32_t kFlagCopyStride = 32;  // in 32-bit words
 
 struct SliceCtl {
   tally_cover_rec *cover;
@@ -116,12 +124,18 @@ __device__ __forceinline__ uint32_t scalar_load_coherent(const uint32_t *p) {
 }
 
 __global__ __launch_bounds__(64) void relay_kernel(PtbCtl c) {
+  uint32_t last = 0xFFFFFFFFu;
   for (uint32_t n = 0;; ++n) {
+    // forward every change of the host's word: a request (the segment's epoch) and, later,
+    // its withdrawal, which lets workers that paused inside a long block carry on
     uint32_t want = scalar_load_coherent(c.host_flag);
-    if (want == c.epoch) {
+    if (want != last) {
       if (threadIdx.x == 0)
-        __hip_atomic_store(c.dev_flag, c.epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      return;
+        __hip_atomic_store(c.dev_flag, want, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (c.flag_copies != nullptr && threadIdx.x < kFlagCopies)
+        __hip_atomic_store(c.flag_copies + threadIdx.x * kFlagCopyStride, want, __ATOMIC_RELAXED,
+                           __HIP_MEMORY_SCOPE_AGENT);
+      last = want;
     }
     // the counters of a slot only ever grow (they are never reset), so a relay that
     // starts late, even after its workers are long gone, still sees the target passed
@@ -136,6 +150,26 @@ __global__ __launch_bounds__(64) void relay_kernel(PtbCtl c) {
                            __HIP_MEMORY_SCOPE_SYSTEM);
     }
   }
+}
+
+// Pause inside a long block while a preemption request stands.  Block-level preemption
+// cannot act before the end of the running block; a block that lasts hundreds of
+// microseconds (a 256x256 GEMM tile over a long K) would keep competing with the
+// high-priority kernel for memory bandwidth and issue slots all that time.  Such a body
+// calls this every few steps: the wave sleeps, holding its registers and LDS (the
+// high-priority kernel runs beside it), until the request is withdrawn or `yield_ticks`
+// have passed, so a high-priority kernel that does NOT fit beside it cannot deadlock.
+struct YieldCtl {          // passed by value: taking the address of the kernel's control
+  const uint32_t *flag;    // block would force it out of scalar registers into memory
+  uint32_t epoch, ticks;
+};
+__device__ __forceinline__ void yield_while_preempted(const YieldCtl &y) {
+  if (scalar_load_coherent(y.flag) != y.epoch) return;
+  const unsigned long long t0 = wall_clock64();
+  do {
+    __builtin_amdgcn_s_sleep(64);
+  } while (scalar_load_coherent(y.flag) == y.epoch &&
+           wall_clock64() - t0 < (unsigned long long)y.ticks);
 }
 
 template <class Body>
@@ -171,7 +205,12 @@ __device__ __forceinline__ void ptb_body(const typename Body::Args &args, const 
     for (uint32_t idx = first; idx < last; ++idx) {
       uint32_t bx, by, bz;
       delinearize(idx, c.gx, c.gy, bx, by, bz);
-      Body::run(args, bx, by, bz);
+      if constexpr (Body::YIELDS)
+        Body::run_yielding(args, bx, by, bz,
+                           YieldCtl{c.flag_copies + (worker % kFlagCopies) * kFlagCopyStride, c.epoch,
+                                    c.flag_copies != nullptr ? c.yield_ticks : 0u});
+      else
+        Body::run(args, bx, by, bz);
       record(c.cover, idx, bx, by, bz, c.segment, worker);
       // the paper ends every iteration with a barrier so that a worker handles one block
       // at a time; a body whose waves share no state across blocks does not need it

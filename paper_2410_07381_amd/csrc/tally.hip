@@ -215,6 +215,7 @@ constexpr size_t kMaxArgs = 96;
 constexpr int kSlots = 64;
 constexpr size_t kDevSlotBytes = 512;   // counter | dev_flag | exited, 128 B apart
 constexpr size_t kHostSlotBytes = 256;  // host_flag | status,live | slice_done
+constexpr size_t kCopySlotBytes = kFlagCopies * kFlagCopyStride * sizeof(uint32_t);
 
 enum JobKind { KIND_PTB = 0, KIND_SLICED = 1, KIND_NATIVE = 2 };
 
@@ -224,6 +225,7 @@ struct tally_ctx {
   hipStream_t hi, be;
   hipStream_t ctl;           // owned: carries the relay kernels, default priority
   unsigned char *dev_pool;   // device
+  uint32_t *copy_pool;       // device: per slot, kFlagCopies copies of the flag word
   unsigned char *host_pool;  // pinned host
   unsigned char *host_pool_dev;
   bool slot_used[kSlots];
@@ -233,6 +235,7 @@ struct tally_ctx {
   uint32_t *marker_host;     // pinned: [0] hi, [32] be (separate lines)
   uint32_t *marker_dev;
   uint32_t num_cus;
+  uint32_t yield_ticks;      // bound of a mid-block pause, 10 ns ticks
   int device;
   int live_jobs;
   std::map<std::tuple<uint32_t, uint32_t, uint32_t, uint32_t, uint32_t>, tally_config> chosen;
@@ -375,6 +378,8 @@ int ptb_launch_segment(tally_job *j, uint32_t limit) {
   c.segment = j->segments;
   c.gx = j->grid.x;
   c.gy = j->grid.y;
+  c.yield_ticks = ctx->yield_ticks;
+  c.flag_copies = ctx->copy_pool + (size_t)slot * (kCopySlotBytes / sizeof(uint32_t));
   hipError_t e = j->ops->ptb(ctx->be, j->args, c);
   if (e != hipSuccess) {  // nothing was enqueued: the slot's bookkeeping is unchanged
     g_last_hip = (int)e;
@@ -470,6 +475,7 @@ int tally_create(tally_ctx **out, void *hip_stream_hi, void *hip_stream_be) {
   c->be = (hipStream_t)hip_stream_be;
   c->ctl = nullptr;
   c->dev_pool = nullptr;
+  c->copy_pool = nullptr;
   c->host_pool = nullptr;
   c->marker_host = nullptr;
   memset(c->slot_used, 0, sizeof(c->slot_used));
@@ -485,6 +491,8 @@ int tally_create(tally_ctx **out, void *hip_stream_hi, void *hip_stream_be) {
       (e = hipStreamCreateWithFlags(&c->ctl, hipStreamNonBlocking)) != hipSuccess ||
       (e = hipMalloc((void **)&c->dev_pool, kSlots * kDevSlotBytes)) != hipSuccess ||
       (e = hipMemset(c->dev_pool, 0, kSlots * kDevSlotBytes)) != hipSuccess ||
+      (e = hipMalloc((void **)&c->copy_pool, kSlots * kCopySlotBytes)) != hipSuccess ||
+      (e = hipMemset(c->copy_pool, 0, kSlots * kCopySlotBytes)) != hipSuccess ||
       (e = hipHostMalloc((void **)&c->host_pool, kSlots * kHostSlotBytes, hipHostMallocDefault)) != hipSuccess ||
       (e = hipHostGetDevicePointer((void **)&c->host_pool_dev, c->host_pool, 0)) != hipSuccess ||
       (e = hipHostMalloc((void **)&c->marker_host, 256, hipHostMallocDefault)) != hipSuccess ||
@@ -492,6 +500,7 @@ int tally_create(tally_ctx **out, void *hip_stream_hi, void *hip_stream_be) {
     g_last_hip = (int)e;
     if (c->ctl) (void)hipStreamDestroy(c->ctl);
     if (c->dev_pool) (void)hipFree(c->dev_pool);
+    if (c->copy_pool) (void)hipFree(c->copy_pool);
     if (c->host_pool) (void)hipHostFree(c->host_pool);
     if (c->marker_host) (void)hipHostFree(c->marker_host);
     delete c;
@@ -500,6 +509,7 @@ int tally_create(tally_ctx **out, void *hip_stream_hi, void *hip_stream_be) {
   memset(c->host_pool, 0, kSlots * kHostSlotBytes);
   memset(c->marker_host, 0, 256);
   c->num_cus = (uint32_t)prop.multiProcessorCount;
+  c->yield_ticks = 100000;  // 1 ms
   c->device = dev;
   for (int k = 0; k < TALLY_K_COUNT; ++k)
     if (kOps[k].init && (e = kOps[k].init()) != hipSuccess) {
@@ -524,6 +534,7 @@ int tally_destroy(tally_ctx *ctx) {
   (void)hipStreamSynchronize(ctx->ctl);
   (void)hipStreamDestroy(ctx->ctl);
   (void)hipFree(ctx->dev_pool);
+  (void)hipFree(ctx->copy_pool);
   (void)hipHostFree(ctx->host_pool);
   (void)hipHostFree(ctx->marker_host);
   delete ctx;
@@ -605,6 +616,13 @@ int tally_resume_until(tally_job *job, uint64_t stop_at) {
   refresh(job);
   int st = job->state.load();
   if (st == TALLY_JOB_COMPLETE) return TALLY_OK;
+  if (st == TALLY_JOB_RUNNING && job->kind == KIND_PTB && job->t_preempt.load() != 0.0) {
+    // requested but not drained yet: withdraw the request; workers pausing inside a
+    // block go on, those that already left stay away until the next launch segment
+    __atomic_store_n(job->h_flag(), 0u, __ATOMIC_RELEASE);
+    job->t_preempt = 0.0;
+    return TALLY_OK;
+  }
   if (st != TALLY_JOB_STOPPED) return TALLY_ERR_BAD_STATE;
   if (job->kind == KIND_PTB) {
     if (stop_at < job->progress.load()) return TALLY_ERR_INVALID_ARG;
@@ -704,6 +722,12 @@ int tally_marker_read(tally_ctx *ctx, int on_hi_stream, uint32_t *value) {
 int tally_last_preempt_latency_us(tally_job *job, double *us) {
   if (!job || !us) return TALLY_ERR_INVALID_ARG;
   *us = job->preempt_latency_us;
+  return TALLY_OK;
+}
+
+int tally_set_yield_bound_us(tally_ctx *ctx, uint32_t us) {
+  if (!ctx || us > 1000000u) return TALLY_ERR_INVALID_ARG;
+  ctx->yield_ticks = us * 100u;
   return TALLY_OK;
 }
 
@@ -897,6 +921,12 @@ void be_thread_main(tally_ctx *ctx, tally_sched_run_t *run, SchedShared *sh, dou
       refresh(be);
       int st = be->state.load();
       if (st != TALLY_JOB_RUNNING) publish(nullptr);
+      if (st == TALLY_JOB_RUNNING && !hold && preempt_seen && be->kind == KIND_PTB) {
+        // the request is over and the job has not drained (its workers sit inside long
+        // blocks, pausing): withdraw the flag instead of waiting for a drain and relaunch
+        (void)tally_resume(be);
+        preempt_seen = false;
+      }
       if (st == TALLY_JOB_COMPLETE) {
         tally_job_free(be);
         be = nullptr;
@@ -995,6 +1025,7 @@ extern "C" int tally_sched_run(tally_ctx *ctx, tally_sched_run_t *run) {
   // ---- high-priority client (this thread) ----------------------------------------------
   uint32_t next_arrival = 0, cur = 0, completed = 0;
   bool inflight = false;
+  uint64_t raised_tok = kNoToken;
   while (rc == TALLY_OK && sh.rc.load() == TALLY_OK) {
     const double now = now_us() - t0;
     if (inflight) {
@@ -1004,9 +1035,17 @@ extern "C" int tally_sched_run(tally_ctx *ctx, tally_sched_run_t *run) {
         run->latency_us[cur] = (now_us() - t0) - run->arrivals_us[cur];
         inflight = false;
         completed++;
-        // a queued request keeps the best-effort client held; otherwise release it
-        if (!(next_arrival < run->n_arrivals && run->arrivals_us[next_arrival] <= now))
+        // a queued request keeps the best-effort client held; otherwise release it and
+        // withdraw the request, so that workers pausing inside a block carry on at once
+        if (!(next_arrival < run->n_arrivals && run->arrivals_us[next_arrival] <= now)) {
+          if (raised_tok != kNoToken) {
+            uint32_t slot = (uint32_t)(raised_tok >> 32) - 1;
+            __atomic_store_n((uint32_t *)(ctx->host_pool + slot * kHostSlotBytes), 0u,
+                             __ATOMIC_RELEASE);
+            raised_tok = kNoToken;
+          }
           sh.hi_active = false;
+        }
       }
     }
     if (!inflight && next_arrival < run->n_arrivals && run->arrivals_us[next_arrival] <= now) {
@@ -1019,6 +1058,7 @@ extern "C" int tally_sched_run(tally_ctx *ctx, tally_sched_run_t *run) {
           uint32_t slot = (uint32_t)(tok >> 32) - 1;
           __atomic_store_n((uint32_t *)(ctx->host_pool + slot * kHostSlotBytes), (uint32_t)tok,
                            __ATOMIC_RELEASE);
+          raised_tok = tok;
         }
       }
       for (uint32_t i = 0; i < run->n_hi_kernels && rc == TALLY_OK; ++i)

@@ -99,3 +99,57 @@ def test_profile_picks_a_config_under_the_threshold(env):
     assert (meas[chosen]["param"], meas[chosen]["kind"]) == (o["param"], 0 if o["kind"] == "ptb" else 1)
     got = ctx.lookup_config(k)
     assert got is not None and got["param"] == meas[chosen]["param"]
+
+
+def test_workers_pause_inside_long_blocks_while_preempted(env):
+    """A 256x256 tile over K = 32768 lasts about a millisecond.  With the pause enabled a
+    preemption request raised mid-tile suspends the workers until it is withdrawn; the
+    kernel then finishes, every block exactly once, with the right numbers."""
+    import time
+    B, ctx, torch = env
+    from gpu_util import host, assert_bf16_close
+    from oracle import kernels as OK
+    m = n = 1024
+    k = 32768
+    g = TI.gemm_inputs(m, n, k, scale=1.0 / 128.0, config_index=1)
+    A = torch.from_numpy(g["A"].view(np.int16)).cuda()
+    Bt = torch.from_numpy(g["Bt"].view(np.int16)).cuda()
+    Cd = torch.zeros((1, m, n), dtype=torch.int16, device="cuda")
+    torch.cuda.synchronize()
+    kern = B.gemm_bf16(A, Bt, Cd)
+    assert kern.total_blocks == 16
+
+    def run(pause_s, bound_us):
+        ctx.set_yield_bound_us(bound_us)
+        t0 = time.perf_counter()
+        job = ctx.launch_ptb(kern, 16, coverage=True)
+        time.sleep(0.0002)
+        if pause_s:
+            job.preempt()
+            time.sleep(pause_s)
+            job.resume()                         # still running: withdraws the request
+        st = job.wait()
+        dt = time.perf_counter() - t0
+        if st == B.JOB_STOPPED:                  # a worker was between blocks: relaunch
+            job.resume()
+            assert job.wait() == B.JOB_COMPLETE
+        rec = job.coverage()
+        job.free()
+        assert (rec["count"] == 1).all()
+        return dt
+
+    run(0.0, 1000)                               # warm-up
+    base = run(0.0, 1000)
+    paused = run(0.004, 100000)                  # bound 100 ms > the 4 ms pause
+    unpaused = run(0.004, 0)                     # pause disabled: request has no effect mid-tile
+    ctx.set_yield_bound_us(1000)
+    assert paused - base > 0.6 * 0.004, (base, paused)
+    assert base < 0.004, base                    # otherwise the test proves nothing
+    assert unpaused >= 0.004                     # (the host itself slept that long)
+    torch.cuda.synchronize()
+    got = host(Cd)
+    for bx, by in ((0, 0), (3, 2)):
+        a = dict(g, C=np.zeros((1, m, n), np.uint16))
+        OK.exec_block("gemm_bf16", (bx, by, 0), (4, 4, 1), a)
+        r, c = slice(by * 256, by * 256 + 256), slice(bx * 256, bx * 256 + 256)
+        assert_bf16_close(got[0, r, c], a["C"][0, r, c])
