@@ -230,8 +230,8 @@ def main():
         "achieved": tf_ptb, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
         "frac": tf_ptb / PEAK_BF16_TFLOPS,
         # HBM-side bytes per launch from the committed rocprofv3 counter runs
-        # (profiles/gemm_bf16_cfg1_roofline_counters.txt): FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0
-        "traffic": 160135.9 * 1024 * 2.0 + 32799.7 * 1024,
+        # (profiles/gemm_bf16_cfg1_rocprofv3.txt): FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0
+        "traffic": 158775.6 * 1024 * 2.0 + 32785.7 * 1024,
         "traffic_unit": "bytes per launch (algorithmic: 100663296)",
         "avg_launch_ms": ms_ptb,
         "native": {"achieved": tf_nat, "frac": tf_nat / PEAK_BF16_TFLOPS, "avg_launch_ms": ms_nat},
