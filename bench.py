@@ -8,8 +8,10 @@ next to a high-priority bf16 GEMV (1x4096 by 4096x4096) that arrives every 1 ms.
 A "step" is one high-priority period: one arrival, its preempt + native launch, and the
 best-effort work scheduled around it.  K steps are timed, after W warm-up steps, for
   (1) the high-priority job alone, (2) the best-effort job alone, (3) both co-located
-under the priority scheduler.  From those: p50/p99 of the high-priority latency alone and
-co-located, the p99 overhead, best-effort throughput retained, preemption latency.
+under the priority scheduler; the pair (1), (3) is run `--repeats` times, alternating, and
+percentiles are taken over the pooled samples.  From those: p50/p99 of the high-priority
+latency alone and co-located, the p99 overhead, best-effort throughput retained,
+preemption latency.
 A separate leg times single launches of the dominant kernel (GEMM, native and
 persistent-worker form) with HIP events for the roofline figures, and the CPU oracle is
 timed on a bounded sample of the same work.
@@ -106,6 +108,10 @@ def main():
     ap.add_argument("--workers", type=int, default=256)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--roofline-reps", type=int, default=20)
+    ap.add_argument("--repeats", type=int, default=3,
+                    help="cfg1: the (alone, co-located) pair of K-step runs is made this many times, "
+                         "alternating, and the percentiles are taken over the pooled samples; the "
+                         "p99 of one 2000-sample run moves by several microseconds with host jitter")
     ap.add_argument("--leg", choices=["all", "roofline", "coloc"], default="all",
                     help="roofline: only single launches of the GEMM/GEMV kernels plus a plain "
                          "copy of known size (for rocprofv3 counter runs); coloc: only the "
@@ -189,19 +195,31 @@ def main():
         return
     window_us = float(arrivals[-1])
 
-    # ---- (1) high-priority alone --------------------------------------------------------
-    solo = ctx.sched_run([gemv], arrivals, [], policy=B.POLICY_TALLY, tail_us=0.0)
-    lat_solo = solo["latency_us"][Wm:]
     # ---- (2) best-effort alone -----------------------------------------------------------
     ctx.sched_run([], [], [(gemm, be_cfg)], tail_us=Wm * args.period_us)          # warm-up
     be_solo = ctx.sched_run([], [], [(gemm, be_cfg)], tail_us=K * args.period_us)
     tput_solo = be_solo["be_kernels_done"] / (be_solo["window_us"] * 1e-6)
-    # ---- (3) co-located under the priority scheduler ------------------------------------
-    t_wall0 = time.perf_counter()
-    co = ctx.sched_run([gemv], arrivals, [(gemm, be_cfg)], policy=B.POLICY_TALLY, tail_us=0.0)
-    t_wall = time.perf_counter() - t_wall0
-    lat_co = co["latency_us"][Wm:]
+    # ---- (1) high-priority alone and (3) co-located under the priority scheduler, alternating
+    solo_runs, co_runs = [], []
+    t_wall = 0.0
+    for _ in range(max(args.repeats, 1)):
+        solo_runs.append(ctx.sched_run([gemv], arrivals, [], policy=B.POLICY_TALLY, tail_us=0.0))
+        t_wall0 = time.perf_counter()
+        co_runs.append(ctx.sched_run([gemv], arrivals, [(gemm, be_cfg)], policy=B.POLICY_TALLY,
+                                     tail_us=0.0))
+        t_wall += time.perf_counter() - t_wall0
+    lat_solo = np.concatenate([r["latency_us"][Wm:] for r in solo_runs])
+    lat_co = np.concatenate([r["latency_us"][Wm:] for r in co_runs])
+    # the part of a latency that follows the host's launch calls (device side and completion)
+    dev_solo = np.concatenate([(r["latency_us"] - r["issue_us"])[Wm:] for r in solo_runs])
+    dev_co = np.concatenate([(r["latency_us"] - r["issue_us"])[Wm:] for r in co_runs])
+    co = {"window_us": sum(r["window_us"] for r in co_runs),
+          "be_kernels_done": sum(r["be_kernels_done"] for r in co_runs),
+          "n_preempts": sum(r["n_preempts"] for r in co_runs),
+          "preempt_latency_us": np.concatenate([r["preempt_latency_us"] for r in co_runs])}
     tput_co = co["be_kernels_done"] / (co["window_us"] * 1e-6)
+    per_repeat = [(pct(c["latency_us"][Wm:], 99) / pct(s_["latency_us"][Wm:], 99) - 1.0) * 100.0
+                  for s_, c in zip(solo_runs, co_runs)]
     # ---- decomposition: same load with native best-effort kernels, and with no scheduling -
     nat = ctx.sched_run([gemv], arrivals[: Wm + max(K // 4, 200)], [(gemm, (B.CFG_NATIVE, 1, 1))],
                         policy=B.POLICY_PRIORITY_NATIVE, tail_us=0.0)
@@ -247,7 +265,8 @@ def main():
         "value": overhead,
         "unit": "% (hi-pri p99 latency overhead, co-located vs alone)",
         "n_gpus": 1, "steps": K, "warmup": Wm,
-        "ms_per_step": co["window_us"] / (K + Wm) / 1e3,
+        "ms_per_step": co["window_us"] / ((K + Wm) * len(co_runs)) / 1e3,
+        "repeats": len(co_runs),
         "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "cfg1: best-effort bf16 GEMM 4096^3 (256x256 logical tiles, "
@@ -256,7 +275,12 @@ def main():
                    "be_form": "ptb", "workers": args.workers, "chunk": 1,
                    "period_us": args.period_us},
         "hi_pri_latency_us": {"solo_p50": p50s, "solo_p99": p99s, "coloc_p50": p50c,
-                              "coloc_p99": p99c, "n": int(len(lat_co))},
+                              "coloc_p99": p99c, "n": int(len(lat_co)),
+                              "after_launch_calls": {"solo_p50": pct(dev_solo, 50),
+                                                     "solo_p99": pct(dev_solo, 99),
+                                                     "coloc_p50": pct(dev_co, 50),
+                                                     "coloc_p99": pct(dev_co, 99)}},
+        "p99_overhead_pct_per_repeat": per_repeat,
         "p99_overhead_pct": overhead,
         "p50_overhead_pct": (p50c - p50s) / p50s * 100.0,
         "be_tput_retained_pct": retained,

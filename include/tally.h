@@ -272,6 +272,8 @@ typedef struct {
   uint64_t be_kernels_done;   /* best-effort kernels completed inside the window             */
   uint64_t be_steps_done;
   double window_us;           /* wall time of the run                                        */
+  double *issue_us;           /* optional (may be NULL), n_arrivals: scheduled arrival -> the
+                                 request's launch calls have returned on the host            */
 } tally_sched_run_t;
 
 /* Run the scheduling loop on the calling thread until every arrival has completed and

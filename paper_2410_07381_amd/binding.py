@@ -108,7 +108,7 @@ class SchedRun(C.Structure):
                 ("preempt_latency_us", C.POINTER(C.c_double)), ("preempt_cap", C.c_uint32),
                 ("n_preempts", C.c_uint32),
                 ("be_kernels_done", C.c_uint64), ("be_steps_done", C.c_uint64),
-                ("window_us", C.c_double)]
+                ("window_us", C.c_double), ("issue_us", C.POINTER(C.c_double))]
 
 
 class TallyError(RuntimeError):
@@ -401,9 +401,12 @@ class Context:
         run.latency_us = lat.ctypes.data_as(C.POINTER(C.c_double))
         run.preempt_latency_us = pre.ctypes.data_as(C.POINTER(C.c_double))
         run.preempt_cap = cap
+        issue = np.zeros(len(arrivals), dtype=np.float64)
+        run.issue_us = issue.ctypes.data_as(C.POINTER(C.c_double))
         _check(_lib.tally_sched_run(self.h, C.byref(run)), "tally_sched_run")
         return {
             "latency_us": lat,
+            "issue_us": issue,
             "preempt_latency_us": pre[: min(run.n_preempts, cap)].copy(),
             "n_preempts": run.n_preempts,
             "be_kernels_done": run.be_kernels_done,

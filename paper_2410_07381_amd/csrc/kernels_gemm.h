@@ -16,8 +16,8 @@
 // holds 256 rows of 64 bytes; slot s holds row s/4, k-chunk (s%4) xor ((row/4)%4), which
 // makes the 16 lanes that a 128-bit LDS read serves together (64 banks, 256 bytes per
 // clock) fall into 16 different 16-byte bank groups, without padding; with the xor taken
-// from row/2 the bank-conflict counter showed every read served at half rate.  The lane-to-address map of the global side is chosen to
-// produce that layout.
+// from row/2 the bank-conflict counter showed every read served at half rate.  The
+// lane-to-address map of the global side is chosen to produce that layout.
 //
 // Register budget: the arithmetic VGPRs are kept low on purpose so that, with the 256
 // accumulators, a wave stays well under the 512 registers of its SIMD and waves of a
@@ -125,18 +125,48 @@ struct GemmBody {
     const uint32_t fB = (wn * 128 + f_row) * (BK * 2);
     const uint32_t koff0 = ((0u + f_half) ^ f_x) * 16, koff1 = ((2u + f_half) ^ f_x) * 16;
 
-    // Two fragment sets: the LDS reads of the next half-step are issued before the MFMAs of
-    // the current one, so the matrix pipe (one wave per SIMD, nothing else to switch to)
-    // does not sit idle for an LDS round trip sixteen MFMAs at a time.
+    // Two fragment sets: the LDS reads of the next half-step travel while the MFMAs of the
+    // current one run.  A wave is alone on its SIMD, so whatever it issues between two
+    // MFMAs that does not fit into the 32 cycles the earlier MFMA occupies the matrix pipe
+    // leaves the pipe idle.  Reads and direct loads are therefore written, and pinned by
+    // scheduling groups, one at a time between MFMAs: the five reads the first four MFMAs of
+    // the next half need come first, then the remaining three reads alternate with the
+    // half's four direct loads, three MFMAs apart (the four waves issue theirs together and
+    // the address unit takes 16 cycles per 1 KB load).  Reads and direct loads both touch
+    // LDS, so the compiler keeps them in source order: the source order below is the issue
+    // order.  Against reads and loads bunched in front of sixteen MFMAs this took a quarter
+    // of the cycles out of the loop.
     bf16x8_t fa0[4], fb0[4], fa1[4], fb1[4];
     auto lfrag = [&](bf16x8_t(&fa)[4], bf16x8_t(&fb)[4], uint32_t kt, uint32_t koff) {
       const unsigned char *cA = sA + (kt & (STAGES - 1)) * OPB + fA + koff;
       const unsigned char *cB = sB + (kt & (STAGES - 1)) * OPB + fB + koff;
+      fa[0] = *reinterpret_cast<const bf16x8_t *>(cA);
 #pragma unroll
-      for (int t = 0; t < 4; ++t) {
+      for (int t = 0; t < 4; ++t) fb[t] = *reinterpret_cast<const bf16x8_t *>(cB + t * 32 * BK * 2);
+#pragma unroll
+      for (int t = 1; t < 4; ++t) fa[t] = *reinterpret_cast<const bf16x8_t *>(cA + t * 32 * BK * 2);
+    };
+    // one direct load (16 rows of one operand) of the four that fill a wave's share of a stage
+    auto issue_one = [&](const unsigned char *g, lptr_t l, int j) {
+      if (j == 0) __builtin_amdgcn_global_load_lds((gptr_t)(g + voff[0]), l, 16, 0, 0);
+      if (j == 1) __builtin_amdgcn_global_load_lds((gptr_t)(g + voff[1]), l, 16, 1024, 0);
+      if (j == 2) __builtin_amdgcn_global_load_lds((gptr_t)(g + voff[2]), l, 16, 2048, 0);
+      if (j == 3) __builtin_amdgcn_global_load_lds((gptr_t)(g + voff[3]), l, 16, 3072, 0);
+    };
+    // fragment reads of (kt, half) interleaved with the loads of one operand of a later stage
+    auto lfrag_and_loads = [&](bf16x8_t(&fa)[4], bf16x8_t(&fb)[4], uint32_t kt, uint32_t koff,
+                               const unsigned char *g, lptr_t l) {
+      const unsigned char *cA = sA + (kt & (STAGES - 1)) * OPB + fA + koff;
+      const unsigned char *cB = sB + (kt & (STAGES - 1)) * OPB + fB + koff;
+      fa[0] = *reinterpret_cast<const bf16x8_t *>(cA);
+#pragma unroll
+      for (int t = 0; t < 4; ++t) fb[t] = *reinterpret_cast<const bf16x8_t *>(cB + t * 32 * BK * 2);
+#pragma unroll
+      for (int t = 1; t < 4; ++t) {
+        issue_one(g, l, t - 1);
         fa[t] = *reinterpret_cast<const bf16x8_t *>(cA + t * 32 * BK * 2);
-        fb[t] = *reinterpret_cast<const bf16x8_t *>(cB + t * 32 * BK * 2);
       }
+      issue_one(g, l, 3);
     };
     auto mma = [&](const bf16x8_t(&fa)[4], const bf16x8_t(&fb)[4]) {
 #pragma unroll
@@ -144,6 +174,26 @@ struct GemmBody {
 #pragma unroll
         for (int j = 0; j < 4; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+    };
+    // issue order of one half-step: M = MFMA (mask 0x8), d = LDS read (0x100), G = direct
+    // load (0x10):  Md Md Md Md Md  MG Md M  MG Md M  MG Md M  MG M
+    auto half_step_order = [&]() {
+#pragma unroll
+      for (int i = 0; i < 5; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      }
+#pragma unroll
+      for (int i = 0; i < 3; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      }
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
     };
 
     // stage 0 has landed once only the two younger stages (8 loads each) are in flight
@@ -160,28 +210,26 @@ struct GemmBody {
     // set 1 holds (kt, second half).  An iteration opens with the barrier, so the one wait
     // the compiler places conservatively (at a loop header) coincides with the wait a
     // barrier needs anyway; all other waits sit inside a basic block and name exactly the
-    // reads they need.  The scheduling fences keep the early reads from being sunk back
-    // down to their first use.
+    // reads they need.
     uint32_t kt = 0;
-    // steady state: stages kt+1 and kt+2 are in flight, stage kt+3 is issued here
+    // steady state: stages kt+1 and kt+2 are in flight, stage kt+3 is issued here (its
+    // slot in the ring held stage kt-1, whose last reads were issued a whole step ago)
     for (; kt + 3 < nk; ++kt) {
       // one wave polls; the others meet it at the barrier below
       if (ctl.ticks != 0 && wave == 0 && (kt & (YIELD_EVERY - 1)) == YIELD_EVERY - 1)
         yield_while_preempted(ctl);
       asm volatile("s_waitcnt vmcnt(8)" ::: "memory");  // stage kt+1 complete, kt+2 in flight
       __syncthreads();  // stage kt+1 is in LDS for everyone; everyone is done with kt-1
-      issue_loads(kt + 3);
-      lfrag(fa0, fb0, kt + 1, koff0);
-      __builtin_amdgcn_sched_barrier(0);
+      const uint32_t st = (kt + 3) & (STAGES - 1);
+      const unsigned char *gA = uA + (uint64_t)(kt + 3) * (BK * 2);
+      const unsigned char *gB = uB + (uint64_t)(kt + 3) * (BK * 2);
+      lfrag_and_loads(fa0, fb0, kt + 1, koff0, gA, (lptr_t)(sA + st * OPB + lds_wave));
       mma(fa1, fb1);
+      half_step_order();
       __builtin_amdgcn_sched_barrier(0);
-      // set 0 was read sixteen MFMAs ago: waiting for it here, before the next reads are
-      // issued, is free, whereas the compiler's own wait in front of the MFMAs below would
-      // also cover the reads issued just above them
-      __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
-      lfrag(fa1, fb1, kt + 1, koff1);
-      __builtin_amdgcn_sched_barrier(0);
+      lfrag_and_loads(fa1, fb1, kt + 1, koff1, gB, (lptr_t)(sB + st * OPB + lds_wave));
       mma(fa0, fb0);
+      half_step_order();
       __builtin_amdgcn_sched_barrier(0);
     }
     // the last steps drain the ring

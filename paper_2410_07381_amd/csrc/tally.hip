@@ -1064,6 +1064,7 @@ extern "C" int tally_sched_run(tally_ctx *ctx, tally_sched_run_t *run) {
       for (uint32_t i = 0; i < run->n_hi_kernels && rc == TALLY_OK; ++i)
         rc = tally_launch_native(ctx, &run->hi_kernels[i], 1);
       if (rc == TALLY_OK) rc = tally_marker(ctx, 1, ++hi_seq);
+      if (run->issue_us) run->issue_us[cur] = (now_us() - t0) - run->arrivals_us[cur];
       inflight = true;
     }
     if (!inflight && completed == run->n_arrivals && (run->n_arrivals > 0 || now >= t_end) &&
