@@ -101,7 +101,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--workload", choices=["cfg0", "cfg1", "cfg2", "cfg3", "cfg4"], default="cfg1",
+    ap.add_argument("--workload", choices=["cfg0", "cfg1", "cfg2", "cfg3", "cfg4", "sweep_threshold", "sweep_load", "multi_be"], default="cfg1",
                     help="cfg1 is the headline workload; the others print one JSON line each "
                          "with that configuration's figures")
     ap.add_argument("--period-us", type=float, default=1000.0)
@@ -118,7 +118,8 @@ def main():
                          "co-located scheduling run")
     args = ap.parse_args()
     defaults = {"cfg0": (1, 0), "cfg1": (2000, 100), "cfg2": (1500, 100), "cfg3": (500, 50),
-                "cfg4": (1000, 100)}[args.workload]
+                "cfg4": (1000, 100), "sweep_threshold": (1500, 100),
+                "sweep_load": (2000, 100), "multi_be": (2000, 100)}[args.workload]
     if args.steps is None:
         args.steps = defaults[0]
     if args.warmup is None:

@@ -6,6 +6,11 @@ cfg3  training-like best-effort step (transformer-layer GEMMs, softmax, LayerNor
       persistent-worker form against a 768-hidden inference-like layer, Poisson 100/s
 cfg4  the cfg3 step against decode-like kernels (two GEMVs + attention), Poisson 200/s
 
+sweep_threshold  turnaround-latency threshold sweep (Section 5.5 sensitivity): the profiler's
+      choice per threshold, and what the hi-pri job and the best-effort job get under it
+sweep_load       hi-pri load from 10 % to 90 % duty, plus a bursty arrival pattern
+multi_be         one to four best-effort clients against the cfg1 hi-pri GEMV
+
 Each returns a dict that bench.py prints as one JSON line.  All inputs are synthetic and
 resident in HBM before timing.  Kernels of a "step" are independent launches with the
 shapes of the layer (no data flows between them): the subject here is scheduling, and
@@ -330,4 +335,224 @@ def cfg4(torch, B, ctx, be_stream, args):
                      "over 2048x32x128 bf16 KV, GEMV 11008x4096 and 4096x11008), Poisson 200/s")
 
 
-WORKLOADS = {"cfg0": cfg0, "cfg2": cfg2, "cfg3": cfg3, "cfg4": cfg4}
+# --------------------------------------------------------------------------- sensitivity sweeps
+THRESHOLDS_MS = (0.01, 0.0316, 0.1, 0.316, 1.0, 10.0)
+
+
+def _coloc_stats(B, ctx, hi, arrivals, items, warm, solo_p99, tput_solo):
+    co = ctx.sched_run(hi, arrivals, items, policy=B.POLICY_TALLY)
+    lat = co["latency_us"][warm:]
+    pre = co["preempt_latency_us"]
+    return {
+        "hi_p50_us": pct(lat, 50), "hi_p99_us": pct(lat, 99),
+        "hi_p99_overhead_pct": (pct(lat, 99) - solo_p99) / solo_p99 * 100.0,
+        "be_tput_retained_pct": co["be_kernels_done"] / co["window_us"] / tput_solo * 100.0,
+        "n_preempts": int(co["n_preempts"]), "preempt_p50_us": pct(pre, 50),
+        "preempt_p99_us": pct(pre, 99),
+    }
+
+
+def sweep_threshold(torch, B, ctx, be_stream, args):
+    """Section 5.5 varies the turnaround-latency threshold from 0.01 ms to 10 ms.  Part (a):
+    one streaming kernel (the 2^28 sum) with sliced and persistent-worker candidates whose
+    Eq.-1 estimates span 1 us to a whole kernel; part (b): the transformer-layer step with
+    per-kernel candidates.  Candidates are measured once; each threshold then selects from
+    the same table and the co-located run uses that selection."""
+    import tally_inputs as TI
+    n = 1 << 28
+    x = torch.rand(n, device="cuda")
+    partial = torch.zeros(n // 4096, device="cuda")
+    sx = torch.randn(1 << 20, device="cuda")
+    sy = torch.randn(1 << 20, device="cuda")
+    torch.cuda.synchronize()
+    red = B.reduce_sum(x, partial)
+    hi = [B.saxpy(sx, sy, 1.5)]
+    arrivals = TI.poisson_arrivals_us(500.0, args.steps, config_index=2)
+    w = args.warmup
+    solo = ctx.sched_run(hi, arrivals, [])
+    solo_p99 = pct(solo["latency_us"][w:], 99)
+    cands = [(B.CFG_SLICED, 4096, 1), (B.CFG_SLICED, 512, 1), (B.CFG_SLICED, 64, 1),
+             (B.CFG_PTB, 256, 1), (B.CFG_PTB, 1024, 1), (B.CFG_PTB, 2048, 1),
+             (B.CFG_PTB, 1024, 2), (B.CFG_PTB, 512, 8), (B.CFG_PTB, 2048, 4),
+             (B.CFG_PTB, 512, 32), (B.CFG_PTB, 256, 256)]
+    meas, _ = ctx.profile(red, cands, runs=10, threshold_ms=0.0316)
+    nat_item = [(red, (B.CFG_NATIVE, 1, 1))]
+    be_solo = ctx.sched_run([], [], nat_item, tail_us=1e6)
+    tput_solo = be_solo["be_kernels_done"] / be_solo["window_us"]
+    part_a, seen = {}, {}
+    for thr in THRESHOLDS_MS:
+        c = meas[B.select_config(meas, thr)]
+        key = (c["kind"], c["param"], c["chunk"])
+        if key not in seen:
+            seen[key] = _coloc_stats(B, ctx, hi, arrivals, [(red, key)], w, solo_p99, tput_solo)
+        part_a[str(thr)] = dict(
+            chosen={"form": "ptb" if c["kind"] == B.CFG_PTB else "sliced", "param": c["param"],
+                    "chunk": c["chunk"], "kernel_latency_us": c["latency_ms"] * 1e3,
+                    "turnaround_estimate_us": c["turnaround_ms"] * 1e3},
+            **seen[key])
+    del x, partial
+
+    # (b) the transformer-layer step
+    info = B.device_info()
+    cu = info["num_cus"]
+    step = _be_step(torch, B)
+    hi_b = _hi_layer(torch, B)
+    arr_b = TI.poisson_arrivals_us(100.0, max(args.steps // 5, 200), config_index=3)
+    wb = min(w, 20)
+    solo_b = ctx.sched_run(hi_b, arr_b, [])
+    solo_b_p99 = pct(solo_b["latency_us"][wb:], 99)
+    tables = []
+    for name, k, flops, nbytes in step:
+        if k.kernel_id == B.K_GEMM_BF16:
+            cs = [(B.CFG_PTB, cu, 1), (B.CFG_SLICED, cu, 1), (B.CFG_SLICED, 4 * cu, 1)]
+        elif "gemm" in name:
+            cs = [(B.CFG_PTB, 4 * cu, 1), (B.CFG_PTB, 4 * cu, 4), (B.CFG_PTB, 4 * cu, 16),
+                  (B.CFG_SLICED, 16 * cu, 1)]
+        else:
+            cs = [(B.CFG_PTB, 2 * cu, 1), (B.CFG_PTB, 2 * cu, 4), (B.CFG_PTB, 2 * cu, 16),
+                  (B.CFG_PTB, 4 * cu, 64), (B.CFG_SLICED, 16 * cu, 1)]
+        m, _ = ctx.profile(k, cs, runs=3, threshold_ms=0.0316)
+        tables.append((name, k, m))
+    nat_items = [(k, (B.CFG_NATIVE, 1, 1)) for _, k, _, _ in step]
+    be_solo_b = ctx.sched_run([], [], nat_items, tail_us=2e6)
+    tput_solo_b = be_solo_b["be_kernels_done"] / be_solo_b["window_us"]
+    part_b = {}
+    for thr in THRESHOLDS_MS:
+        items, picks = [], {}
+        for name, k, m in tables:
+            c = m[B.select_config(m, thr)]
+            items.append((k, (c["kind"], c["param"], c["chunk"])))
+            picks[name] = {"form": "ptb" if c["kind"] == B.CFG_PTB else "sliced",
+                           "param": c["param"], "chunk": c["chunk"],
+                           "turnaround_estimate_us": c["turnaround_ms"] * 1e3}
+        part_b[str(thr)] = dict(chosen=picks, **_coloc_stats(B, ctx, hi_b, arr_b, items, wb,
+                                                             solo_b_p99, tput_solo_b))
+    return {
+        "workload": "turnaround-latency threshold sweep (thresholds in ms): (a) 2^28 fp32 sum vs "
+                    "hi-pri 2^20 SAXPY, Poisson 500/s; (b) transformer-layer step vs 768-hidden "
+                    "inference layer, Poisson 100/s",
+        "note": "be_tput_retained_pct is relative to the same kernels run natively, alone",
+        "a_sum": {"hi_solo_p99_us": solo_p99, "candidates": meas, "by_threshold_ms": part_a},
+        "b_step": {"hi_solo_p99_us": solo_b_p99, "by_threshold_ms": part_b},
+    }
+
+
+def sweep_load(torch, B, ctx, be_stream, args):
+    """Section 5.4 varies the load of the inference service.  Hi-pri: the 768-hidden
+    inference layer (9 kernels); its duty cycle = arrival rate x solo latency is set to
+    10 ... 90 %; best-effort: the 4096^3 GEMM as persistent workers.  A bursty arrival
+    pattern (30 % mean duty; 2 ms bursts at ten times the off-burst rate, which overload the
+    service while they last) stands in for the spikes of production traces."""
+    import tally_inputs as TI
+    g = TI.gemm_inputs(4096, 4096, 4096, config_index=1)
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).cuda()
+    A, Bt = dev(g["A"]), dev(g["Bt"])
+    Cd = torch.zeros((1, 4096, 4096), dtype=torch.int16, device="cuda")
+    torch.cuda.synchronize()
+    gemm = B.gemm_bf16(A, Bt, Cd)
+    hi = _hi_layer(torch, B)
+    items = [(gemm, (B.CFG_PTB, B.device_info()["num_cus"], 1))]
+    probe = ctx.sched_run(hi, TI.periodic_arrivals_us(2000.0, 300), [])
+    svc_us = pct(probe["latency_us"][50:], 50)
+    be_solo = ctx.sched_run([], [], items, tail_us=1e6)
+    tput_solo = be_solo["be_kernels_done"] / be_solo["window_us"]
+    n = args.steps
+    w = args.warmup
+    rows = {}
+    for duty in (0.1, 0.3, 0.5, 0.7, 0.9):
+        rate = duty / (svc_us * 1e-6)
+        arr = TI.poisson_arrivals_us(rate, n, config_index=1)
+        solo = ctx.sched_run(hi, arr, [])
+        sp99 = pct(solo["latency_us"][w:], 99)
+        row = _coloc_stats(B, ctx, hi, arr, items, w, sp99, tput_solo)
+        row.update({"arrivals_per_s": rate, "hi_solo_p50_us": pct(solo["latency_us"][w:], 50),
+                    "hi_solo_p99_us": sp99})
+        nat = ctx.sched_run(hi, arr[: max(n // 4, 200)], [(gemm, (B.CFG_NATIVE, 1, 1))],
+                            policy=B.POLICY_NONE)
+        row["no_scheduling_p99_us"] = pct(nat["latency_us"][min(w, 20):], 99)
+        rows["%d%%" % round(duty * 100)] = row
+    rate = 0.3 / (svc_us * 1e-6)
+    arr = TI.bursty_arrivals_us(rate, 2 * n, config_index=1, burst=10.0, p_on=0.05,
+                                mean_segment_us=2000.0)
+    solo = ctx.sched_run(hi, arr, [])
+    sp99 = pct(solo["latency_us"][w:], 99)
+    bursty = _coloc_stats(B, ctx, hi, arr, items, w, sp99, tput_solo)
+    bursty.update({"mean_arrivals_per_s": len(arr) / (arr[-1] * 1e-6), "hi_solo_p99_us": sp99,
+                   "hi_solo_p50_us": pct(solo["latency_us"][w:], 50)})
+    return {
+        "workload": "hi-pri load sweep: 768-hidden inference layer (9 kernels) at 10-90 % duty "
+                    "(Poisson) and a bursty pattern, vs best-effort bf16 GEMM 4096^3 as persistent "
+                    "workers",
+        "hi_service_time_us": svc_us, "by_duty": rows,
+        "bursty_30pct_mean_duty_10x_bursts_of_2ms": bursty,
+        "note": "latency is measured from the scheduled arrival (open loop), so queueing behind "
+                "earlier requests is part of it, alone and co-located alike",
+    }
+
+
+def multi_be(torch, B, ctx, be_stream, args):
+    """Section 5.5 adds best-effort clients.  Hi-pri: the cfg1 GEMV every 1 ms.  Best-effort
+    clients, each a loop over one kernel on its own stream pair: (0) bf16 GEMM 4096^3,
+    (1) fp32 sum of 2^26, (2) fp32 softmax 65536 x 2048, (3) a second GEMM 4096^3."""
+    import tally_inputs as TI
+    g = TI.gemm_inputs(4096, 4096, 4096, config_index=1)
+    gv = TI.gemv_inputs(4096, 4096, config_index=1)
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a).view(np.int16)
+                                     if a.dtype == np.uint16 else np.ascontiguousarray(a)).cuda()
+    A, Bt = dev(g["A"]), dev(g["Bt"])
+    C0 = torch.zeros((1, 4096, 4096), dtype=torch.int16, device="cuda")
+    C1 = torch.zeros((1, 4096, 4096), dtype=torch.int16, device="cuda")
+    x, W = dev(gv["x"]), dev(gv["W"])
+    y = torch.zeros(4096, dtype=torch.int16, device="cuda")
+    rx = torch.rand(1 << 26, device="cuda")
+    rp = torch.zeros((1 << 26) // 4096, device="cuda")
+    sx = torch.randn((65536, 2048), device="cuda")
+    so = torch.empty_like(sx)
+    torch.cuda.synchronize()
+    cu = B.device_info()["num_cus"]
+    hi = [B.gemv_bf16(x, W, y)]
+    clients = [
+        ("gemm_a", B.gemm_bf16(A, Bt, C0), (B.CFG_PTB, cu, 1)),
+        ("sum_2^26", B.reduce_sum(rx, rp), (B.CFG_PTB, 2 * cu, 8)),
+        ("softmax_65536x2048", B.softmax_f32(sx, so), (B.CFG_PTB, 2 * cu, 4)),
+        ("gemm_b", B.gemm_bf16(A, Bt, C1), (B.CFG_PTB, cu, 1)),
+    ]
+    arrivals = TI.periodic_arrivals_us(1000.0, args.steps + args.warmup)
+    w = args.warmup
+    solo = ctx.sched_run(hi, arrivals, [])
+    solo_p50, solo_p99 = pct(solo["latency_us"][w:], 50), pct(solo["latency_us"][w:], 99)
+    alone = {}
+    for name, k, cfg in clients:
+        r = ctx.sched_run([], [], [(k, cfg)], tail_us=0.5e6)
+        alone[name] = r["be_kernels_done"] / r["window_us"] * 1e6
+    rows = {}
+    for n in (1, 2, 3, 4):
+        items = [(k, cfg) for _, k, cfg in clients[:n]]
+        co = ctx.sched_run(hi, arrivals, items, policy=B.POLICY_TALLY, be_clients=[1] * n)
+        nos = ctx.sched_run(hi, arrivals[: w + max(args.steps // 4, 200)],
+                            [(k, (B.CFG_NATIVE, 1, 1)) for _, k, _ in clients[:n]],
+                            policy=B.POLICY_NONE, be_clients=[1] * n)
+        lat = co["latency_us"][w:]
+        per = co["be_client_kernels_done"] / co["window_us"] * 1e6
+        rows[str(n)] = {
+            "hi_p50_us": pct(lat, 50), "hi_p99_us": pct(lat, 99),
+            "hi_p99_overhead_pct": (pct(lat, 99) - solo_p99) / solo_p99 * 100.0,
+            "no_scheduling_p99_us": pct(nos["latency_us"][w:], 99),
+            "n_preempts": int(co["n_preempts"]),
+            "preempt_p50_us": pct(co["preempt_latency_us"], 50),
+            "client_kernels_per_s": {clients[i][0]: float(per[i]) for i in range(n)},
+            "client_share_of_alone_pct": {clients[i][0]: float(per[i]) / alone[clients[i][0]] * 100.0
+                                          for i in range(n)},
+            "sum_of_shares_pct": float(sum(per[i] / alone[clients[i][0]] for i in range(n)) * 100.0),
+        }
+    return {
+        "workload": "1 to 4 best-effort clients (GEMM 4096^3, sum 2^26, softmax 65536x2048, GEMM "
+                    "4096^3; persistent workers, one stream pair each) vs hi-pri bf16 GEMV 4096x4096 "
+                    "every 1000 us",
+        "hi_solo_p50_us": solo_p50, "hi_solo_p99_us": solo_p99,
+        "client_alone_kernels_per_s": alone, "by_clients": rows,
+    }
+
+
+WORKLOADS = {"cfg0": cfg0, "cfg2": cfg2, "cfg3": cfg3, "cfg4": cfg4,
+             "sweep_threshold": sweep_threshold, "sweep_load": sweep_load, "multi_be": multi_be}

@@ -244,7 +244,11 @@ int tally_select_config(const tally_config *cands, uint32_t n, double threshold_
 /* Measure every candidate configuration of a kernel on the best-effort stream (`runs`
  * timed executions each, after one warm-up; the kernel really runs, so its outputs are
  * written `runs`+1 times per candidate), fill latency and turnaround, choose under
- * threshold_ms and cache the choice per (kernel, grid, block).  cands: in/out array. */
+ * threshold_ms and cache the choice per (kernel, grid, block).  cands: in/out array.
+ * Turnaround of a persistent-worker candidate is Eq. 1; for a kernel whose workers pause
+ * inside their blocks while preempted (and with the pause enabled, see
+ * tally_set_yield_bound_us) it is the time of ONE block times the share of a block
+ * between two pause points, since that is when the execution units are handed over. */
 int tally_profile(tally_ctx *ctx, const tally_kernel_desc *desc, tally_config *cands, uint32_t n,
                   uint32_t runs, double threshold_ms, uint32_t *chosen);
 /* Cached choice for (kernel, grid, block); TALLY_ERR_BAD_STATE if not profiled yet. */
@@ -274,6 +278,17 @@ typedef struct {
   double window_us;           /* wall time of the run                                        */
   double *issue_us;           /* optional (may be NULL), n_arrivals: scheduled arrival -> the
                                  request's launch calls have returned on the host            */
+  /* several best-effort clients (Figure 4 loops over them): be_items is the concatenation
+   * of the clients' steps, client c owning be_client_items[c] consecutive items; each
+   * client has one kernel in flight at a time on a stream pair of its own (client 0 uses
+   * the context's best-effort stream).  NULL / 0 = one client owning every item; at most
+   * 8 clients.  be_steps_done counts client 0's steps.  A kernel is launched only when
+   * the workgroups it brings fit beside the other clients' resident ones (clients wait
+   * first come, first served).  n clients need 2 + 2n hardware queues: the process must
+   * have been started with GPU_MAX_HW_QUEUES at least that (HIP's default is 4), else
+   * TALLY_ERR_UNSUPPORTED. */
+  const uint32_t *be_client_items; uint32_t n_be_clients;
+  uint64_t *be_client_kernels_done; /* optional output, n_be_clients entries                */
 } tally_sched_run_t;
 
 /* Run the scheduling loop on the calling thread until every arrival has completed and

@@ -12,6 +12,18 @@ import os
 
 import numpy as np
 
+# Several best-effort clients need two hardware queues each (see tally_sched_run: 2 + 2n
+# for n clients, n <= 8); HIP folds the process's streams onto GPU_MAX_HW_QUEUES hardware
+# queues (default 4) and reads the variable when it initialises, so raising it only helps
+# if this module is imported before the first GPU call of the process.  A larger value
+# already in the environment is kept.
+try:
+    _hwq = int(os.environ.get("GPU_MAX_HW_QUEUES", "4"))
+except ValueError:
+    _hwq = 4
+if _hwq < 20:
+    os.environ["GPU_MAX_HW_QUEUES"] = "20"
+
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libtally.so")
 
@@ -108,7 +120,9 @@ class SchedRun(C.Structure):
                 ("preempt_latency_us", C.POINTER(C.c_double)), ("preempt_cap", C.c_uint32),
                 ("n_preempts", C.c_uint32),
                 ("be_kernels_done", C.c_uint64), ("be_steps_done", C.c_uint64),
-                ("window_us", C.c_double), ("issue_us", C.POINTER(C.c_double))]
+                ("window_us", C.c_double), ("issue_us", C.POINTER(C.c_double)),
+                ("be_client_items", C.POINTER(C.c_uint32)), ("n_be_clients", C.c_uint32),
+                ("be_client_kernels_done", C.POINTER(C.c_uint64))]
 
 
 class TallyError(RuntimeError):
@@ -376,9 +390,12 @@ class Context:
         return dict(kind=c.kind, param=c.param, chunk=c.chunk, latency_ms=c.latency_ms,
                     turnaround_ms=c.turnaround_ms)
 
-    def sched_run(self, hi_kernels, arrivals_us, be_items, policy=POLICY_TALLY, tail_us=0.0):
+    def sched_run(self, hi_kernels, arrivals_us, be_items, policy=POLICY_TALLY, tail_us=0.0,
+                  be_clients=None):
         """hi_kernels: list of Kernel (one request).  be_items: list of (Kernel, (kind, param,
-        chunk)).  Returns a dict of numpy arrays and counters."""
+        chunk)).  be_clients: optional list of item counts, one per best-effort client (the
+        items are the concatenation of the clients' steps).  Returns a dict of numpy arrays
+        and counters."""
         n_hi = len(hi_kernels)
         hi_arr = (KernelDesc * max(n_hi, 1))(*[k.desc for k in hi_kernels])
         arrivals = np.ascontiguousarray(arrivals_us, dtype=np.float64)
@@ -401,6 +418,13 @@ class Context:
         run.latency_us = lat.ctypes.data_as(C.POINTER(C.c_double))
         run.preempt_latency_us = pre.ctypes.data_as(C.POINTER(C.c_double))
         run.preempt_cap = cap
+        per_client = None
+        if be_clients is not None:
+            counts = (C.c_uint32 * len(be_clients))(*be_clients)
+            per_client = np.zeros(len(be_clients), dtype=np.uint64)
+            run.be_client_items = counts
+            run.n_be_clients = len(be_clients)
+            run.be_client_kernels_done = per_client.ctypes.data_as(C.POINTER(C.c_uint64))
         issue = np.zeros(len(arrivals), dtype=np.float64)
         run.issue_us = issue.ctypes.data_as(C.POINTER(C.c_double))
         _check(_lib.tally_sched_run(self.h, C.byref(run)), "tally_sched_run")
@@ -412,6 +436,7 @@ class Context:
             "be_kernels_done": run.be_kernels_done,
             "be_steps_done": run.be_steps_done,
             "window_us": run.window_us,
+            "be_client_kernels_done": per_client,
         }
 
 

@@ -52,7 +52,12 @@ struct GemmBody {
   // the next tile's first loads cannot overtake a reader of this tile
   static constexpr bool END_BARRIER = false;
   static constexpr bool YIELDS = true;
-  static constexpr uint32_t YIELD_EVERY = 16;             // k-steps between flag checks (~10 us)
+  static constexpr uint32_t YIELD_EVERY = 16;             // k-steps between flag checks (~8 us)
+  // share of a tile between two flag checks (host side, for turnaround estimates)
+  static double pause_fraction(const Args &a) {
+    const uint32_t nk = a.k / BK;
+    return nk > YIELD_EVERY ? (double)YIELD_EVERY / nk : 1.0;
+  }
 
   static __device__ __forceinline__ void run(const Args &a, uint32_t bx, uint32_t by, uint32_t bz) {
     run_yielding(a, bx, by, bz, YieldCtl{nullptr, 0, 0});

@@ -56,6 +56,11 @@ struct KernelOps {
   hipError_t (*ptb)(hipStream_t, const void *args, const PtbCtl &);
   hipError_t (*init)();
   int (*occupancy)(int *blocks_per_cu);
+  // share of one logical block between two points at which a preempted worker pauses
+  // (1 for bodies that only stop at block boundaries)
+  double (*pause_fraction)(const void *args);
+  // what one workgroup of the persistent-worker kernel occupies on a compute unit
+  hipError_t (*footprint)(uint32_t *lds_bytes, uint32_t *waves, uint32_t *regs_per_lane);
 };
 
 template <class Body>
@@ -103,6 +108,17 @@ int occupancy_t(int *blocks_per_cu) {
   HIPCHK(hipOccupancyMaxActiveBlocksPerMultiprocessor(blocks_per_cu, ptb_kernel<Body>,
                                                       Body::THREADS, Body::DYN_LDS));
   return TALLY_OK;
+}
+
+template <class Body>
+hipError_t footprint_t(uint32_t *lds_bytes, uint32_t *waves, uint32_t *regs_per_lane) {
+  hipFuncAttributes attr;
+  hipError_t e = hipFuncGetAttributes(&attr, (const void *)ptb_kernel<Body>);
+  if (e != hipSuccess) return e;
+  *lds_bytes = (uint32_t)attr.sharedSizeBytes + Body::DYN_LDS;
+  *waves = Body::THREADS / 64;
+  *regs_per_lane = ((uint32_t)attr.numRegs + 7u) & ~7u;
+  return hipSuccess;
 }
 
 const tally_dim3 kBlock256 = {256, 1, 1};
@@ -194,9 +210,21 @@ int grid_attn(const void *p, tally_dim3 *g, tally_dim3 *b) {
   return TALLY_OK;
 }
 
+template <class Body>
+double pause_fraction_t(const void *args) {
+  if constexpr (Body::YIELDS) {
+    typename Body::Args a;
+    memcpy(&a, args, sizeof(a));
+    return Body::pause_fraction(a);
+  } else {
+    return 1.0;
+  }
+}
+
 #define OPS(Body, nm, gridfn)                                                              \
   {nm, sizeof(Body::Args), true, gridfn, launch_native_t<Body>, launch_sliced_t<Body>,     \
-   launch_ptb_t<Body>, init_t<Body>, occupancy_t<Body>}
+   launch_ptb_t<Body>, init_t<Body>, occupancy_t<Body>, pause_fraction_t<Body>,              \
+   footprint_t<Body>}
 
 const KernelOps kOps[TALLY_K_COUNT] = {
     OPS(SaxpyBody, "saxpy", grid_saxpy),
@@ -207,12 +235,13 @@ const KernelOps kOps[TALLY_K_COUNT] = {
     OPS(SoftmaxBody, "softmax_f32", grid_softmax),
     OPS(LayerNormBody, "layernorm_f32", grid_layernorm),
     {"attn_decode_bf16", sizeof(tally_attn_decode_args), false, grid_attn, launch_attn_decode,
-     nullptr, nullptr, nullptr, nullptr},
+     nullptr, nullptr, nullptr, nullptr, nullptr, nullptr},
     OPS(GemmSmallBody, "gemm_bf16_small", grid_gemm_small),
 };
 
 constexpr size_t kMaxArgs = 96;
 constexpr int kSlots = 64;
+constexpr int kMaxBeClients = 8;
 constexpr size_t kDevSlotBytes = 512;   // counter | dev_flag | exited, 128 B apart
 constexpr size_t kHostSlotBytes = 256;  // host_flag | status,live | slice_done
 constexpr size_t kCopySlotBytes = kFlagCopies * kFlagCopyStride * sizeof(uint32_t);
@@ -224,6 +253,10 @@ enum JobKind { KIND_PTB = 0, KIND_SLICED = 1, KIND_NATIVE = 2 };
 struct tally_ctx {
   hipStream_t hi, be;
   hipStream_t ctl;           // owned: carries the relay kernels, default priority
+  // streams that new jobs take (normally be / ctl); the scheduler points them at a
+  // best-effort client's own pair while it launches for that client
+  hipStream_t cur_be, cur_ctl;
+  hipStream_t client_be[kMaxBeClients], client_ctl[kMaxBeClients];  // owned, [0] unused
   unsigned char *dev_pool;   // device
   uint32_t *copy_pool;       // device: per slot, kFlagCopies copies of the flag word
   unsigned char *host_pool;  // pinned host
@@ -235,6 +268,7 @@ struct tally_ctx {
   uint32_t *marker_host;     // pinned: [0] hi, [32] be (separate lines)
   uint32_t *marker_dev;
   uint32_t num_cus;
+  uint32_t lds_per_cu;
   uint32_t yield_ticks;      // bound of a mid-block pause, 10 ns ticks
   int device;
   int live_jobs;
@@ -243,6 +277,7 @@ struct tally_ctx {
 
 struct tally_job {
   tally_ctx *ctx;
+  hipStream_t be, ctl;       // the streams this job's kernels and relays go to
   const KernelOps *ops;
   alignas(16) unsigned char args[kMaxArgs];
   tally_dim3 grid;
@@ -311,6 +346,8 @@ int new_job(tally_ctx *ctx, const tally_kernel_desc *desc, int kind, int coverag
   tally_job *j = new (std::nothrow) tally_job();
   if (!j) return TALLY_ERR_NOMEM;
   j->ctx = ctx;
+  j->be = ctx->cur_be;
+  j->ctl = ctx->cur_ctl;
   j->ops = ops;
   memcpy(j->args, desc->args, ops->args_size);
   j->grid = g;
@@ -332,7 +369,7 @@ int new_job(tally_ctx *ctx, const tally_kernel_desc *desc, int kind, int coverag
   if (coverage) {
     e = hipMalloc((void **)&j->cover, sizeof(tally_cover_rec) * (size_t)j->total);
     if (e == hipSuccess)
-      e = hipMemsetAsync(j->cover, 0, sizeof(tally_cover_rec) * (size_t)j->total, ctx->be);
+      e = hipMemsetAsync(j->cover, 0, sizeof(tally_cover_rec) * (size_t)j->total, j->be);
   }
   if (e != hipSuccess) {
     g_last_hip = (int)e;
@@ -352,7 +389,7 @@ int ptb_launch_segment(tally_job *j, uint32_t limit) {
   const int slot = j->slot;
   if (j->counter_dirty) {
     uint32_t raw = j->counter_base + j->progress.load();
-    hipLaunchKernelGGL(set_word_kernel, dim3(1), dim3(64), 0, ctx->be, j->d_counter(), raw);
+    hipLaunchKernelGGL(set_word_kernel, dim3(1), dim3(64), 0, j->be, j->d_counter(), raw);
     HIPCHK(hipGetLastError());
     ctx->slot_counter[slot] = raw;
     j->counter_dirty = false;
@@ -380,7 +417,7 @@ int ptb_launch_segment(tally_job *j, uint32_t limit) {
   c.gy = j->grid.y;
   c.yield_ticks = ctx->yield_ticks;
   c.flag_copies = ctx->copy_pool + (size_t)slot * (kCopySlotBytes / sizeof(uint32_t));
-  hipError_t e = j->ops->ptb(ctx->be, j->args, c);
+  hipError_t e = j->ops->ptb(j->be, j->args, c);
   if (e != hipSuccess) {  // nothing was enqueued: the slot's bookkeeping is unchanged
     g_last_hip = (int)e;
     return TALLY_ERR_HIP;
@@ -392,7 +429,7 @@ int ptb_launch_segment(tally_job *j, uint32_t limit) {
   j->state = TALLY_JOB_RUNNING;
   // the relay runs beside the workers on its own stream and ends with them; without it
   // the job still completes but cannot be preempted
-  hipLaunchKernelGGL(relay_kernel, dim3(1), dim3(64), 0, ctx->ctl, c);
+  hipLaunchKernelGGL(relay_kernel, dim3(1), dim3(64), 0, j->ctl, c);
   e = hipGetLastError();
   if (e != hipSuccess) {
     g_last_hip = (int)e;
@@ -402,7 +439,6 @@ int ptb_launch_segment(tally_job *j, uint32_t limit) {
 }
 
 int sliced_issue(tally_job *j) {
-  tally_ctx *ctx = j->ctx;
   while (!j->stop_issuing.load() && j->next_off < j->total &&
          j->issued - j->retired < j->max_in_flight) {
     uint32_t n = j->total - j->next_off;
@@ -413,10 +449,10 @@ int sliced_issue(tally_job *j) {
     c.gx = j->grid.x;
     c.gy = j->grid.y;
     c.segment = j->segment;
-    HIPCHK(j->ops->sliced(ctx->be, j->args, n, c));
+    HIPCHK(j->ops->sliced(j->be, j->args, n, c));
     j->issued += 1;
     j->next_off += n;
-    hipLaunchKernelGGL(marker_kernel, dim3(1), dim3(64), 0, ctx->be,
+    hipLaunchKernelGGL(marker_kernel, dim3(1), dim3(64), 0, j->be,
                        (uint32_t *)(j->h_base_dev() + 128), j->issued);
     HIPCHK(hipGetLastError());
   }
@@ -474,6 +510,8 @@ int tally_create(tally_ctx **out, void *hip_stream_hi, void *hip_stream_be) {
   c->hi = (hipStream_t)hip_stream_hi;
   c->be = (hipStream_t)hip_stream_be;
   c->ctl = nullptr;
+  memset(c->client_be, 0, sizeof(c->client_be));
+  memset(c->client_ctl, 0, sizeof(c->client_ctl));
   c->dev_pool = nullptr;
   c->copy_pool = nullptr;
   c->host_pool = nullptr;
@@ -508,7 +546,10 @@ int tally_create(tally_ctx **out, void *hip_stream_hi, void *hip_stream_be) {
   }
   memset(c->host_pool, 0, kSlots * kHostSlotBytes);
   memset(c->marker_host, 0, 256);
+  c->cur_be = c->be;
+  c->cur_ctl = c->ctl;
   c->num_cus = (uint32_t)prop.multiProcessorCount;
+  c->lds_per_cu = (uint32_t)prop.maxSharedMemoryPerMultiProcessor;
   c->yield_ticks = 100000;  // 1 ms
   c->device = dev;
   for (int k = 0; k < TALLY_K_COUNT; ++k)
@@ -533,6 +574,10 @@ int tally_destroy(tally_ctx *ctx) {
   (void)hipStreamSynchronize(ctx->be);
   (void)hipStreamSynchronize(ctx->ctl);
   (void)hipStreamDestroy(ctx->ctl);
+  for (int i = 0; i < kMaxBeClients; ++i) {
+    if (ctx->client_be[i]) { (void)hipStreamSynchronize(ctx->client_be[i]); (void)hipStreamDestroy(ctx->client_be[i]); }
+    if (ctx->client_ctl[i]) { (void)hipStreamSynchronize(ctx->client_ctl[i]); (void)hipStreamDestroy(ctx->client_ctl[i]); }
+  }
   (void)hipFree(ctx->dev_pool);
   (void)hipFree(ctx->copy_pool);
   (void)hipHostFree(ctx->host_pool);
@@ -668,11 +713,11 @@ int tally_wait(tally_job *job, int *state) {
     if (st == TALLY_JOB_STOPPED || st == TALLY_JOB_COMPLETE) break;
     // a kernel that failed after enqueue would leave the status word unwritten for ever
     if ((spins & 0xFFFFu) == 0) {
-      hipError_t q = hipStreamQuery(job->ctx->be);
+      hipError_t q = hipStreamQuery(job->be);
       if (q != hipSuccess && q != hipErrorNotReady) { g_last_hip = (int)q; return TALLY_ERR_HIP; }
     }
   }
-  HIPCHK(hipStreamSynchronize(job->ctx->be));
+  HIPCHK(hipStreamSynchronize(job->be));
   if (state) *state = job->state.load();
   return TALLY_OK;
 }
@@ -682,10 +727,10 @@ int tally_job_free(tally_job *job) {
   tally_ctx *ctx = job->ctx;
   if (job->state.load() == TALLY_JOB_RUNNING) {
     job->stop_issuing = true;
-    (void)hipStreamSynchronize(ctx->be);
+    (void)hipStreamSynchronize(job->be);
   }
   if (job->cover) {
-    (void)hipStreamSynchronize(ctx->be);
+    (void)hipStreamSynchronize(job->be);
     (void)hipFree(job->cover);
   }
   if (job->kind == KIND_PTB) refresh(job);  // learn the counter's final value for the slot
@@ -700,7 +745,7 @@ int tally_coverage(tally_job *job, void *host_records, size_t bytes) {
   if (bytes != sizeof(tally_cover_rec) * (size_t)job->total) return TALLY_ERR_INVALID_ARG;
   refresh(job);
   if (job->state.load() == TALLY_JOB_RUNNING) return TALLY_ERR_BAD_STATE;
-  HIPCHK(hipStreamSynchronize(job->ctx->be));
+  HIPCHK(hipStreamSynchronize(job->be));
   HIPCHK(hipMemcpy(host_records, job->cover, bytes, hipMemcpyDeviceToHost));
   return TALLY_OK;
 }
@@ -817,6 +862,12 @@ int tally_profile(tally_ctx *ctx, const tally_kernel_desc *desc, tally_config *c
     if (cands[i].kind == 0) {
       cands[i].turnaround_ms = (float)tally_ptb_turnaround_ms(
           cands[i].latency_ms, cands[i].param, cands[i].chunk ? cands[i].chunk : 1, total);
+      // a body that pauses inside its blocks hands the execution units over after a share
+      // of ONE block, whatever the chunk: Eq. 1 with chunk 1, times that share
+      const double share = ctx->yield_ticks ? ops->pause_fraction(desc->args) : 1.0;
+      if (share < 1.0)
+        cands[i].turnaround_ms = (float)(tally_ptb_turnaround_ms(cands[i].latency_ms, cands[i].param,
+                                                                 1, total) * share);
     } else {
       uint64_t slices = (total + cands[i].param - 1) / cands[i].param;
       cands[i].turnaround_ms = (float)(cands[i].latency_ms / (double)slices);
@@ -851,9 +902,9 @@ int launch_be_item(tally_ctx *ctx, const tally_be_item *it, tally_job **out) {
   int rc = new_job(ctx, it->kernel, KIND_NATIVE, 0, &j);
   if (rc) return rc;
   j->state = TALLY_JOB_RUNNING;
-  hipError_t e = j->ops->native(ctx->be, j->args, j->grid, 0u);
+  hipError_t e = j->ops->native(j->be, j->args, j->grid, 0u);
   if (e == hipSuccess) {
-    hipLaunchKernelGGL(marker_kernel, dim3(1), dim3(64), 0, ctx->be,
+    hipLaunchKernelGGL(marker_kernel, dim3(1), dim3(64), 0, j->be,
                        (uint32_t *)(j->h_base_dev() + 128), 1u);
     e = hipGetLastError();
   }
@@ -882,101 +933,187 @@ namespace {
 struct SchedShared {
   std::atomic<bool> hi_active{false};
   std::atomic<bool> stop{false};
-  // slot and epoch of the persistent-worker segment now running: what the
-  // high-priority thread needs in order to raise the flag without touching the job
-  std::atomic<uint64_t> ptb_token{0};
+  // per best-effort client, slot and epoch of its persistent-worker segment now running:
+  // what the high-priority thread needs in order to raise the flag without touching the job
+  std::atomic<uint64_t> ptb_token[kMaxBeClients];
   std::atomic<double> t_preempt{0.0};
   std::atomic<int> rc{TALLY_OK};
+  SchedShared() { for (auto &t : ptb_token) t = 0; }
 };
 
 constexpr uint64_t kNoToken = 0;
 
-void be_thread_main(tally_ctx *ctx, tally_sched_run_t *run, SchedShared *sh, double t0, double t_end) {
-  tally_job *be = nullptr;
-  uint32_t be_idx = 0;
+// One best-effort client: its own step of kernels, its own stream pair, one kernel in
+// flight at a time (Figure 4 visits every best-effort client on every pass).
+struct BeClient {
+  uint32_t first = 0, count = 0, idx = 0;  // its items in run->be_items
+  hipStream_t be = nullptr, ctl = nullptr;
+  tally_job *job = nullptr;
   bool preempt_seen = false;  // a preemption request was raised against the current segment
+  uint64_t kernels_done = 0, steps_done = 0;
+  // admission among best-effort clients: what the client's resident workgroups occupy on
+  // one compute unit (zero while it has none), and its place in the queue of clients
+  // that want to put workgroups on the GPU (0 = not asking)
+  uint32_t lds = 0, waves = 0, regs = 0;
+  uint64_t ticket = 0;
+};
+
+// Per-compute-unit demand of the workgroups a best-effort item puts on the GPU at once
+// (all its workers; one slice; the whole grid for a native launch), spread evenly.
+int item_demand(tally_ctx *ctx, const tally_be_item *it, uint32_t *lds, uint32_t *waves, uint32_t *regs) {
+  const KernelOps *ops;
+  tally_dim3 g;
+  int rc = check_desc(it->kernel, &ops, &g);
+  if (rc) return rc;
+  // per kernel id, asked of the runtime once (only the best-effort thread comes here)
+  static uint32_t known[TALLY_K_COUNT], fl[TALLY_K_COUNT], fw[TALLY_K_COUNT], fr[TALLY_K_COUNT];
+  const uint32_t id = it->kernel->kernel_id;
+  if (!known[id]) {
+    fl[id] = 0; fw[id] = 4; fr[id] = 128;
+    if (ops->footprint) HIPCHK(ops->footprint(&fl[id], &fw[id], &fr[id]));
+    known[id] = 1;
+  }
+  const uint32_t l = fl[id], w = fw[id], r = fr[id];
+  const uint64_t total = (uint64_t)g.x * g.y * g.z;
+  uint64_t groups = it->config.kind == 2 ? total : it->config.param;
+  if (groups > total) groups = total;
+  const uint64_t per_cu = (groups + ctx->num_cus - 1) / ctx->num_cus;
+  const uint64_t cap = 64;  // beyond any compute unit's capacity: keeps the products small
+  const uint32_t n = (uint32_t)(per_cu < cap ? per_cu : cap);
+  *lds = n * l;
+  *waves = n * w;
+  *regs = n * ((w + 3) / 4) * r;  // per SIMD: a workgroup's waves go round the four SIMDs
+  return TALLY_OK;
+}
+
+
+void be_thread_main(tally_ctx *ctx, tally_sched_run_t *run, SchedShared *sh, BeClient *clients,
+                    uint32_t n_clients, double t0, double t_end) {
   int rc = TALLY_OK;
+  // A kernel is put on the GPU only if all the workgroups it brings fit beside the
+  // best-effort workgroups already resident: a dispatch that waits for resources blocks
+  // its hardware pipe for every queue mapped to that pipe, the high-priority queue
+  // possibly among them (two 128 KB-LDS GEMMs launched together held high-priority
+  // kernels back for milliseconds).  Clients that have to wait are served first come,
+  // first served.  A client with the GPU to itself is always admitted.
+  uint64_t next_ticket = 0;
+  auto admit = [&](uint32_t c, const tally_be_item *it) -> bool {
+    BeClient &cl = clients[c];
+    if (cl.ticket == 0) cl.ticket = ++next_ticket;
+    uint32_t lds = 0, waves = 0, regs = 0, others = 0;
+    for (uint32_t o = 0; o < n_clients; ++o) {
+      if (o == c) continue;
+      if (clients[o].ticket != 0 && clients[o].ticket < cl.ticket) return false;
+      if (clients[o].waves) others++;
+      lds += clients[o].lds;
+      waves += clients[o].waves;
+      regs += clients[o].regs;
+    }
+    uint32_t l, w, r;
+    if (item_demand(ctx, it, &l, &w, &r) != TALLY_OK) return true;  // the launch reports it
+    if (others && (lds + l > ctx->lds_per_cu || waves + w > 32u || regs + r > 512u)) return false;
+    cl.lds = l;
+    cl.waves = w;
+    cl.regs = r;
+    cl.ticket = 0;
+    return true;
+  };
+  auto vacate = [&](BeClient &cl) { cl.lds = cl.waves = cl.regs = 0; };
   if (hipSetDevice(ctx->device) != hipSuccess) {
     sh->rc = TALLY_ERR_HIP;
     return;
   }
-  auto publish = [&](tally_job *j) {
+  auto publish = [&](uint32_t c, tally_job *j) {
     if (j && j->kind == KIND_PTB && j->state.load() == TALLY_JOB_RUNNING)
-      sh->ptb_token = ((uint64_t)(j->slot + 1) << 32) | j->epoch;
+      sh->ptb_token[c] = ((uint64_t)(j->slot + 1) << 32) | j->epoch;
     else
-      sh->ptb_token = kNoToken;
+      sh->ptb_token[c] = kNoToken;
   };
-  for (;;) {
-    const double now = now_us() - t0;
-    const bool closing = sh->stop.load() || (run->n_arrivals == 0 && now >= t_end);
-    const bool hold = run->policy != 2 && sh->hi_active.load();
-    if (be) {
-      if (hold && !preempt_seen && be->state.load() == TALLY_JOB_RUNNING) {
-        // the other thread raised the flag (persistent workers); for the other kinds
-        // "preempt" means that nothing further is issued until the request is done
-        preempt_seen = true;
-        if (be->t_preempt.load() == 0.0) be->t_preempt = sh->t_preempt.load();
-        if (be->kind == KIND_SLICED) be->stop_issuing = true;
-      }
-      refresh(be);
-      int st = be->state.load();
-      if (st != TALLY_JOB_RUNNING) publish(nullptr);
-      if (st == TALLY_JOB_RUNNING && !hold && preempt_seen && be->kind == KIND_PTB) {
-        // the request is over and the job has not drained (its workers sit inside long
-        // blocks, pausing): withdraw the flag instead of waiting for a drain and relaunch
-        (void)tally_resume(be);
-        preempt_seen = false;
-      }
-      if (st == TALLY_JOB_COMPLETE) {
-        tally_job_free(be);
-        be = nullptr;
-        preempt_seen = false;
-        run->be_kernels_done++;
-        if (++be_idx == run->n_be_items) { be_idx = 0; run->be_steps_done++; }
-      } else if (st == TALLY_JOB_STOPPED) {
-        if (preempt_seen && be->preempt_latency_us >= 0.0) {
-          if (run->preempt_latency_us && run->n_preempts < run->preempt_cap)
-            run->preempt_latency_us[run->n_preempts] = be->preempt_latency_us;
-          run->n_preempts++;
+  bool done = false;
+  while (!done && rc == TALLY_OK) {
+    uint32_t idle = 0;
+    for (uint32_t c = 0; c < n_clients && rc == TALLY_OK; ++c) {
+      BeClient &cl = clients[c];
+      tally_job *&be = cl.job;
+      const double now = now_us() - t0;
+      const bool closing = sh->stop.load() || (run->n_arrivals == 0 && now >= t_end);
+      const bool hold = run->policy != 2 && sh->hi_active.load();
+      if (be) {
+        if (hold && !cl.preempt_seen && be->state.load() == TALLY_JOB_RUNNING) {
+          // the other thread raised the flag (persistent workers); for the other kinds
+          // "preempt" means that nothing further is issued until the request is done
+          cl.preempt_seen = true;
+          if (be->t_preempt.load() == 0.0) be->t_preempt = sh->t_preempt.load();
+          if (be->kind == KIND_SLICED) be->stop_issuing = true;
         }
-        preempt_seen = false;
-        if (closing) {
+        refresh(be);
+        int st = be->state.load();
+        if (st != TALLY_JOB_RUNNING) publish(c, nullptr);
+        if (st == TALLY_JOB_RUNNING && !hold && cl.preempt_seen && be->kind == KIND_PTB) {
+          // the request is over and the job has not drained (its workers sit inside long
+          // blocks, pausing): withdraw the flag instead of waiting for a drain and relaunch
+          (void)tally_resume(be);
+          cl.preempt_seen = false;
+        }
+        if (st != TALLY_JOB_RUNNING) vacate(cl);
+        if (st == TALLY_JOB_COMPLETE) {
           tally_job_free(be);
           be = nullptr;
-        } else if (!hold) {
-          rc = tally_resume(be);
-          if (rc) break;
-          publish(be);
-          if (run->policy != 2 && sh->hi_active.load()) (void)tally_preempt(be);
-        }
-      } else if (be->kind == KIND_SLICED) {
-        if (closing) be->stop_issuing = true;
-        if (!hold && !closing) {
-          rc = sliced_issue(be);
-          if (rc) break;
-        }
-      } else if (closing && be->kind == KIND_PTB) {
-        (void)tally_preempt(be);
-      }
-    }
-    if (!be) {
-      if (closing) break;
-      if (!hold) {
-        rc = launch_be_item(ctx, &run->be_items[be_idx], &be);
-        if (rc) break;
-        publish(be);
-        // a request that arrived while this launch was being made has used the old
-        // token: raise the flag of the new segment here
-        if (run->policy == 0 && sh->hi_active.load() && be->kind == KIND_PTB) {
-          be->t_preempt = sh->t_preempt.load();
+          cl.preempt_seen = false;
+          cl.kernels_done++;
+          if (++cl.idx == cl.count) { cl.idx = 0; cl.steps_done++; }
+        } else if (st == TALLY_JOB_STOPPED) {
+          if (cl.preempt_seen && be->preempt_latency_us >= 0.0) {
+            if (run->preempt_latency_us && run->n_preempts < run->preempt_cap)
+              run->preempt_latency_us[run->n_preempts] = be->preempt_latency_us;
+            run->n_preempts++;
+          }
+          cl.preempt_seen = false;
+          if (closing) {
+            tally_job_free(be);
+            be = nullptr;
+          } else if (!hold && admit(c, &run->be_items[cl.first + cl.idx])) {
+            rc = tally_resume(be);
+            if (rc) break;
+            publish(c, be);
+            if (run->policy != 2 && sh->hi_active.load()) (void)tally_preempt(be);
+          }
+        } else if (be->kind == KIND_SLICED) {
+          if (closing) be->stop_issuing = true;
+          if (!hold && !closing) {
+            rc = sliced_issue(be);
+            if (rc) break;
+          }
+        } else if (closing && be->kind == KIND_PTB) {
           (void)tally_preempt(be);
-          preempt_seen = true;
+        }
+      }
+      if (!be) {
+        if (closing) { idle++; continue; }
+        if (!hold && admit(c, &run->be_items[cl.first + cl.idx])) {
+          ctx->cur_be = cl.be;
+          ctx->cur_ctl = cl.ctl;
+          rc = launch_be_item(ctx, &run->be_items[cl.first + cl.idx], &be);
+          ctx->cur_be = ctx->be;
+          ctx->cur_ctl = ctx->ctl;
+          if (rc) break;
+          publish(c, be);
+          // a request that arrived while this launch was being made has used the old
+          // token: raise the flag of the new segment here
+          if (run->policy == 0 && sh->hi_active.load() && be->kind == KIND_PTB) {
+            be->t_preempt = sh->t_preempt.load();
+            (void)tally_preempt(be);
+            cl.preempt_seen = true;
+          }
         }
       }
     }
+    done = idle == n_clients;
   }
-  publish(nullptr);
-  if (be) tally_job_free(be);
+  for (uint32_t c = 0; c < n_clients; ++c) {
+    publish(c, nullptr);
+    if (clients[c].job) { tally_job_free(clients[c].job); clients[c].job = nullptr; }
+  }
   if (rc) sh->rc = rc;
 }
 
@@ -1006,6 +1143,42 @@ extern "C" int tally_sched_run(tally_ctx *ctx, tally_sched_run_t *run) {
     if (rc) return rc;
     if (run->be_items[i].config.kind != 2 && !ops->transformable) return TALLY_ERR_UNSUPPORTED;
   }
+  // best-effort clients: one owning every item unless the caller splits them up
+  BeClient clients[kMaxBeClients];
+  uint32_t n_clients = run->n_be_items ? 1 : 0;
+  if (run->n_be_items && run->n_be_clients) {
+    if (!run->be_client_items || run->n_be_clients > (uint32_t)kMaxBeClients) return TALLY_ERR_INVALID_ARG;
+    uint64_t sum = 0;
+    for (uint32_t c = 0; c < run->n_be_clients; ++c) {
+      if (run->be_client_items[c] == 0) return TALLY_ERR_INVALID_ARG;
+      sum += run->be_client_items[c];
+    }
+    if (sum != run->n_be_items) return TALLY_ERR_INVALID_ARG;
+    n_clients = run->n_be_clients;
+  }
+  // Every client needs two hardware queues (kernels, relays) beside the null stream's and
+  // the high-priority stream's.  HIP folds streams onto GPU_MAX_HW_QUEUES hardware queues
+  // (4 unless the environment says otherwise), and streams that share one run in order:
+  // a high-priority kernel behind a relay would wait for a whole best-effort kernel.
+  if (n_clients > 1) {
+    const char *env = getenv("GPU_MAX_HW_QUEUES");
+    const long have = env ? strtol(env, nullptr, 10) : 4;
+    if (have < (long)(2 + 2 * n_clients)) return TALLY_ERR_UNSUPPORTED;
+  }
+  for (uint32_t c = 0, first = 0; c < n_clients; ++c) {
+    clients[c].first = first;
+    clients[c].count = run->n_be_clients ? run->be_client_items[c] : run->n_be_items;
+    first += clients[c].count;
+    if (c == 0) {
+      clients[c].be = ctx->be;
+      clients[c].ctl = ctx->ctl;
+    } else {  // further clients get a stream pair of their own, made once per context
+      if (!ctx->client_be[c]) HIPCHK(hipStreamCreateWithFlags(&ctx->client_be[c], hipStreamNonBlocking));
+      if (!ctx->client_ctl[c]) HIPCHK(hipStreamCreateWithFlags(&ctx->client_ctl[c], hipStreamNonBlocking));
+      clients[c].be = ctx->client_be[c];
+      clients[c].ctl = ctx->client_ctl[c];
+    }
+  }
   HIPCHK(hipStreamSynchronize(ctx->hi));
   HIPCHK(hipStreamSynchronize(ctx->be));
 
@@ -1020,12 +1193,12 @@ extern "C" int tally_sched_run(tally_ctx *ctx, tally_sched_run_t *run) {
   int rc = TALLY_OK;
   const double t0 = now_us();
   std::thread be_thread;
-  if (run->n_be_items) be_thread = std::thread(be_thread_main, ctx, run, &sh, t0, t_end);
+  if (n_clients) be_thread = std::thread(be_thread_main, ctx, run, &sh, clients, n_clients, t0, t_end);
 
   // ---- high-priority client (this thread) ----------------------------------------------
   uint32_t next_arrival = 0, cur = 0, completed = 0;
   bool inflight = false;
-  uint64_t raised_tok = kNoToken;
+  uint64_t raised_tok[kMaxBeClients] = {};
   while (rc == TALLY_OK && sh.rc.load() == TALLY_OK) {
     const double now = now_us() - t0;
     if (inflight) {
@@ -1038,11 +1211,12 @@ extern "C" int tally_sched_run(tally_ctx *ctx, tally_sched_run_t *run) {
         // a queued request keeps the best-effort client held; otherwise release it and
         // withdraw the request, so that workers pausing inside a block carry on at once
         if (!(next_arrival < run->n_arrivals && run->arrivals_us[next_arrival] <= now)) {
-          if (raised_tok != kNoToken) {
-            uint32_t slot = (uint32_t)(raised_tok >> 32) - 1;
+          for (uint32_t c = 0; c < n_clients; ++c) {
+            if (raised_tok[c] == kNoToken) continue;
+            uint32_t slot = (uint32_t)(raised_tok[c] >> 32) - 1;
             __atomic_store_n((uint32_t *)(ctx->host_pool + slot * kHostSlotBytes), 0u,
                              __ATOMIC_RELEASE);
-            raised_tok = kNoToken;
+            raised_tok[c] = kNoToken;
           }
           sh.hi_active = false;
         }
@@ -1051,14 +1225,15 @@ extern "C" int tally_sched_run(tally_ctx *ctx, tally_sched_run_t *run) {
     if (!inflight && next_arrival < run->n_arrivals && run->arrivals_us[next_arrival] <= now) {
       cur = next_arrival++;
       sh.hi_active = true;
-      if (run->policy == 0) {  // preempt_best_effort_kernel(): one store to pinned memory
-        uint64_t tok = sh.ptb_token.load();
+      if (run->policy == 0) {  // preempt_best_effort_kernel(): one store to pinned memory each
         sh.t_preempt = now_us();
-        if (tok != kNoToken) {
+        for (uint32_t c = 0; c < n_clients; ++c) {
+          uint64_t tok = sh.ptb_token[c].load();
+          if (tok == kNoToken) continue;
           uint32_t slot = (uint32_t)(tok >> 32) - 1;
           __atomic_store_n((uint32_t *)(ctx->host_pool + slot * kHostSlotBytes), (uint32_t)tok,
                            __ATOMIC_RELEASE);
-          raised_tok = tok;
+          raised_tok[c] = tok;
         }
       }
       for (uint32_t i = 0; i < run->n_hi_kernels && rc == TALLY_OK; ++i)
@@ -1075,6 +1250,12 @@ extern "C" int tally_sched_run(tally_ctx *ctx, tally_sched_run_t *run) {
   sh.hi_active = false;
   if (be_thread.joinable()) be_thread.join();
   run->window_us = now_us() - t0;
+  for (uint32_t c = 0; c < n_clients; ++c) {
+    run->be_kernels_done += clients[c].kernels_done;
+    if (run->be_client_kernels_done) run->be_client_kernels_done[c] = clients[c].kernels_done;
+    (void)hipStreamSynchronize(clients[c].be);
+  }
+  run->be_steps_done = n_clients ? clients[0].steps_done : 0;
   (void)hipStreamSynchronize(ctx->hi);
   (void)hipStreamSynchronize(ctx->be);
   if (rc == TALLY_OK) rc = sh.rc.load();

@@ -113,5 +113,27 @@ def poisson_arrivals_us(rate_per_s, count, config_index, stream=7):
     return np.cumsum(gaps)
 
 
+def bursty_arrivals_us(mean_rate_per_s, count, config_index, burst=50.0, p_on=0.02,
+                       mean_segment_us=20000.0, stream=8):
+    """Open-loop arrivals of an on/off-modulated Poisson process with the given mean rate:
+    time is cut into segments of exponential length; a segment is "on" with probability
+    p_on and then has `burst` times the arrival rate of an "off" segment (load spikes of
+    tens of times the average, as production inference traces show)."""
+    rng = rng_for(config_index, stream)
+    rate_off = mean_rate_per_s / (1.0 - p_on + p_on * burst)
+    out, t = [], 0.0
+    while len(out) < count:
+        seg = rng.exponential(mean_segment_us)
+        rate = rate_off * (burst if rng.random() < p_on else 1.0)
+        u = t
+        while True:
+            u += rng.exponential(1e6 / rate)
+            if u > t + seg or len(out) >= count:
+                break
+            out.append(u)
+        t += seg
+    return np.asarray(out[:count], dtype=np.float64)
+
+
 def periodic_arrivals_us(period_us, count):
     return np.arange(1, count + 1, dtype=np.float64) * period_us

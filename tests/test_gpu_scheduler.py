@@ -63,6 +63,44 @@ def test_solo_runs(env):
     assert be["be_kernels_done"] > 5 and be["window_us"] >= 5000.0
 
 
+def test_several_best_effort_clients_all_progress_and_stay_correct(env):
+    """Three best-effort clients (persistent workers, sliced, persistent workers with a
+    chunked fetch), each on its own stream pair, against a hi-pri SAXPY: every client
+    completes kernels, every request runs once, every output is right."""
+    B, ctx, torch = env
+    from gpu_util import host
+    x0 = torch.rand(1 << 24, device="cuda")
+    p0 = torch.zeros(1 << 12, device="cuda")
+    x1 = torch.rand(1 << 23, device="cuda")
+    p1 = torch.zeros(1 << 11, device="cuda")
+    r2 = torch.randn((4096, 1024), device="cuda")
+    o2 = torch.zeros_like(r2)
+    sx = torch.ones(1 << 16, device="cuda")
+    sy = torch.zeros(1 << 16, device="cuda")
+    torch.cuda.synchronize()
+    items = [(B.reduce_sum(x0, p0), (B.CFG_PTB, 512, 1)),
+             (B.reduce_sum(x1, p1), (B.CFG_SLICED, 256, 1)),
+             (B.softmax_f32(r2, o2), (B.CFG_PTB, 256, 4))]
+    arrivals = TI.poisson_arrivals_us(4000.0, 300, config_index=2)
+    out = ctx.sched_run([B.saxpy(sx, sy, 1.0)], arrivals, items, policy=0, tail_us=500.0,
+                        be_clients=[1, 1, 1])
+    per = out["be_client_kernels_done"]
+    assert (per > 3).all(), per
+    assert out["be_kernels_done"] == per.sum()
+    assert (out["latency_us"] > 0).all() and out["latency_us"].max() < 5e4
+    torch.cuda.synchronize()
+    assert (host(sy) == 300.0).all()
+    for x, p in ((x0, p0), (x1, p1)):
+        want = host(x).reshape(-1, 4096).sum(axis=1, dtype=np.float64)
+        assert np.allclose(host(p), want, rtol=2e-6, atol=0)
+    h = host(r2).astype(np.float64)
+    e = np.exp(h - h.max(axis=1, keepdims=True))
+    assert np.allclose(host(o2), e / e.sum(axis=1, keepdims=True), rtol=1e-5, atol=1e-7)
+    # a client may own several items (its step); two clients, 2 + 1 items
+    out = ctx.sched_run([B.saxpy(sx, sy, 1.0)], arrivals[:100], items, policy=0, be_clients=[2, 1])
+    assert (out["be_client_kernels_done"] > 1).all()
+
+
 def test_scheduler_rejects_bad_input(env):
     B, ctx, torch = env
     import ctypes as C
@@ -72,6 +110,14 @@ def test_scheduler_rejects_bad_input(env):
     run = B.SchedRun()
     run.policy = 7
     assert B.lib().tally_sched_run(ctx.h, C.byref(run)) == B.ERR_INVALID_ARG
+    # client item counts that do not add up to the number of items
+    x = torch.rand(1 << 20, device="cuda")
+    partial = torch.zeros(1 << 8, device="cuda")
+    torch.cuda.synchronize()
+    k = B.reduce_sum(x, partial)
+    for counts in ([2], [1, 1], [0, 1], [1] * 9):
+        with pytest.raises(B.TallyError):
+            ctx.sched_run([], [], [(k, (B.CFG_PTB, 256, 1))], tail_us=100.0, be_clients=counts)
 
 
 def test_profile_picks_a_config_under_the_threshold(env):
