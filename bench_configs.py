@@ -519,12 +519,12 @@ def multi_be(torch, B, ctx, be_stream, args):
     ]
     arrivals = TI.periodic_arrivals_us(1000.0, args.steps + args.warmup)
     w = args.warmup
-    solo = ctx.sched_run(hi, arrivals, [])
-    solo_p50, solo_p99 = pct(solo["latency_us"][w:], 50), pct(solo["latency_us"][w:], 99)
     alone = {}
     for name, k, cfg in clients:
         r = ctx.sched_run([], [], [(k, cfg)], tail_us=0.5e6)
         alone[name] = r["be_kernels_done"] / r["window_us"] * 1e6
+    solo = ctx.sched_run(hi, arrivals, [])
+    solo_p50, solo_p99 = pct(solo["latency_us"][w:], 50), pct(solo["latency_us"][w:], 99)
     rows = {}
     for n in (1, 2, 3, 4):
         items = [(k, cfg) for _, k, cfg in clients[:n]]

@@ -1224,9 +1224,10 @@ extern "C" int tally_sched_run(tally_ctx *ctx, tally_sched_run_t *run) {
     }
     if (!inflight && next_arrival < run->n_arrivals && run->arrivals_us[next_arrival] <= now) {
       cur = next_arrival++;
+      // the request time is published before the flag that makes the other thread read it
+      sh.t_preempt = now_us();
       sh.hi_active = true;
       if (run->policy == 0) {  // preempt_best_effort_kernel(): one store to pinned memory each
-        sh.t_preempt = now_us();
         for (uint32_t c = 0; c < n_clients; ++c) {
           uint64_t tok = sh.ptb_token[c].load();
           if (tok == kNoToken) continue;
