@@ -6,7 +6,7 @@ cfg3  training-like best-effort step (transformer-layer GEMMs, softmax, LayerNor
       persistent-worker form against a 768-hidden inference-like layer, Poisson 100/s
 cfg4  the cfg3 step against decode-like kernels (two GEMVs + attention), Poisson 200/s
 
-sweep_threshold  turnaround-latency threshold sweep (Section 5.5 sensitivity): the profiler's
+sweep_threshold  turnaround-latency threshold sweep (Section 5.6): the profiler's
       choice per threshold, and what the hi-pri job and the best-effort job get under it
 sweep_load       hi-pri load from 10 % to 90 % duty, plus a bursty arrival pattern
 multi_be         one to four best-effort clients against the cfg1 hi-pri GEMV
@@ -353,7 +353,7 @@ def _coloc_stats(B, ctx, hi, arrivals, items, warm, solo_p99, tput_solo):
 
 
 def sweep_threshold(torch, B, ctx, be_stream, args):
-    """Section 5.5 varies the turnaround-latency threshold from 0.01 ms to 10 ms.  Part (a):
+    """Section 5.6 varies the turnaround-latency threshold from 0.01 ms to 10 ms.  Part (a):
     one streaming kernel (the 2^28 sum) with sliced and persistent-worker candidates whose
     Eq.-1 estimates span 1 us to a whole kernel; part (b): the transformer-layer step with
     per-kernel candidates.  Candidates are measured once; each threshold then selects from
@@ -438,7 +438,7 @@ def sweep_threshold(torch, B, ctx, be_stream, args):
 
 
 def sweep_load(torch, B, ctx, be_stream, args):
-    """Section 5.4 varies the load of the inference service.  Hi-pri: the 768-hidden
+    """Section 5.3 varies the load of the inference service.  Hi-pri: the 768-hidden
     inference layer (9 kernels); its duty cycle = arrival rate x solo latency is set to
     10 ... 90 %; best-effort: the 4096^3 GEMM as persistent workers.  A bursty arrival
     pattern (30 % mean duty; 2 ms bursts at ten times the off-burst rate, which overload the
@@ -491,7 +491,7 @@ def sweep_load(torch, B, ctx, be_stream, args):
 
 
 def multi_be(torch, B, ctx, be_stream, args):
-    """Section 5.5 adds best-effort clients.  Hi-pri: the cfg1 GEMV every 1 ms.  Best-effort
+    """Section 5.4 adds best-effort clients.  Hi-pri: the cfg1 GEMV every 1 ms.  Best-effort
     clients, each a loop over one kernel on its own stream pair: (0) bf16 GEMM 4096^3,
     (1) fp32 sum of 2^26, (2) fp32 softmax 65536 x 2048, (3) a second GEMM 4096^3."""
     import tally_inputs as TI
