@@ -83,7 +83,8 @@ typedef struct { const float *partial; double *total; uint32_t count; } tally_re
  * accumulated in fp32 and rounded to nearest-even bf16 once.  Batch z uses element
  * strides stride_a/b/c.  Block (bx, by, bz) owns the output tile rows [T by, T by + T),
  * columns [T bx, T bx + T) of batch bz, T = 256 (GEMM_BF16: m, n multiples of 256 and
- * k a multiple of 32 required) or T = 64 (GEMM_BF16_SMALL: any m, n; k multiple of 32). */
+ * k a multiple of 32 required) or T = 64 (GEMM_BF16_SMALL: any m, n; k multiple of 32).
+ * A, Bt (and for GEMM_BF16 also C) 16-byte aligned, strides multiples of 8 elements. */
 typedef struct {
   const uint16_t *A; const uint16_t *Bt; uint16_t *C;
   uint32_t m, n, k, batch;

@@ -251,6 +251,8 @@ struct GemmBody {
       mma(fa0, fb0);
       __builtin_amdgcn_sched_barrier(0);
     }
+    // every wave is past its last fragment read: the ring can be reused as staging space
+    __syncthreads();
     mma(fa1, fb1);
     // The accumulators are read below through inline assembly, which the compiler's
     // hazard recogniser cannot see into: keep the last MFMAs from being interleaved with
@@ -259,27 +261,50 @@ struct GemmBody {
     asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory");
     __builtin_amdgcn_sched_barrier(0);
 
-    // epilogue: lane l, register r of a 32x32 block holds row 8 (r/4) + 4 (l/32) + r%4,
-    // column l%32
+    // Epilogue.  Lane l, register r of a 32x32 block holds row 8 (r/4) + 4 (l/32) + r%4,
+    // column l%32: stored straight from there a wave instruction would write 2 bytes per
+    // lane.  Each wave instead stages its 128x128 sub-tile through LDS, 64 rows at a time
+    // (a region of its own, rows 272 bytes apart so that the two half-waves of a write and
+    // the four rows of a read fall into different banks), and writes whole 256-byte row
+    // pieces, 16 bytes per lane.  Registers r and r+1 are adjacent rows: one hardware
+    // conversion packs both (round to nearest even) and the halves go to LDS separately.
+    // Each accumulator is read where it is used: a wholesale copy of the 256 accumulators
+    // into arithmetic registers would double the wave's register footprint, which decides
+    // how many other waves fit beside this one.
+    typedef float f32x2_t __attribute__((ext_vector_type(2)));
+    typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+    constexpr uint32_t PITCH = 272;
+    unsigned char *stage = tally_dyn_lds + wave * (64 * PITCH);
+    const uint32_t w_row = (lane >> 5) * 4, w_col = (lane & 31) * 2;
+    const uint32_t r_row = lane >> 4, r_chunk = lane & 15;
     uint16_t *gC = a.C + bz * a.stride_c;
-    const uint32_t row0 = by * TILE + wm * 128 + (lane >> 5) * 4;
-    const uint32_t col0 = bx * TILE + wn * 128 + (lane & 31);
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int h = 0; h < 2; ++h) {
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
+      for (int ii = 0; ii < 2; ++ii)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          uint32_t row = row0 + i * 32 + (r >> 2) * 8 + (r & 3);
-          uint32_t col = col0 + j * 32;
-          // read each accumulator where it is used: a wholesale copy of the 256
-          // accumulators into arithmetic registers would double the wave's register
-          // footprint, which decides how many other waves fit beside this one
-          float v;
-          asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(v) : "a"(acc[i][j][r]));
-          gC[(uint64_t)row * a.n + col] = f32_to_bf16(v);
-        }
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+          for (int r = 0; r < 16; r += 2) {
+            float v0, v1;
+            asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(v0) : "a"(acc[2 * h + ii][j][r]));
+            asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(v1) : "a"(acc[2 * h + ii][j][r + 1]));
+            const f32x2_t p = {v0, v1};
+            const uint32_t pk = __builtin_bit_cast(uint32_t, __builtin_convertvector(p, bf16x2_t));
+            const uint32_t row = ii * 32 + (r >> 2) * 8 + w_row + (r & 3);
+            unsigned char *w = stage + row * PITCH + j * 64 + w_col;
+            *reinterpret_cast<uint16_t *>(w) = (uint16_t)pk;
+            *reinterpret_cast<uint16_t *>(w + PITCH) = (uint16_t)(pk >> 16);
+          }
+#pragma unroll
+      for (int t = 0; t < 16; ++t) {
+        const uint32_t row = t * 4 + r_row;
+        const uint4 v = *reinterpret_cast<const uint4 *>(stage + row * PITCH + r_chunk * 16);
+        const uint32_t grow = by * TILE + wm * 128 + h * 64 + row;
+        const uint32_t gcol = bx * TILE + wn * 128 + r_chunk * 8;
+        *reinterpret_cast<uint4 *>(gC + (uint64_t)grow * a.n + gcol) = v;
       }
+    }
   }
 };
 

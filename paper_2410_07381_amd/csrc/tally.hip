@@ -159,6 +159,7 @@ int grid_gemm(const void *p, tally_dim3 *g, tally_dim3 *b) {
   int rc = grid_gemm_common(a);
   if (rc) return rc;
   if ((a->m % 256) || (a->n % 256) || (a->k % 32)) return TALLY_ERR_INVALID_ARG;
+  if (!aligned16(a->C) || (a->stride_c % 8)) return TALLY_ERR_INVALID_ARG;  // 16-byte stores
   *g = {a->n / 256, a->m / 256, a->batch};
   *b = kBlock256;
   return TALLY_OK;
