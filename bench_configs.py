@@ -183,7 +183,7 @@ def _be_step(torch, B):
         ("qkv_gemm", B.gemm_bf16(X, Wqkv, QKV), 2.0 * T * 3 * H * H, 0),
         ("scores_gemm", B.gemm_bf16(Q, Kh, SC), 2.0 * BATCH * NH * S * S * D, 0),
         ("softmax", B.softmax_f32(P32, P32o), 0, 8.0 * P32.numel()),
-        ("pv_gemm", B.gemm_bf16(Pb, Vt, O, small=True), 2.0 * BATCH * NH * S * S * D, 0),
+        ("pv_gemm", B.gemm_bf16(Pb, Vt, O, n128=True), 2.0 * BATCH * NH * S * S * D, 0),
         ("out_gemm", B.gemm_bf16(X, Wo, AO), 2.0 * T * H * H, 0),
         ("layernorm1", B.layernorm_f32(L32, g, b, L32o, 1e-5), 0, 8.0 * L32.numel()),
         ("ffn1_gemm", B.gemm_bf16(X, W1, H1), 2.0 * T * F * H, 0),
@@ -253,7 +253,7 @@ def _choose_configs(torch, B, ctx, be_stream, step, num_cus):
     for name, k, flops, nbytes in step:
         nat = _time(torch, B, be_stream, lambda: (ctx.launch_native(k), None)[1], reps=3, warm=1)
         tot = k.total_blocks
-        if "gemm" in name and k.kernel_id == B.K_GEMM_BF16:
+        if "gemm" in name and k.kernel_id in (B.K_GEMM_BF16, B.K_GEMM_BF16_N128):
             cands = [(B.CFG_PTB, num_cus, 1)]
         elif "gemm" in name:
             cands = [(B.CFG_PTB, 4 * num_cus, 1), (B.CFG_PTB, 4 * num_cus, 4)]
@@ -403,7 +403,7 @@ def sweep_threshold(torch, B, ctx, be_stream, args):
     solo_b_p99 = pct(solo_b["latency_us"][wb:], 99)
     tables = []
     for name, k, flops, nbytes in step:
-        if k.kernel_id == B.K_GEMM_BF16:
+        if k.kernel_id in (B.K_GEMM_BF16, B.K_GEMM_BF16_N128):
             cs = [(B.CFG_PTB, cu, 1), (B.CFG_SLICED, cu, 1), (B.CFG_SLICED, 4 * cu, 1)]
         elif "gemm" in name:
             cs = [(B.CFG_PTB, 4 * cu, 1), (B.CFG_PTB, 4 * cu, 4), (B.CFG_PTB, 4 * cu, 16),

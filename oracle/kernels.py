@@ -24,6 +24,7 @@ REDUCE_PER_THREAD = 16   # elements each thread of a reduce block sums
 REDUCE_BLOCK = THREADS * REDUCE_PER_THREAD
 GEMM_TILE = 256          # logical output tile edge of the best-effort GEMM
 GEMM_SMALL_TILE = 64     # output tile edge of the ragged-edge GEMM (high-priority layer)
+GEMM_N128_COLS = 128     # column extent of the 256-row x 128-column tile variant
 ROWS_PER_BLOCK = 4       # row-wise kernels: one row per 64-lane wave, 4 waves per block
 
 
@@ -44,6 +45,8 @@ def grid_of(name, args):
     if name == "gemm_bf16_small":
         return (_cdiv(args["n"], GEMM_SMALL_TILE), _cdiv(args["m"], GEMM_SMALL_TILE),
                 args.get("batch", 1))
+    if name == "gemm_bf16_n128":
+        return (_cdiv(args["n"], GEMM_N128_COLS), _cdiv(args["m"], GEMM_TILE), args.get("batch", 1))
     if name == "gemv_bf16":
         return (_cdiv(args["n"], ROWS_PER_BLOCK), 1, 1)
     if name in ("softmax_f32", "layernorm_f32"):
@@ -78,11 +81,12 @@ def _reduce_final(b, grid, a):
     a["total"][0] = math.fsum(a["partial"][: a["count"]].astype(np.float64))
 
 
-def _gemm_tile(b, grid, a, tile):
+def _gemm_tile(b, grid, a, tile, tile_cols=None):
     # C[z, r0:r1, c0:c1] = A[z, r0:r1, :] . Bt[z, c0:c1, :]^T, bf16 in, bf16 out
     bx, by, bz = b
+    tile_cols = tile if tile_cols is None else tile_cols
     r0, r1 = by * tile, min((by + 1) * tile, a["m"])
-    c0, c1 = bx * tile, min((bx + 1) * tile, a["n"])
+    c0, c1 = bx * tile_cols, min((bx + 1) * tile_cols, a["n"])
     if r1 <= r0 or c1 <= c0:
         return
     A = bf16.decode(a["A"][bz, r0:r1, :])
@@ -96,6 +100,10 @@ def _gemm(b, grid, a):
 
 def _gemm_small(b, grid, a):
     _gemm_tile(b, grid, a, GEMM_SMALL_TILE)
+
+
+def _gemm_n128(b, grid, a):
+    _gemm_tile(b, grid, a, GEMM_TILE, GEMM_N128_COLS)
 
 
 def _gemv(b, grid, a):
@@ -148,6 +156,7 @@ _BODIES = {
     "reduce_final": _reduce_final,
     "gemm_bf16": _gemm,
     "gemm_bf16_small": _gemm_small,
+    "gemm_bf16_n128": _gemm_n128,
     "gemv_bf16": _gemv,
     "softmax_f32": _softmax,
     "layernorm_f32": _layernorm,

@@ -30,6 +30,7 @@ LIB_PATH = os.path.join(_HERE, "libtally.so")
 # ---------------------------------------------------------------- enums
 K_SAXPY, K_REDUCE_SUM, K_REDUCE_FINAL, K_GEMM_BF16, K_GEMV_BF16 = 0, 1, 2, 3, 4
 K_SOFTMAX_F32, K_LAYERNORM_F32, K_ATTN_DECODE_BF16, K_GEMM_BF16_SMALL = 5, 6, 7, 8
+K_GEMM_BF16_N128 = 9
 JOB_QUEUED, JOB_RUNNING, JOB_STOPPED, JOB_COMPLETE = 0, 1, 2, 3
 OK, ERR_INVALID_ARG, ERR_BAD_STATE, ERR_HIP, ERR_NOMEM, ERR_UNSUPPORTED = 0, -1, -2, -3, -4, -5
 CFG_PTB, CFG_SLICED, CFG_NATIVE = 0, 1, 2
@@ -194,7 +195,8 @@ def _check(rc, what):
 # ---------------------------------------------------------------- descriptors
 _ARGS_FOR = {
     K_SAXPY: SaxpyArgs, K_REDUCE_SUM: ReduceSumArgs, K_REDUCE_FINAL: ReduceFinalArgs,
-    K_GEMM_BF16: GemmArgs, K_GEMM_BF16_SMALL: GemmArgs, K_GEMV_BF16: GemvArgs,
+    K_GEMM_BF16: GemmArgs, K_GEMM_BF16_SMALL: GemmArgs, K_GEMM_BF16_N128: GemmArgs,
+    K_GEMV_BF16: GemvArgs,
     K_SOFTMAX_F32: SoftmaxArgs, K_LAYERNORM_F32: LayerNormArgs, K_ATTN_DECODE_BF16: AttnDecodeArgs,
 }
 
@@ -244,13 +246,15 @@ def reduce_final(partial, total, count=None):
                   (partial, total))
 
 
-def gemm_bf16(A, Bt, Cout, small=False):
-    """A [batch,m,k], Bt [batch,n,k], C [batch,m,n]; 16-bit storage tensors."""
+def gemm_bf16(A, Bt, Cout, small=False, n128=False):
+    """A [batch,m,k], Bt [batch,n,k], C [batch,m,n]; 16-bit storage tensors.  Tiles of
+    256 x 256 outputs, 256 x 128 with n128, 64 x 64 (ragged edges allowed) with small."""
     batch, m, k = A.shape
     n = Bt.shape[1]
     args = GemmArgs(A.data_ptr(), Bt.data_ptr(), Cout.data_ptr(), m, n, k, batch,
                     m * k, n * k, m * n)
-    return Kernel(K_GEMM_BF16_SMALL if small else K_GEMM_BF16, args, (A, Bt, Cout))
+    kid = K_GEMM_BF16_SMALL if small else (K_GEMM_BF16_N128 if n128 else K_GEMM_BF16)
+    return Kernel(kid, args, (A, Bt, Cout))
 
 
 def gemv_bf16(x, W, y):

@@ -1,4 +1,5 @@
-// bf16 GEMM logical-block body for gfx950: one 256x256 output tile per logical block.
+// bf16 GEMM logical-block body for gfx950: one 256x256 (or 256x128) output tile per logical
+// block.
 //
 // C = A * B with A (m x k) and Bt (n x k) both K-contiguous, so an MFMA operand fragment
 // (8 consecutive bf16 along K) is one 16-byte access for either matrix.  Four 64-lane
@@ -39,15 +40,21 @@ typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4_t;
 typedef const __attribute__((address_space(1))) void *gptr_t;
 typedef __attribute__((address_space(3))) void *lptr_t;
 
-struct GemmBody {
+// NB = 32-column MFMA blocks per wave: 4 gives the 256x256 tile, 2 a 256x128 tile (128
+// accumulators per lane) for operands whose n is only a multiple of 128.
+template <int NB>
+struct GemmBodyT {
+  static_assert(NB == 2 || NB == 4, "two or four column blocks per wave");
   using Args = tally_gemm_bf16_args;
   static constexpr int THREADS = 256;
   static constexpr int MIN_WAVES = 1;
-  static constexpr int TILE = 256;
+  static constexpr int TILE = 256;                        // rows of C per logical block
+  static constexpr int TILE_N = 64 * NB;                  // columns of C per logical block
   static constexpr int BK = 32;
   static constexpr int STAGES = 4;
-  static constexpr int OPB = TILE * BK * 2;               // bytes of one operand in one stage (16 KB)
-  static constexpr unsigned DYN_LDS = 2u * OPB * STAGES;  // 128 KB
+  static constexpr int OPA = TILE * BK * 2;               // bytes of A in one stage (16 KB)
+  static constexpr int OPB = TILE_N * BK * 2;             // bytes of B in one stage
+  static constexpr unsigned DYN_LDS = (unsigned)(OPA + OPB) * STAGES;  // 128 KB / 96 KB
   // every k-step starts with a barrier that follows the LDS reads of the step before, so
   // the next tile's first loads cannot overtake a reader of this tile
   static constexpr bool END_BARRIER = false;
@@ -67,52 +74,66 @@ struct GemmBody {
                                                       uint32_t bz, const YieldCtl ctl) {
     extern __shared__ __align__(1024) unsigned char tally_dyn_lds[];
     unsigned char *sA = tally_dyn_lds;                    // STAGES x 16 KB
-    unsigned char *sB = tally_dyn_lds + STAGES * OPB;
+    unsigned char *sB = tally_dyn_lds + STAGES * OPA;
 
     const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const uint32_t wm = wave >> 1, wn = wave & 1;
     const uint32_t K = a.k;
 
-    // global side of the direct loads: wave w fills rows [64 w, 64 w + 64) of each operand
-    // with 4 loads of 16 rows; lane l supplies row l/4, k-chunk (l%4) xor ((l/16)%4).
-    // Addresses are split into a wave-uniform base that advances by 64 bytes per k-step
-    // (scalar registers) and per-lane byte offsets that never change (8 registers), so the
-    // loop spends no vector instructions on address arithmetic.  The four loads of an
-    // operand share one LDS base (M0) and differ by the instruction's immediate offset,
-    // which also moves the global address; the lane offsets compensate for that.
-    const uint32_t ld_row = wave * 64 + (lane >> 2);
+    // global side of the direct loads: wave w fills rows [64 w, 64 w + 64) of A with 4 loads
+    // of 16 rows and rows [16 NB w, 16 NB (w + 1)) of B with NB loads; lane l supplies row
+    // l/4, k-chunk (l%4) xor ((l/16)%4).  Addresses are split into a wave-uniform base that
+    // advances by 64 bytes per k-step and per-lane byte offsets that never change.  The
+    // loads of an operand share one LDS base (M0) and differ by the instruction's immediate
+    // offset, which also moves the global address; the lane offsets compensate for that.
     const uint32_t ld_kc = (lane & 3) ^ ((lane >> 4) & 3);
     const unsigned char *uA =
         reinterpret_cast<const unsigned char *>(a.A + bz * a.stride_a + (uint64_t)(by * TILE) * K);
     const unsigned char *uB =
-        reinterpret_cast<const unsigned char *>(a.Bt + bz * a.stride_b + (uint64_t)(bx * TILE) * K);
-    uint32_t voff[4];
+        reinterpret_cast<const unsigned char *>(a.Bt + bz * a.stride_b + (uint64_t)(bx * TILE_N) * K);
+    uint32_t voffA[4], voffB[NB];
 #pragma unroll
     for (int j = 0; j < 4; ++j)
-      voff[j] = ((ld_row + 16 * j) * K + ld_kc * 8) * 2 - j * 1024;
-    const uint32_t lds_wave = wave * 64 * BK * 2;         // byte offset of the wave's rows
+      voffA[j] = ((wave * 64 + (lane >> 2) + 16 * j) * K + ld_kc * 8) * 2 - j * 1024;
+#pragma unroll
+    for (int j = 0; j < NB; ++j)
+      voffB[j] = ((wave * 16 * NB + (lane >> 2) + 16 * j) * K + ld_kc * 8) * 2 - j * 1024;
+    const uint32_t ldsA_wave = wave * 64 * BK * 2;        // byte offset of the wave's rows
+    const uint32_t ldsB_wave = wave * 16 * NB * BK * 2;
 
+    // one direct load: 16 rows of A (B) of the 64 (16 NB) a wave contributes to a stage
+    auto load_a = [&](const unsigned char *g, lptr_t l, int j) {
+      if (j == 0) __builtin_amdgcn_global_load_lds((gptr_t)(g + voffA[0]), l, 16, 0, 0);
+      if (j == 1) __builtin_amdgcn_global_load_lds((gptr_t)(g + voffA[1]), l, 16, 1024, 0);
+      if (j == 2) __builtin_amdgcn_global_load_lds((gptr_t)(g + voffA[2]), l, 16, 2048, 0);
+      if (j == 3) __builtin_amdgcn_global_load_lds((gptr_t)(g + voffA[3]), l, 16, 3072, 0);
+    };
+    auto load_b = [&](const unsigned char *g, lptr_t l, int j) {
+      if (j == 0) __builtin_amdgcn_global_load_lds((gptr_t)(g + voffB[0]), l, 16, 0, 0);
+      if (j == 1) __builtin_amdgcn_global_load_lds((gptr_t)(g + voffB[1]), l, 16, 1024, 0);
+      if constexpr (NB > 2) {
+        if (j == 2) __builtin_amdgcn_global_load_lds((gptr_t)(g + voffB[2]), l, 16, 2048, 0);
+        if (j == 3) __builtin_amdgcn_global_load_lds((gptr_t)(g + voffB[3]), l, 16, 3072, 0);
+      }
+    };
     auto issue_loads = [&](uint32_t kt) {
       const uint32_t st = kt & (STAGES - 1);
       const unsigned char *gA = uA + (uint64_t)kt * (BK * 2);
       const unsigned char *gB = uB + (uint64_t)kt * (BK * 2);
-      lptr_t lA = (lptr_t)(sA + st * OPB + lds_wave);
-      lptr_t lB = (lptr_t)(sB + st * OPB + lds_wave);
-      __builtin_amdgcn_global_load_lds((gptr_t)(gA + voff[0]), lA, 16, 0, 0);
-      __builtin_amdgcn_global_load_lds((gptr_t)(gA + voff[1]), lA, 16, 1024, 0);
-      __builtin_amdgcn_global_load_lds((gptr_t)(gA + voff[2]), lA, 16, 2048, 0);
-      __builtin_amdgcn_global_load_lds((gptr_t)(gA + voff[3]), lA, 16, 3072, 0);
-      __builtin_amdgcn_global_load_lds((gptr_t)(gB + voff[0]), lB, 16, 0, 0);
-      __builtin_amdgcn_global_load_lds((gptr_t)(gB + voff[1]), lB, 16, 1024, 0);
-      __builtin_amdgcn_global_load_lds((gptr_t)(gB + voff[2]), lB, 16, 2048, 0);
-      __builtin_amdgcn_global_load_lds((gptr_t)(gB + voff[3]), lB, 16, 3072, 0);
+      lptr_t lA = (lptr_t)(sA + st * OPA + ldsA_wave);
+      lptr_t lB = (lptr_t)(sB + st * OPB + ldsB_wave);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) load_a(gA, lA, j);
+#pragma unroll
+      for (int j = 0; j < NB; ++j) load_b(gB, lB, j);
     };
+    constexpr int LOADS = 4 + NB;                         // direct loads per wave per k-step
 
-    f32x16_t acc[4][4];
+    f32x16_t acc[4][NB];
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
-      for (int j = 0; j < 4; ++j)
+      for (int j = 0; j < NB; ++j)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
@@ -127,83 +148,101 @@ struct GemmBody {
     // fragment reads: lane l takes row (l%32) of a 32-row block and k-chunk 2 ks + l/32
     const uint32_t f_row = lane & 31, f_half = lane >> 5, f_x = (lane >> 2) & 3;
     const uint32_t fA = (wm * 128 + f_row) * (BK * 2);
-    const uint32_t fB = (wn * 128 + f_row) * (BK * 2);
+    const uint32_t fB = (wn * 32 * NB + f_row) * (BK * 2);
     const uint32_t koff0 = ((0u + f_half) ^ f_x) * 16, koff1 = ((2u + f_half) ^ f_x) * 16;
 
     // Two fragment sets: the LDS reads of the next half-step travel while the MFMAs of the
     // current one run.  A wave is alone on its SIMD, so whatever it issues between two
     // MFMAs that does not fit into the 32 cycles the earlier MFMA occupies the matrix pipe
     // leaves the pipe idle.  Reads and direct loads are therefore written, and pinned by
-    // scheduling groups, one at a time between MFMAs: the five reads the first four MFMAs of
-    // the next half need come first, then the remaining three reads alternate with the
-    // half's four direct loads, three MFMAs apart (the four waves issue theirs together and
-    // the address unit takes 16 cycles per 1 KB load).  Reads and direct loads both touch
-    // LDS, so the compiler keeps them in source order: the source order below is the issue
-    // order.  Against reads and loads bunched in front of sixteen MFMAs this took a quarter
-    // of the cycles out of the loop.
-    bf16x8_t fa0[4], fb0[4], fa1[4], fb1[4];
-    auto lfrag = [&](bf16x8_t(&fa)[4], bf16x8_t(&fb)[4], uint32_t kt, uint32_t koff) {
-      const unsigned char *cA = sA + (kt & (STAGES - 1)) * OPB + fA + koff;
+    // scheduling groups, one at a time between MFMAs: the reads the first MFMAs of the next
+    // half need come first, then the remaining reads alternate with the half's direct
+    // loads (with four column blocks three MFMAs apart: the four waves issue theirs
+    // together and the address unit takes 16 cycles per 1 KB load).  Reads and direct loads
+    // both touch LDS, so the compiler keeps them in source order: the source order below is
+    // the issue order.  Against reads and loads bunched in front of sixteen MFMAs this took
+    // a quarter of the cycles out of the loop.
+    bf16x8_t fa0[4], fb0[NB], fa1[4], fb1[NB];
+    auto lfrag = [&](bf16x8_t(&fa)[4], bf16x8_t(&fb)[NB], uint32_t kt, uint32_t koff) {
+      const unsigned char *cA = sA + (kt & (STAGES - 1)) * OPA + fA + koff;
       const unsigned char *cB = sB + (kt & (STAGES - 1)) * OPB + fB + koff;
       fa[0] = *reinterpret_cast<const bf16x8_t *>(cA);
 #pragma unroll
-      for (int t = 0; t < 4; ++t) fb[t] = *reinterpret_cast<const bf16x8_t *>(cB + t * 32 * BK * 2);
+      for (int t = 0; t < NB; ++t) fb[t] = *reinterpret_cast<const bf16x8_t *>(cB + t * 32 * BK * 2);
 #pragma unroll
       for (int t = 1; t < 4; ++t) fa[t] = *reinterpret_cast<const bf16x8_t *>(cA + t * 32 * BK * 2);
     };
-    // one direct load (16 rows of one operand) of the four that fill a wave's share of a stage
-    auto issue_one = [&](const unsigned char *g, lptr_t l, int j) {
-      if (j == 0) __builtin_amdgcn_global_load_lds((gptr_t)(g + voff[0]), l, 16, 0, 0);
-      if (j == 1) __builtin_amdgcn_global_load_lds((gptr_t)(g + voff[1]), l, 16, 1024, 0);
-      if (j == 2) __builtin_amdgcn_global_load_lds((gptr_t)(g + voff[2]), l, 16, 2048, 0);
-      if (j == 3) __builtin_amdgcn_global_load_lds((gptr_t)(g + voff[3]), l, 16, 3072, 0);
-    };
-    // fragment reads of (kt, half) interleaved with the loads of one operand of a later stage
-    auto lfrag_and_loads = [&](bf16x8_t(&fa)[4], bf16x8_t(&fb)[4], uint32_t kt, uint32_t koff,
-                               const unsigned char *g, lptr_t l) {
-      const unsigned char *cA = sA + (kt & (STAGES - 1)) * OPB + fA + koff;
+    // fragment reads of (kt, half) interleaved with the loads of one operand of a later
+    // stage: the three last reads each follow one load, loads left over come after them
+    auto lfrag_and_loads = [&](bf16x8_t(&fa)[4], bf16x8_t(&fb)[NB], uint32_t kt, uint32_t koff,
+                               const unsigned char *g, lptr_t l, bool operand_a) {
+      const unsigned char *cA = sA + (kt & (STAGES - 1)) * OPA + fA + koff;
       const unsigned char *cB = sB + (kt & (STAGES - 1)) * OPB + fB + koff;
+      const int nloads = operand_a ? 4 : NB;
       fa[0] = *reinterpret_cast<const bf16x8_t *>(cA);
 #pragma unroll
-      for (int t = 0; t < 4; ++t) fb[t] = *reinterpret_cast<const bf16x8_t *>(cB + t * 32 * BK * 2);
+      for (int t = 0; t < NB; ++t) fb[t] = *reinterpret_cast<const bf16x8_t *>(cB + t * 32 * BK * 2);
 #pragma unroll
       for (int t = 1; t < 4; ++t) {
-        issue_one(g, l, t - 1);
+        if (t - 1 < nloads) { if (operand_a) load_a(g, l, t - 1); else load_b(g, l, t - 1); }
         fa[t] = *reinterpret_cast<const bf16x8_t *>(cA + t * 32 * BK * 2);
       }
-      issue_one(g, l, 3);
+      if (3 < nloads) { if (operand_a) load_a(g, l, 3); else load_b(g, l, 3); }
     };
-    auto mma = [&](const bf16x8_t(&fa)[4], const bf16x8_t(&fb)[4]) {
+    auto mma = [&](const bf16x8_t(&fa)[4], const bf16x8_t(&fb)[NB]) {
 #pragma unroll
       for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < NB; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
     };
     // issue order of one half-step: M = MFMA (mask 0x8), d = LDS read (0x100), G = direct
-    // load (0x10):  Md Md Md Md Md  MG Md M  MG Md M  MG Md M  MG M
-    auto half_step_order = [&]() {
+    // load (0x10).  Four column blocks:  Md Md Md Md Md  MG Md M  MG Md M  MG Md M  MG M
+    // two column blocks, A half:  Md Md Md  MGd MGd MGd  MG M;  B half:  Md Md Md  MGd MGd  Md M M
+    auto half_step_order = [&](bool operand_a) {
 #pragma unroll
-      for (int i = 0; i < 5; ++i) {
+      for (int i = 0; i < 1 + NB; ++i) {
         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
         __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
       }
+      if constexpr (NB == 4) {
 #pragma unroll
-      for (int i = 0; i < 3; ++i) {
+        for (int i = 0; i < 3; ++i) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        }
         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
         __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);
         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      } else if (operand_a) {
+#pragma unroll
+        for (int i = 0; i < 3; ++i) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      } else {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
       }
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
     };
 
-    // stage 0 has landed once only the two younger stages (8 loads each) are in flight
-    if (nk > 2) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
-    else if (nk > 1) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+    // stage 0 has landed once only the two younger stages are in flight
+    if (nk > 2) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * LOADS) : "memory");
+    else if (nk > 1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LOADS) : "memory");
     else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     lfrag(fa0, fb0, 0, koff0);
@@ -223,23 +262,24 @@ struct GemmBody {
       // one wave polls; the others meet it at the barrier below
       if (ctl.ticks != 0 && wave == 0 && (kt & (YIELD_EVERY - 1)) == YIELD_EVERY - 1)
         yield_while_preempted(ctl);
-      asm volatile("s_waitcnt vmcnt(8)" ::: "memory");  // stage kt+1 complete, kt+2 in flight
+      // stage kt+1 complete, kt+2 in flight
+      asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LOADS) : "memory");
       __syncthreads();  // stage kt+1 is in LDS for everyone; everyone is done with kt-1
       const uint32_t st = (kt + 3) & (STAGES - 1);
       const unsigned char *gA = uA + (uint64_t)(kt + 3) * (BK * 2);
       const unsigned char *gB = uB + (uint64_t)(kt + 3) * (BK * 2);
-      lfrag_and_loads(fa0, fb0, kt + 1, koff0, gA, (lptr_t)(sA + st * OPB + lds_wave));
+      lfrag_and_loads(fa0, fb0, kt + 1, koff0, gA, (lptr_t)(sA + st * OPA + ldsA_wave), true);
       mma(fa1, fb1);
-      half_step_order();
+      half_step_order(true);
       __builtin_amdgcn_sched_barrier(0);
-      lfrag_and_loads(fa1, fb1, kt + 1, koff1, gB, (lptr_t)(sB + st * OPB + lds_wave));
+      lfrag_and_loads(fa1, fb1, kt + 1, koff1, gB, (lptr_t)(sB + st * OPB + ldsB_wave), false);
       mma(fa0, fb0);
-      half_step_order();
+      half_step_order(false);
       __builtin_amdgcn_sched_barrier(0);
     }
     // the last steps drain the ring
     for (; kt + 1 < nk; ++kt) {
-      if (kt + 2 < nk) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+      if (kt + 2 < nk) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LOADS) : "memory");
       else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
       __syncthreads();
       lfrag(fa0, fb0, kt + 1, koff0);
@@ -263,27 +303,30 @@ struct GemmBody {
 
     // Epilogue.  Lane l, register r of a 32x32 block holds row 8 (r/4) + 4 (l/32) + r%4,
     // column l%32: stored straight from there a wave instruction would write 2 bytes per
-    // lane.  Each wave instead stages its 128x128 sub-tile through LDS, 64 rows at a time
-    // (a region of its own, rows 272 bytes apart so that the two half-waves of a write and
-    // the four rows of a read fall into different banks), and writes whole 256-byte row
-    // pieces, 16 bytes per lane.  Registers r and r+1 are adjacent rows: one hardware
-    // conversion packs both (round to nearest even) and the halves go to LDS separately.
-    // Each accumulator is read where it is used: a wholesale copy of the 256 accumulators
-    // into arithmetic registers would double the wave's register footprint, which decides
-    // how many other waves fit beside this one.
+    // lane.  Each wave instead stages its 128 x 32 NB sub-tile through LDS, 64 rows at a time
+    // (a region of its own, rows 16 bytes more than their length apart so that the two
+    // half-waves of a write and the rows of a read fall into different banks), and writes
+    // whole row pieces, 16 bytes per lane.  Registers r and r+1 are adjacent rows: one
+    // hardware conversion packs both (round to nearest even) and the halves go to LDS
+    // separately.  Each accumulator is read where it is used: a wholesale copy of the
+    // accumulators into arithmetic registers would double the wave's register footprint,
+    // which decides how many other waves fit beside this one.
     typedef float f32x2_t __attribute__((ext_vector_type(2)));
     typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
-    constexpr uint32_t PITCH = 272;
+    constexpr uint32_t ROWB = 64 * NB;                    // bytes of a sub-tile row
+    constexpr uint32_t PITCH = ROWB + 16;
+    constexpr uint32_t LPR = ROWB / 16;                   // lanes per row when reading back
+    constexpr uint32_t RPI = 64 / LPR;                    // rows per wave instruction
     unsigned char *stage = tally_dyn_lds + wave * (64 * PITCH);
     const uint32_t w_row = (lane >> 5) * 4, w_col = (lane & 31) * 2;
-    const uint32_t r_row = lane >> 4, r_chunk = lane & 15;
+    const uint32_t r_row = lane / LPR, r_chunk = lane % LPR;
     uint16_t *gC = a.C + bz * a.stride_c;
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
 #pragma unroll
       for (int ii = 0; ii < 2; ++ii)
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < NB; ++j)
 #pragma unroll
           for (int r = 0; r < 16; r += 2) {
             float v0, v1;
@@ -297,16 +340,18 @@ struct GemmBody {
             *reinterpret_cast<uint16_t *>(w + PITCH) = (uint16_t)(pk >> 16);
           }
 #pragma unroll
-      for (int t = 0; t < 16; ++t) {
-        const uint32_t row = t * 4 + r_row;
+      for (uint32_t t = 0; t < 64 / RPI; ++t) {
+        const uint32_t row = t * RPI + r_row;
         const uint4 v = *reinterpret_cast<const uint4 *>(stage + row * PITCH + r_chunk * 16);
         const uint32_t grow = by * TILE + wm * 128 + h * 64 + row;
-        const uint32_t gcol = bx * TILE + wn * 128 + r_chunk * 8;
+        const uint32_t gcol = bx * TILE_N + wn * 32 * NB + r_chunk * 8;
         *reinterpret_cast<uint4 *>(gC + (uint64_t)grow * a.n + gcol) = v;
       }
     }
   }
 };
+using GemmBody = GemmBodyT<4>;
+using GemmN128Body = GemmBodyT<2>;
 
 // Same operator with 64x64 output tiles and predicated edges, for small or ragged
 // problems (the high-priority inference-like layer).  One wave per 32x32 block.

@@ -164,6 +164,16 @@ int grid_gemm(const void *p, tally_dim3 *g, tally_dim3 *b) {
   *b = kBlock256;
   return TALLY_OK;
 }
+int grid_gemm_n128(const void *p, tally_dim3 *g, tally_dim3 *b) {
+  auto *a = static_cast<const tally_gemm_bf16_args *>(p);
+  int rc = grid_gemm_common(a);
+  if (rc) return rc;
+  if ((a->m % 256) || (a->n % 128) || (a->k % 32)) return TALLY_ERR_INVALID_ARG;
+  if (!aligned16(a->C) || (a->stride_c % 8)) return TALLY_ERR_INVALID_ARG;  // 16-byte stores
+  *g = {a->n / 128, a->m / 256, a->batch};
+  *b = kBlock256;
+  return TALLY_OK;
+}
 int grid_gemm_small(const void *p, tally_dim3 *g, tally_dim3 *b) {
   auto *a = static_cast<const tally_gemm_bf16_args *>(p);
   int rc = grid_gemm_common(a);
@@ -238,6 +248,7 @@ const KernelOps kOps[TALLY_K_COUNT] = {
     {"attn_decode_bf16", sizeof(tally_attn_decode_args), false, grid_attn, launch_attn_decode,
      nullptr, nullptr, nullptr, nullptr, nullptr, nullptr},
     OPS(GemmSmallBody, "gemm_bf16_small", grid_gemm_small),
+    OPS(GemmN128Body, "gemm_bf16_n128", grid_gemm_n128),
 };
 
 constexpr size_t kMaxArgs = 96;

@@ -61,6 +61,96 @@ def test_gemm_bf16_forms(env, form):
     assert_bf16_close(host(Cd), a["C"])
 
 
+@pytest.mark.parametrize("k", [32, 64, 96, 128])
+@pytest.mark.parametrize("form", ["native", "ptb"])
+def test_gemm_short_k(env, k, form):
+    """One to four k-steps: fewer than the LDS ring has stages (prologue and drain paths)."""
+    B, ctx, torch = env
+    from gpu_util import dev, host, assert_bf16_close
+    m, n = 256, 512
+    g = TI.gemm_inputs(m, n, k, config_index=3, scale=0.25)
+    a = dict(g, C=np.zeros((1, m, n), np.uint16))
+    OS.run_native("gemm_bf16", OK.grid_of("gemm_bf16", a), a)
+    A, Bt, Cd = dev(g["A"]), dev(g["Bt"]), dev(np.zeros((1, m, n), np.uint16))
+    torch.cuda.synchronize()
+    _run_form(B, ctx, torch, B.gemm_bf16(A, Bt, Cd), form)
+    assert_bf16_close(host(Cd), a["C"])
+
+
+def test_gemm_training_step_shapes(env):
+    """Shapes of the transformer-layer step: attention scores (batched, K = 128, 2048 x 2048
+    outputs per batch) and the second FFN product (K = 16384), persistent workers; the
+    oracle recomputes whole batches / tiles."""
+    B, ctx, torch = env
+    from gpu_util import dev, host, assert_bf16_close
+    g = TI.gemm_inputs(2048, 2048, 128, config_index=3, batch=3, scale=0.25)
+    A, Bt = dev(g["A"]), dev(g["Bt"])
+    Cd = torch.zeros((3, 2048, 2048), dtype=torch.int16, device="cuda")
+    torch.cuda.synchronize()
+    kern = B.gemm_bf16(A, Bt, Cd)
+    assert kern.grid == (8, 8, 3)
+    job = ctx.launch_ptb(kern, 256)
+    assert job.wait() == B.JOB_COMPLETE
+    job.free()
+    a = dict(g, C=np.zeros((3, 2048, 2048), np.uint16))
+    OS.run_native("gemm_bf16", OK.grid_of("gemm_bf16", a), a)
+    assert_bf16_close(host(Cd), a["C"])
+    g = TI.gemm_inputs(512, 256, 16384, config_index=3, scale=1.0 / 128.0)
+    A, Bt = dev(g["A"]), dev(g["Bt"])
+    Cd = torch.zeros((1, 512, 256), dtype=torch.int16, device="cuda")
+    torch.cuda.synchronize()
+    job = ctx.launch_ptb(B.gemm_bf16(A, Bt, Cd), 256)
+    assert job.wait() == B.JOB_COMPLETE
+    job.free()
+    a = dict(g, C=np.zeros((1, 512, 256), np.uint16))
+    OS.run_native("gemm_bf16", OK.grid_of("gemm_bf16", a), a)
+    assert_bf16_close(host(Cd), a["C"])
+
+
+@pytest.mark.parametrize("form", FORMS)
+def test_gemm_n128_forms(env, form):
+    """256-row x 128-column tiles (n a multiple of 128 only): 3 x 2 x 2 tiles, 6 k-steps."""
+    B, ctx, torch = env
+    from gpu_util import dev, host, assert_bf16_close
+    m, n, k, batch = 512, 384, 192, 2
+    g = TI.gemm_inputs(m, n, k, config_index=3, batch=batch, scale=0.125)
+    a = dict(g, C=np.zeros((batch, m, n), np.uint16))
+    OS.run_native("gemm_bf16_n128", OK.grid_of("gemm_bf16_n128", a), a)
+    A, Bt, Cd = dev(g["A"]), dev(g["Bt"]), dev(np.zeros((batch, m, n), np.uint16))
+    torch.cuda.synchronize()
+    kern = B.gemm_bf16(A, Bt, Cd, n128=True)
+    assert kern.grid == (3, 2, 2)
+    _run_form(B, ctx, torch, kern, form)
+    assert_bf16_close(host(Cd), a["C"])
+
+
+@pytest.mark.parametrize("k", [32, 96, 2048])
+def test_gemm_n128_attention_value_shape(env, k):
+    """The P.V product of the training-like step: 2048 x 128 outputs per batch entry."""
+    B, ctx, torch = env
+    from gpu_util import dev, host, assert_bf16_close
+    m, n, batch = 2048, 128, 2
+    g = TI.gemm_inputs(m, n, k, config_index=3, batch=batch, scale=0.05)
+    a = dict(g, C=np.zeros((batch, m, n), np.uint16))
+    OS.run_native("gemm_bf16_n128", OK.grid_of("gemm_bf16_n128", a), a)
+    A, Bt, Cd = dev(g["A"]), dev(g["Bt"]), dev(np.zeros((batch, m, n), np.uint16))
+    torch.cuda.synchronize()
+    kern = B.gemm_bf16(A, Bt, Cd, n128=True)
+    assert kern.grid == (1, 8, 2)
+    job = ctx.launch_ptb(kern, 256)
+    assert job.wait() == B.JOB_COMPLETE
+    job.free()
+    assert_bf16_close(host(Cd), a["C"])
+
+
+def test_gemm_rejects_unaligned_output(env):
+    B, ctx, torch = env
+    A = torch.zeros((1, 256, 64), dtype=torch.int16, device="cuda")
+    Cbuf = torch.zeros(256 * 256 + 8, dtype=torch.int16, device="cuda")
+    with pytest.raises(B.TallyError):
+        B.gemm_bf16(A, A, Cbuf[1:1 + 256 * 256].view(1, 256, 256))
+
+
 def test_gemm_identity_is_exact(env):
     B, ctx, torch = env
     from gpu_util import dev, host

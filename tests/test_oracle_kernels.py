@@ -146,6 +146,16 @@ def test_gemm_elementwise_brute_force_rectangular_batched():
     b = dict(g, C=np.zeros((batch, m, n), np.uint16))
     S.run_native("gemm_bf16_small", K.grid_of("gemm_bf16_small", b), b)
     assert (a["C"] == b["C"]).all()
+    # and through the 256-row x 128-column tiling: grid (5, 2, 2), tile axes not interchangeable
+    c = dict(g, C=np.zeros((batch, m, n), np.uint16))
+    assert K.grid_of("gemm_bf16_n128", c) == (5, 2, 2)
+    S.run_native("gemm_bf16_n128", K.grid_of("gemm_bf16_n128", c), c)
+    assert (a["C"] == c["C"]).all()
+    one = dict(g, C=np.zeros((batch, m, n), np.uint16))
+    K.exec_block("gemm_bf16_n128", (1, 0, 1), (5, 2, 2), one)      # rows 0..255, cols 128..255
+    touched = np.argwhere(one["C"] != 0)
+    assert touched[:, 0].min() == 1 == touched[:, 0].max()
+    assert touched[:, 1].max() <= 255 and 128 <= touched[:, 2].min() and touched[:, 2].max() <= 255
     # library cross-check: torch fp64 matmul of the decoded operands
     A64 = torch.from_numpy(bf16.decode(g["A"]))
     B64 = torch.from_numpy(bf16.decode(g["Bt"]))
