@@ -60,7 +60,7 @@ typedef enum {
   TALLY_K_SOFTMAX_F32 = 5,    /* row softmax, fp32                                          */
   TALLY_K_LAYERNORM_F32 = 6,  /* row LayerNorm with gain and bias, fp32                     */
   TALLY_K_ATTN_DECODE_BF16 = 7, /* one query per head over a bf16 K/V cache (native only)   */
-  TALLY_K_GEMM_BF16_SMALL = 8,  /* same operator as GEMM_BF16 with 64x64 tiles, ragged edges */
+  TALLY_K_GEMM_BF16_SMALL = 8,  /* same operator as GEMM_BF16 with 32x32 tiles, ragged edges */
   TALLY_K_GEMM_BF16_N128 = 9,   /* same operator with tiles of 256 rows x 128 columns         */
   TALLY_K_COUNT = 10
 } tally_kernel_id;
@@ -85,7 +85,7 @@ typedef struct { const float *partial; double *total; uint32_t count; } tally_re
  * strides stride_a/b/c.  Block (bx, by, bz) owns the output tile rows [Tm by, Tm by + Tm),
  * columns [Tn bx, Tn bx + Tn) of batch bz.  GEMM_BF16: Tm = Tn = 256, m and n multiples of
  * 256; GEMM_BF16_N128: Tm = 256, Tn = 128, m a multiple of 256 and n of 128;
- * GEMM_BF16_SMALL: Tm = Tn = 64, any m, n.  k a multiple of 32 in all three.  A, Bt (and
+ * GEMM_BF16_SMALL: Tm = Tn = 32, any m, n.  k a multiple of 32 in all three.  A, Bt (and
  * C, except for GEMM_BF16_SMALL) 16-byte aligned, strides multiples of 8 elements. */
 typedef struct {
   const uint16_t *A; const uint16_t *Bt; uint16_t *C;

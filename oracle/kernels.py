@@ -23,7 +23,7 @@ THREADS = 256            # threads per logical block, all kernels
 REDUCE_PER_THREAD = 16   # elements each thread of a reduce block sums
 REDUCE_BLOCK = THREADS * REDUCE_PER_THREAD
 GEMM_TILE = 256          # logical output tile edge of the best-effort GEMM
-GEMM_SMALL_TILE = 64     # output tile edge of the ragged-edge GEMM (high-priority layer)
+GEMM_SMALL_TILE = 32     # output tile edge of the ragged-edge GEMM (high-priority layer)
 GEMM_N128_COLS = 128     # column extent of the 256-row x 128-column tile variant
 ROWS_PER_BLOCK = 4       # row-wise kernels: one row per 64-lane wave, 4 waves per block
 

@@ -353,65 +353,85 @@ struct GemmBodyT {
 using GemmBody = GemmBodyT<4>;
 using GemmN128Body = GemmBodyT<2>;
 
-// Same operator with 64x64 output tiles and predicated edges, for small or ragged
-// problems (the high-priority inference-like layer).  One wave per 32x32 block.
+// Same operator with 32x32 output tiles and predicated edges, for small or ragged
+// problems (the high-priority inference-like layer), where the grid is far smaller than
+// the GPU and every kernel is a chain of memory latencies.  The four waves of a block
+// split K between them: wave w multiplies the 16-wide k-chunks w, w+4, w+8, ... (together
+// the four waves read whole 128-byte lines of a row), so the serial chain per wave is a
+// quarter as long and four times as many waves have loads in flight; the four partial
+// tiles are summed through LDS.  Operands come straight from global memory / L2.
 struct GemmSmallBody {
   using Args = tally_gemm_bf16_args;
   static constexpr int THREADS = 256;
   static constexpr int MIN_WAVES = 2;
-  static constexpr int TILE = 64;
+  static constexpr int TILE = 32;
   static constexpr unsigned DYN_LDS = 0;
   static constexpr bool YIELDS = false;
-  static constexpr bool END_BARRIER = false;
+  // the partial sums of consecutive blocks of one workgroup share LDS
+  static constexpr bool END_BARRIER = true;
+  static constexpr int BATCH = 8;                         // k-chunks requested together per wave
 
   static __device__ __forceinline__ void run(const Args &a, uint32_t bx, uint32_t by, uint32_t bz) {
-    const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const uint32_t wm = wave >> 1, wn = wave & 1;
+    __shared__ float s_part[4][16][64];                   // [wave][register][lane]
+    const uint32_t tid = threadIdx.x, lane = tid & 63;
+    // the wave index decides trip counts below: as a scalar, those become scalar branches
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const uint32_t K = a.k;
-    const uint32_t arow = by * TILE + wm * 32 + (lane & 31);
-    const uint32_t brow = bx * TILE + wn * 32 + (lane & 31);
+    const uint32_t arow = by * TILE + (lane & 31);
+    const uint32_t brow = bx * TILE + (lane & 31);
     const bool aok = arow < a.m, bok = brow < a.n;
+    // lane l holds row l%32, elements [8 (l/32), 8 (l/32) + 8) of a 16-wide k-chunk
     const uint16_t *pA = a.A + bz * a.stride_a + (uint64_t)(aok ? arow : 0) * K + (lane >> 5) * 8;
     const uint16_t *pB = a.Bt + bz * a.stride_b + (uint64_t)(bok ? brow : 0) * K + (lane >> 5) * 8;
-    f32x16_t acc0, acc1;
-#pragma unroll
-    for (int r = 0; r < 16; ++r) { acc0[r] = 0.f; acc1[r] = 0.f; }
     const uint4 zero = make_uint4(0, 0, 0, 0);
-    // operands straight from global/L2 (the 2x2 waves of a block share rows through the
-    // L1).  The loop is latency-bound, so 128 elements of K (eight 16-byte loads per
-    // operand) are requested before the first of their MFMAs is issued.
-    uint32_t k0 = 0;
-    for (; k0 + 128 <= K; k0 += 128) {
-      uint4 av[8], bv[8];
+    f32x16_t acc;
 #pragma unroll
-      for (int u = 0; u < 8; ++u) {
-        av[u] = aok ? *reinterpret_cast<const uint4 *>(pA + k0 + 16 * u) : zero;
-        bv[u] = bok ? *reinterpret_cast<const uint4 *>(pB + k0 + 16 * u) : zero;
-      }
+    for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+
+    const uint32_t nchunk = K / 16;                       // this wave takes w, w + 4, ...
+    const uint32_t mine = nchunk > wave ? (nchunk - wave + 3) / 4 : 0;
+    // chunks [first, first + BATCH) of this wave's share, as far as they exist
+    auto request = [&](uint4(&av)[BATCH], uint4(&bv)[BATCH], uint32_t first) {
 #pragma unroll
-      for (int u = 0; u < 8; u += 2) {
-        acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, av[u]),
-                                                       __builtin_bit_cast(bf16x8_t, bv[u]), acc0, 0, 0, 0);
-        acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, av[u + 1]),
-                                                       __builtin_bit_cast(bf16x8_t, bv[u + 1]), acc1, 0, 0, 0);
-      }
+      for (int u = 0; u < BATCH; ++u)
+        if (first + u < mine) {
+          const uint32_t k0 = (wave + 4 * (first + u)) * 16;
+          av[u] = aok ? *reinterpret_cast<const uint4 *>(pA + k0) : zero;
+          bv[u] = bok ? *reinterpret_cast<const uint4 *>(pB + k0) : zero;
+        }
+    };
+    auto multiply = [&](const uint4(&av)[BATCH], const uint4(&bv)[BATCH], uint32_t first) {
+#pragma unroll
+      for (int u = 0; u < BATCH; ++u)
+        if (first + u < mine)
+          acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, av[u]),
+                                                        __builtin_bit_cast(bf16x8_t, bv[u]), acc, 0, 0, 0);
+    };
+    // two register sets: the next batch is on its way while the current one is multiplied
+    uint4 a0[BATCH], b0[BATCH], a1[BATCH], b1[BATCH];
+#pragma unroll
+    for (int u = 0; u < BATCH; ++u) a0[u] = b0[u] = a1[u] = b1[u] = zero;
+    request(a0, b0, 0);
+    for (uint32_t c = 0; c < mine; c += 2 * BATCH) {
+      request(a1, b1, c + BATCH);
+      multiply(a0, b0, c);
+      request(a0, b0, c + 2 * BATCH);
+      multiply(a1, b1, c + BATCH);
     }
-    for (; k0 < K; k0 += 32) {
-      uint4 a0 = aok ? *reinterpret_cast<const uint4 *>(pA + k0) : zero;
-      uint4 b0 = bok ? *reinterpret_cast<const uint4 *>(pB + k0) : zero;
-      uint4 a1 = aok ? *reinterpret_cast<const uint4 *>(pA + k0 + 16) : zero;
-      uint4 b1 = bok ? *reinterpret_cast<const uint4 *>(pB + k0 + 16) : zero;
-      acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a0),
-                                                     __builtin_bit_cast(bf16x8_t, b0), acc0, 0, 0, 0);
-      acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a1),
-                                                     __builtin_bit_cast(bf16x8_t, b1), acc1, 0, 0, 0);
-    }
+
+    // sum the four partial tiles: wave w finishes registers 4w .. 4w+3, i.e. rows
+    // 8w + 4 (l/32) + {0..3}, column l%32
+#pragma unroll
+    for (int r = 0; r < 16; ++r) s_part[wave][r][lane] = acc[r];
+    __syncthreads();
     uint16_t *gC = a.C + bz * a.stride_c;
-    const uint32_t col = bx * TILE + wn * 32 + (lane & 31);
+    const uint32_t col = bx * TILE + (lane & 31);
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      uint32_t row = by * TILE + wm * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
-      if (row < a.m && col < a.n) gC[(uint64_t)row * a.n + col] = f32_to_bf16(acc0[r] + acc1[r]);
+    for (int q = 0; q < 4; ++q) {
+      const uint32_t r = wave * 4 + q;
+      const float v = (s_part[0][r][lane] + s_part[1][r][lane]) + (s_part[2][r][lane] + s_part[3][r][lane]);
+      const uint32_t row = by * TILE + wave * 8 + (lane >> 5) * 4 + q;
+      if (row < a.m && col < a.n) gC[(uint64_t)row * a.n + col] = f32_to_bf16(v);
     }
   }
 };

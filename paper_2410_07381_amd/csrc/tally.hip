@@ -179,7 +179,7 @@ int grid_gemm_small(const void *p, tally_dim3 *g, tally_dim3 *b) {
   int rc = grid_gemm_common(a);
   if (rc) return rc;
   if (a->k % 32) return TALLY_ERR_INVALID_ARG;
-  *g = {cdiv(a->n, 64), cdiv(a->m, 64), a->batch};
+  *g = {cdiv(a->n, 32), cdiv(a->m, 32), a->batch};
   *b = kBlock256;
   return TALLY_OK;
 }

@@ -198,7 +198,7 @@ def test_gemm_cfg1_full_size_sampled_tiles(env):
     assert (host(Cd) == 0x3F80).all()
 
 
-# ------------------------------------------------------------------ GEMM, 64-wide ragged tiles
+# ------------------------------------------------------------------ GEMM, 32-wide ragged tiles
 @pytest.mark.parametrize("form", FORMS)
 def test_gemm_small_forms(env, form):
     B, ctx, torch = env

@@ -144,14 +144,14 @@ def test_sliced_preempt_and_resume_segments(env):
 
 # ------------------------------------------------------------------ multi-dimensional grid
 def test_ptb_three_dimensional_grid_mapping(env):
-    """Batched 64-wide GEMM tiles give a (gx, gy, gz) grid: the rebuilt block indices
+    """Batched 32-wide GEMM tiles give a (gx, gy, gz) grid: the rebuilt block indices
     must follow x-fastest order in both transformed forms."""
     B, ctx, torch = env
     from gpu_util import dev, host, assert_cover_equal, assert_bf16_close
     g = TI.gemm_inputs(m=150, n=200, k=64, config_index=1, batch=3)
     a = dict(g, C=np.zeros((3, 150, 200), np.uint16))
     grid = OK.grid_of("gemm_bf16_small", a)
-    assert grid == (4, 3, 3)
+    assert grid == (7, 5, 3)
     A, Bt = dev(g["A"]), dev(g["Bt"])
     Cp, Cs = dev(a["C"]), dev(a["C"])
     torch.cuda.synchronize()

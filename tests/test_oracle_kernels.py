@@ -142,7 +142,7 @@ def test_gemm_elementwise_brute_force_rectangular_batched():
             acc += _one_bf16(g["A"][z, i, kk]) * _one_bf16(g["Bt"][z, j, kk])
         got = _one_bf16(a["C"][z, i, j])
         assert abs(got - acc) <= 2.0 ** -8 * abs(acc) + 1e-30
-    # same result through the 64-wide tiling (each element written once either way)
+    # same result through the 32-wide tiling (each element written once either way)
     b = dict(g, C=np.zeros((batch, m, n), np.uint16))
     S.run_native("gemm_bf16_small", K.grid_of("gemm_bf16_small", b), b)
     assert (a["C"] == b["C"]).all()
