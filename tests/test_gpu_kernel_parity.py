@@ -277,6 +277,34 @@ def test_attn_decode(env, tokens, heads, scale):
     out = dev(np.zeros((heads, 128), np.uint16))
     scratch = torch.zeros(B.attn_decode_scratch_bytes(heads), dtype=torch.uint8, device="cuda")
     torch.cuda.synchronize()
+    kern = B.attn_decode_bf16(q, Kc, Vc, out, scratch)
+    ctx.launch_native(kern, hi=True)
+    torch.cuda.synchronize()
+    assert_bf16_close(host(out), a["out"])
+    # the scratch serves later calls as it is
+    first = host(out).copy()
+    for _ in range(3):
+        out.zero_()
+        ctx.launch_native(kern, hi=True)
+    torch.cuda.synchronize()
+    assert (host(out) == first).all()
+
+
+def test_attn_decode_longest_cache(env):
+    """16 splits x 2048 tokens is the longest cache one call takes; one token more is refused."""
+    B, ctx, torch = env
+    from gpu_util import dev, host, assert_bf16_close
+    tokens, heads = 16 * 2048, 2
+    at = TI.attn_decode_inputs(tokens, heads, 128, scale=0.5)
+    a = dict(at, out=np.zeros((heads, 128), np.uint16))
+    OS.run_native("attn_decode_bf16", OK.grid_of("attn_decode_bf16", a), a)
+    q, Kc, Vc = dev(at["q"]), dev(at["K"]), dev(at["V"])
+    out = dev(np.zeros((heads, 128), np.uint16))
+    scratch = torch.zeros(B.attn_decode_scratch_bytes(heads), dtype=torch.uint8, device="cuda")
+    torch.cuda.synchronize()
     ctx.launch_native(B.attn_decode_bf16(q, Kc, Vc, out, scratch), hi=True)
     torch.cuda.synchronize()
     assert_bf16_close(host(out), a["out"])
+    Kbig = torch.zeros((tokens + 1, heads, 128), dtype=torch.int16, device="cuda")
+    with pytest.raises(B.TallyError):
+        B.attn_decode_bf16(q, Kbig, Kbig, out, scratch)
