@@ -52,6 +52,18 @@ def _time(torch, B, stream, launch, reps=10, warm=2, wait_before_stop=False):
     return float(np.mean(us)), float(np.min(us))
 
 
+def _cap(B, ctx, kernel, cands):
+    """Persistent-worker candidates are multiples of the compute-unit count that fit (all
+    workers resident at once): clamp to the kernel's limit and drop duplicates."""
+    mw = ctx.max_workers(kernel)
+    out = []
+    for kind, param, chunk in cands:
+        c = (kind, min(param, mw) if kind == B.CFG_PTB else param, chunk)
+        if c not in out:
+            out.append(c)
+    return out
+
+
 def _bf16(torch, shape, scale):
     return (torch.randn(shape, device="cuda") * scale).to(torch.bfloat16).view(torch.int16)
 
@@ -144,7 +156,7 @@ def cfg2(torch, B, ctx, be_stream, args):
         }
     cands = [(B.CFG_PTB, 512, 32), (B.CFG_PTB, 512, 8), (B.CFG_PTB, 1024, 2), (B.CFG_PTB, 256, 1),
              (B.CFG_SLICED, 4096, 1), (B.CFG_SLICED, 512, 1)]
-    meas, chosen = ctx.profile(red, cands, runs=10, threshold_ms=0.0316)
+    meas, chosen = ctx.profile(red, _cap(B, ctx, red, cands), runs=10, threshold_ms=0.0316)
     out["profile_guided_choice"] = {"threshold_ms": 0.0316, "chosen": meas[chosen],
                                     "candidates": meas}
     return out
@@ -260,7 +272,7 @@ def _choose_configs(torch, B, ctx, be_stream, step, num_cus):
         else:
             cands = [(B.CFG_PTB, 2 * num_cus, 4), (B.CFG_PTB, 4 * num_cus, 2),
                      (B.CFG_PTB, 2 * num_cus, 16)]
-        meas, chosen = ctx.profile(k, cands, runs=3, threshold_ms=0.0316)
+        meas, chosen = ctx.profile(k, _cap(B, ctx, k, cands), runs=3, threshold_ms=0.0316)
         c = meas[chosen]
         ptb = _time(torch, B, be_stream, lambda: ctx.launch_ptb(k, c["param"], chunk=c["chunk"]),
                     reps=3, warm=1)
@@ -305,7 +317,15 @@ def _colocate(torch, B, ctx, be_stream, args, hi, rate, cfg_index, label):
     return {
         "workload": label,
         "hi_pri_latency_us": {"solo_p50": pct(ls, 50), "solo_p99": pct(ls, 99),
-                              "coloc_p50": pct(lc, 50), "coloc_p99": pct(lc, 99), "n": len(lc)},
+                              "coloc_p50": pct(lc, 50), "coloc_p99": pct(lc, 99), "n": len(lc),
+                              # host share: scheduled arrival -> launch calls returned (includes
+                              # waiting behind the previous request); the rest is the device's
+                              "issue_solo_p99": pct(solo_hi["issue_us"][w:], 99),
+                              "issue_coloc_p99": pct(co["issue_us"][w:], 99),
+                              "after_launch_calls_solo_p99":
+                                  pct((solo_hi["latency_us"] - solo_hi["issue_us"])[w:], 99),
+                              "after_launch_calls_coloc_p99":
+                                  pct((co["latency_us"] - co["issue_us"])[w:], 99)},
         "p99_overhead_pct": (pct(lc, 99) - pct(ls, 99)) / pct(ls, 99) * 100.0,
         "p50_overhead_pct": (pct(lc, 50) - pct(ls, 50)) / pct(ls, 50) * 100.0,
         "be_tput_retained_pct": tput_co / tput_solo * 100.0,
@@ -375,7 +395,7 @@ def sweep_threshold(torch, B, ctx, be_stream, args):
              (B.CFG_PTB, 256, 1), (B.CFG_PTB, 1024, 1), (B.CFG_PTB, 2048, 1),
              (B.CFG_PTB, 1024, 2), (B.CFG_PTB, 512, 8), (B.CFG_PTB, 2048, 4),
              (B.CFG_PTB, 512, 32), (B.CFG_PTB, 256, 256)]
-    meas, _ = ctx.profile(red, cands, runs=10, threshold_ms=0.0316)
+    meas, _ = ctx.profile(red, _cap(B, ctx, red, cands), runs=10, threshold_ms=0.0316)
     nat_item = [(red, (B.CFG_NATIVE, 1, 1))]
     be_solo = ctx.sched_run([], [], nat_item, tail_us=1e6)
     tput_solo = be_solo["be_kernels_done"] / be_solo["window_us"]
@@ -411,7 +431,7 @@ def sweep_threshold(torch, B, ctx, be_stream, args):
         else:
             cs = [(B.CFG_PTB, 2 * cu, 1), (B.CFG_PTB, 2 * cu, 4), (B.CFG_PTB, 2 * cu, 16),
                   (B.CFG_PTB, 4 * cu, 64), (B.CFG_SLICED, 16 * cu, 1)]
-        m, _ = ctx.profile(k, cs, runs=3, threshold_ms=0.0316)
+        m, _ = ctx.profile(k, _cap(B, ctx, k, cs), runs=3, threshold_ms=0.0316)
         tables.append((name, k, m))
     nat_items = [(k, (B.CFG_NATIVE, 1, 1)) for _, k, _, _ in step]
     be_solo_b = ctx.sched_run([], [], nat_items, tail_us=2e6)

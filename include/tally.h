@@ -160,9 +160,18 @@ int tally_launch_sliced(tally_ctx *ctx, const tally_kernel_desc *desc, uint32_t 
  * num_workers worker blocks loop { check flag; fetch-and-add the global task counter;
  * map the task index to the logical block index; run the block; barrier }.
  * `chunk` (>= 1) is the number of consecutive task indices taken per fetch; 1 is the
- * paper's form.  A fetched index is always executed before the worker exits. */
+ * paper's form.  A fetched index is always executed before the worker exits.
+ * num_workers must not exceed tally_max_workers(): every worker has to be resident at
+ * once (Section 4.2 draws its candidates from the multiples of the compute-unit count
+ * that fit).  Workgroups that wait for room keep their hardware queue's dispatcher busy,
+ * and then neither the relay of the preemption flag nor a high-priority kernel is sure
+ * to start before the kernel ends.  TALLY_ERR_INVALID_ARG otherwise. */
 int tally_launch_ptb(tally_ctx *ctx, const tally_kernel_desc *desc, uint32_t num_workers,
                      uint32_t chunk, int coverage, tally_job **out);
+
+/* Largest worker count of the persistent-worker form of this kernel whose workgroups are
+ * all resident at once on an otherwise idle GPU: compute units x workgroups per unit. */
+int tally_max_workers(tally_ctx *ctx, const tally_kernel_desc *desc, uint32_t *max_workers);
 
 /* Non-blocking.  Persistent-worker job: raise its preemption flag (one host store);
  * workers finish their current block(s) and exit.  Sliced job: stop issuing
@@ -295,7 +304,10 @@ typedef struct {
 } tally_sched_run_t;
 
 /* Run the scheduling loop on the calling thread until every arrival has completed and
- * tail_us has elapsed.  n_arrivals == 0 runs the best-effort job alone for tail_us;
+ * tail_us has elapsed.  Best-effort workers pause inside their blocks while preempted
+ * (where the kernel supports it) only if every high-priority kernel of the request fits
+ * beside the paused workers on a compute unit; otherwise that item's workers give way at
+ * block boundaries only.  n_arrivals == 0 runs the best-effort job alone for tail_us;
  * n_be_items == 0 runs the high-priority job alone. */
 int tally_sched_run(tally_ctx *ctx, tally_sched_run_t *run);
 

@@ -42,7 +42,7 @@ EXPORTS = [
     "tally_resume", "tally_progress", "tally_pump", "tally_wait", "tally_job_free",
     "tally_launch_ptb_until", "tally_resume_until", "tally_coverage", "tally_marker",
     "tally_marker_read", "tally_last_preempt_latency_us", "tally_last_hip_error",
-    "tally_strerror", "tally_device_info", "tally_ptb_turnaround_ms", "tally_select_config",
+    "tally_strerror", "tally_max_workers", "tally_device_info", "tally_ptb_turnaround_ms", "tally_select_config",
     "tally_profile", "tally_lookup_config", "tally_sched_run", "tally_set_yield_bound_us",
 ]
 
@@ -384,6 +384,12 @@ class Context:
         out = [dict(kind=c.kind, param=c.param, chunk=c.chunk, latency_ms=c.latency_ms,
                     turnaround_ms=c.turnaround_ms) for c in arr]
         return out, chosen.value
+
+    def max_workers(self, kernel):
+        """Largest worker count whose workgroups are all resident at once."""
+        n = C.c_uint32()
+        _check(_lib.tally_max_workers(self.h, C.byref(kernel.desc), C.byref(n)), "tally_max_workers")
+        return n.value
 
     def lookup_config(self, kernel):
         c = Config()

@@ -363,13 +363,16 @@ using GemmN128Body = GemmBodyT<2>;
 struct GemmSmallBody {
   using Args = tally_gemm_bf16_args;
   static constexpr int THREADS = 256;
-  static constexpr int MIN_WAVES = 2;
+  // at most 128 registers per lane: that is what a resident 256x256 GEMM tile leaves free
+  // on a SIMD, and a high-priority kernel that does not fit beside the paused tiles of a
+  // best-effort GEMM waits for them
+  static constexpr int MIN_WAVES = 4;
   static constexpr int TILE = 32;
   static constexpr unsigned DYN_LDS = 0;
   static constexpr bool YIELDS = false;
   // the partial sums of consecutive blocks of one workgroup share LDS
   static constexpr bool END_BARRIER = true;
-  static constexpr int BATCH = 8;                         // k-chunks requested together per wave
+  static constexpr int BATCH = 6;                         // k-chunks requested together per wave
 
   static __device__ __forceinline__ void run(const Args &a, uint32_t bx, uint32_t by, uint32_t bz) {
     __shared__ float s_part[4][16][64];                   // [wave][register][lane]

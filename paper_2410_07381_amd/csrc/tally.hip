@@ -61,6 +61,8 @@ struct KernelOps {
   double (*pause_fraction)(const void *args);
   // what one workgroup of the persistent-worker kernel occupies on a compute unit
   hipError_t (*footprint)(uint32_t *lds_bytes, uint32_t *waves, uint32_t *regs_per_lane);
+  // the same for one workgroup of the kernel in its original form
+  hipError_t (*footprint_native)(uint32_t *lds_bytes, uint32_t *waves, uint32_t *regs_per_lane);
 };
 
 template <class Body>
@@ -117,6 +119,26 @@ hipError_t footprint_t(uint32_t *lds_bytes, uint32_t *waves, uint32_t *regs_per_
   if (e != hipSuccess) return e;
   *lds_bytes = (uint32_t)attr.sharedSizeBytes + Body::DYN_LDS;
   *waves = Body::THREADS / 64;
+  *regs_per_lane = ((uint32_t)attr.numRegs + 7u) & ~7u;
+  return hipSuccess;
+}
+
+template <class Body>
+hipError_t footprint_native_t(uint32_t *lds_bytes, uint32_t *waves, uint32_t *regs_per_lane) {
+  hipFuncAttributes attr;
+  hipError_t e = hipFuncGetAttributes(&attr, (const void *)native_kernel<Body>);
+  if (e != hipSuccess) return e;
+  *lds_bytes = (uint32_t)attr.sharedSizeBytes + Body::DYN_LDS;
+  *waves = Body::THREADS / 64;
+  *regs_per_lane = ((uint32_t)attr.numRegs + 7u) & ~7u;
+  return hipSuccess;
+}
+hipError_t footprint_attn(uint32_t *lds_bytes, uint32_t *waves, uint32_t *regs_per_lane) {
+  hipFuncAttributes attr;
+  hipError_t e = hipFuncGetAttributes(&attr, (const void *)attn_decode_partial);
+  if (e != hipSuccess) return e;
+  *lds_bytes = (uint32_t)attr.sharedSizeBytes;
+  *waves = 4;
   *regs_per_lane = ((uint32_t)attr.numRegs + 7u) & ~7u;
   return hipSuccess;
 }
@@ -235,7 +257,7 @@ double pause_fraction_t(const void *args) {
 #define OPS(Body, nm, gridfn)                                                              \
   {nm, sizeof(Body::Args), true, gridfn, launch_native_t<Body>, launch_sliced_t<Body>,     \
    launch_ptb_t<Body>, init_t<Body>, occupancy_t<Body>, pause_fraction_t<Body>,              \
-   footprint_t<Body>}
+   footprint_t<Body>, footprint_native_t<Body>}
 
 const KernelOps kOps[TALLY_K_COUNT] = {
     OPS(SaxpyBody, "saxpy", grid_saxpy),
@@ -246,7 +268,7 @@ const KernelOps kOps[TALLY_K_COUNT] = {
     OPS(SoftmaxBody, "softmax_f32", grid_softmax),
     OPS(LayerNormBody, "layernorm_f32", grid_layernorm),
     {"attn_decode_bf16", sizeof(tally_attn_decode_args), false, grid_attn, launch_attn_decode,
-     nullptr, nullptr, nullptr, nullptr, nullptr, nullptr},
+     nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, footprint_attn},
     OPS(GemmSmallBody, "gemm_bf16_small", grid_gemm_small),
     OPS(GemmN128Body, "gemm_bf16_n128", grid_gemm_n128),
 };
@@ -281,6 +303,7 @@ struct tally_ctx {
   uint32_t *marker_dev;
   uint32_t num_cus;
   uint32_t lds_per_cu;
+  uint32_t max_workers[TALLY_K_COUNT];  // persistent-worker workgroups resident at once, per kernel
   uint32_t yield_ticks;      // bound of a mid-block pause, 10 ns ticks
   int device;
   int live_jobs;
@@ -301,6 +324,7 @@ struct tally_job {
   std::atomic<uint32_t> progress;
   // persistent workers
   uint32_t workers, chunk, epoch, limit;
+  uint32_t yield_ticks;      // the context's pause bound when the job was made
   uint32_t counter_base;     // raw counter value standing for task index 0
   uint32_t segments;         // launch segments so far
   bool counter_dirty;        // counter overshot a stop_at limit and must be rewound
@@ -371,6 +395,7 @@ int new_job(tally_ctx *ctx, const tally_kernel_desc *desc, int kind, int coverag
   j->progress = 0;
   j->workers = j->chunk = j->epoch = j->segments = 0;
   j->counter_base = ctx->slot_counter[slot];
+  j->yield_ticks = ctx->yield_ticks;
   j->limit = j->total;
   j->counter_dirty = false;
   j->slice_blocks = j->max_in_flight = j->next_off = j->issued = j->retired = j->segment = 0;
@@ -403,6 +428,9 @@ int ptb_launch_segment(tally_job *j, uint32_t limit) {
     uint32_t raw = j->counter_base + j->progress.load();
     hipLaunchKernelGGL(set_word_kernel, dim3(1), dim3(64), 0, j->be, j->d_counter(), raw);
     HIPCHK(hipGetLastError());
+    // the relay below runs on another stream and mirrors the counter to the host: it must
+    // not see the value from before the rewind (the job is drained, the stream is idle)
+    HIPCHK(hipStreamSynchronize(j->be));
     ctx->slot_counter[slot] = raw;
     j->counter_dirty = false;
   }
@@ -427,26 +455,31 @@ int ptb_launch_segment(tally_job *j, uint32_t limit) {
   c.segment = j->segments;
   c.gx = j->grid.x;
   c.gy = j->grid.y;
-  c.yield_ticks = ctx->yield_ticks;
+  c.yield_ticks = j->yield_ticks;
   c.flag_copies = ctx->copy_pool + (size_t)slot * (kCopySlotBytes / sizeof(uint32_t));
-  hipError_t e = j->ops->ptb(j->be, j->args, c);
+  // The relay goes first, on its own stream: once the workers are on the GPU there may be
+  // no wave slot or register left anywhere for it (four 128-register softmax workgroups
+  // fill a compute unit exactly), and without the relay a request is never seen.  Its exit
+  // depends only on the slot's exit counter reaching the target, so it may start early.
+  hipLaunchKernelGGL(relay_kernel, dim3(1), dim3(64), 0, j->ctl, c);
+  hipError_t e = hipGetLastError();
   if (e != hipSuccess) {  // nothing was enqueued: the slot's bookkeeping is unchanged
     g_last_hip = (int)e;
     return TALLY_ERR_HIP;
   }
+  e = j->ops->ptb(j->be, j->args, c);
   ctx->slot_epoch[slot] = j->epoch;
   ctx->slot_exited[slot] = c.exit_target;
+  if (e != hipSuccess) {
+    // no workers will ever count themselves out: do it for them, so that the relay ends
+    g_last_hip = (int)e;
+    hipLaunchKernelGGL(set_word_kernel, dim3(1), dim3(64), 0, j->be, j->d_exited(), c.exit_target);
+    (void)hipGetLastError();
+    return TALLY_ERR_HIP;
+  }
   j->segments += 1;
   j->t_preempt = 0.0;
   j->state = TALLY_JOB_RUNNING;
-  // the relay runs beside the workers on its own stream and ends with them; without it
-  // the job still completes but cannot be preempted
-  hipLaunchKernelGGL(relay_kernel, dim3(1), dim3(64), 0, j->ctl, c);
-  e = hipGetLastError();
-  if (e != hipSuccess) {
-    g_last_hip = (int)e;
-    return TALLY_ERR_HIP;
-  }
   return TALLY_OK;
 }
 
@@ -564,12 +597,22 @@ int tally_create(tally_ctx **out, void *hip_stream_hi, void *hip_stream_be) {
   c->lds_per_cu = (uint32_t)prop.maxSharedMemoryPerMultiProcessor;
   c->yield_ticks = 100000;  // 1 ms
   c->device = dev;
-  for (int k = 0; k < TALLY_K_COUNT; ++k)
+  for (int k = 0; k < TALLY_K_COUNT; ++k) {
     if (kOps[k].init && (e = kOps[k].init()) != hipSuccess) {
       g_last_hip = (int)e;
       tally_destroy(c);
       return TALLY_ERR_HIP;
     }
+    int per_cu = 0;
+    c->max_workers[k] = 0;
+    if (kOps[k].occupancy) {
+      if (kOps[k].occupancy(&per_cu) != TALLY_OK || per_cu < 1) {
+        tally_destroy(c);
+        return TALLY_ERR_HIP;
+      }
+      c->max_workers[k] = (uint32_t)per_cu * c->num_cus;
+    }
+  }
   if ((e = attn_decode_init()) != hipSuccess) {
     g_last_hip = (int)e;
     tally_destroy(c);
@@ -639,8 +682,11 @@ int tally_launch_sliced(tally_ctx *ctx, const tally_kernel_desc *desc, uint32_t 
 
 int tally_launch_ptb_until(tally_ctx *ctx, const tally_kernel_desc *desc, uint32_t num_workers,
                            uint32_t chunk, uint64_t stop_at, int coverage, tally_job **out) {
-  if (!ctx || !out || num_workers == 0 || chunk == 0) return TALLY_ERR_INVALID_ARG;
-  if (num_workers > (1u << 20) || chunk > (1u << 16)) return TALLY_ERR_INVALID_ARG;
+  if (!ctx || !out || !desc || num_workers == 0 || chunk == 0) return TALLY_ERR_INVALID_ARG;
+  if (desc->kernel_id >= TALLY_K_COUNT || chunk > (1u << 16)) return TALLY_ERR_INVALID_ARG;
+  // every worker resident at once (an unsupported kernel is reported by new_job below)
+  if (kOps[desc->kernel_id].transformable && num_workers > ctx->max_workers[desc->kernel_id])
+    return TALLY_ERR_INVALID_ARG;
   tally_job *j;
   int rc = new_job(ctx, desc, KIND_PTB, coverage, &j);
   if (rc) return rc;
@@ -655,6 +701,13 @@ int tally_launch_ptb_until(tally_ctx *ctx, const tally_kernel_desc *desc, uint32
 int tally_launch_ptb(tally_ctx *ctx, const tally_kernel_desc *desc, uint32_t num_workers,
                      uint32_t chunk, int coverage, tally_job **out) {
   return tally_launch_ptb_until(ctx, desc, num_workers, chunk, ~0ull, coverage, out);
+}
+
+int tally_max_workers(tally_ctx *ctx, const tally_kernel_desc *desc, uint32_t *max_workers) {
+  if (!ctx || !desc || !max_workers || desc->kernel_id >= TALLY_K_COUNT) return TALLY_ERR_INVALID_ARG;
+  if (!kOps[desc->kernel_id].transformable) return TALLY_ERR_UNSUPPORTED;
+  *max_workers = ctx->max_workers[desc->kernel_id];
+  return TALLY_OK;
 }
 
 int tally_preempt(tally_job *job) {
@@ -977,7 +1030,8 @@ int item_demand(tally_ctx *ctx, const tally_be_item *it, uint32_t *lds, uint32_t
   tally_dim3 g;
   int rc = check_desc(it->kernel, &ops, &g);
   if (rc) return rc;
-  // per kernel id, asked of the runtime once (only the best-effort thread comes here)
+  // per kernel id, asked of the runtime once (the scheduling call before it starts its
+  // best-effort thread, then only that thread, come here)
   static uint32_t known[TALLY_K_COUNT], fl[TALLY_K_COUNT], fw[TALLY_K_COUNT], fr[TALLY_K_COUNT];
   const uint32_t id = it->kernel->kernel_id;
   if (!known[id]) {
@@ -1000,7 +1054,7 @@ int item_demand(tally_ctx *ctx, const tally_be_item *it, uint32_t *lds, uint32_t
 
 
 void be_thread_main(tally_ctx *ctx, tally_sched_run_t *run, SchedShared *sh, BeClient *clients,
-                    uint32_t n_clients, double t0, double t_end) {
+                    uint32_t n_clients, const std::vector<uint8_t> *pause_ok, double t0, double t_end) {
   int rc = TALLY_OK;
   // A kernel is put on the GPU only if all the workgroups it brings fit beside the
   // best-effort workgroups already resident: a dispatch that waits for resources blocks
@@ -1105,7 +1159,12 @@ void be_thread_main(tally_ctx *ctx, tally_sched_run_t *run, SchedShared *sh, BeC
         if (!hold && admit(c, &run->be_items[cl.first + cl.idx])) {
           ctx->cur_be = cl.be;
           ctx->cur_ctl = cl.ctl;
+          // workers may pause inside their blocks only if every high-priority kernel fits
+          // beside the paused blocks; otherwise they stop at block boundaries and drain
+          const uint32_t bound = ctx->yield_ticks;
+          if (!(*pause_ok)[cl.first + cl.idx]) ctx->yield_ticks = 0;
           rc = launch_be_item(ctx, &run->be_items[cl.first + cl.idx], &be);
+          ctx->yield_ticks = bound;
           ctx->cur_be = ctx->be;
           ctx->cur_ctl = ctx->ctl;
           if (rc) break;
@@ -1121,6 +1180,9 @@ void be_thread_main(tally_ctx *ctx, tally_sched_run_t *run, SchedShared *sh, BeC
       }
     }
     done = idle == n_clients;
+    // both scheduling threads poll; where the host has fewer free cores than pollers the
+    // high-priority thread must not wait out a time slice (milliseconds) behind this one
+    std::this_thread::yield();
   }
   for (uint32_t c = 0; c < n_clients; ++c) {
     publish(c, nullptr);
@@ -1154,6 +1216,9 @@ extern "C" int tally_sched_run(tally_ctx *ctx, tally_sched_run_t *run) {
     int rc = check_desc(run->be_items[i].kernel, &ops, &g);
     if (rc) return rc;
     if (run->be_items[i].config.kind != 2 && !ops->transformable) return TALLY_ERR_UNSUPPORTED;
+    if (run->be_items[i].config.kind == 0 &&
+        run->be_items[i].config.param > ctx->max_workers[run->be_items[i].kernel->kernel_id])
+      return TALLY_ERR_INVALID_ARG;
   }
   // best-effort clients: one owning every item unless the caller splits them up
   BeClient clients[kMaxBeClients];
@@ -1191,6 +1256,30 @@ extern "C" int tally_sched_run(tally_ctx *ctx, tally_sched_run_t *run) {
       clients[c].ctl = ctx->client_ctl[c];
     }
   }
+  // A best-effort worker that pauses inside a block keeps its registers and LDS.  A
+  // high-priority kernel that does not fit beside such workers would wait for them while
+  // they wait for the request to end (until the pause bound): those items run without the
+  // pause and give way at block boundaries only.
+  std::vector<uint8_t> pause_ok(run->n_be_items, 1);
+  if (run->n_arrivals) {
+    uint32_t hl = 0, hw = 0, hr = 0;  // largest demand of one high-priority workgroup
+    for (uint32_t i = 0; i < run->n_hi_kernels; ++i) {
+      const KernelOps *ops = &kOps[run->hi_kernels[i].kernel_id];
+      uint32_t l = 0, w = 4, r = 128;
+      if (ops->footprint_native) HIPCHK(ops->footprint_native(&l, &w, &r));
+      hl = l > hl ? l : hl;
+      hw = w > hw ? w : hw;
+      const uint32_t per_simd = ((w + 3) / 4) * r;
+      hr = per_simd > hr ? per_simd : hr;
+    }
+    for (uint32_t i = 0; i < run->n_be_items; ++i) {
+      uint32_t l, w, r;
+      if (run->be_items[i].config.kind != 0) continue;
+      int rc2 = item_demand(ctx, &run->be_items[i], &l, &w, &r);
+      if (rc2) return rc2;
+      if (l + hl > ctx->lds_per_cu || w + hw > 32u || r + hr > 512u) pause_ok[i] = 0;
+    }
+  }
   HIPCHK(hipStreamSynchronize(ctx->hi));
   HIPCHK(hipStreamSynchronize(ctx->be));
 
@@ -1205,7 +1294,7 @@ extern "C" int tally_sched_run(tally_ctx *ctx, tally_sched_run_t *run) {
   int rc = TALLY_OK;
   const double t0 = now_us();
   std::thread be_thread;
-  if (n_clients) be_thread = std::thread(be_thread_main, ctx, run, &sh, clients, n_clients, t0, t_end);
+  if (n_clients) be_thread = std::thread(be_thread_main, ctx, run, &sh, clients, n_clients, &pause_ok, t0, t_end);
 
   // ---- high-priority client (this thread) ----------------------------------------------
   uint32_t next_arrival = 0, cur = 0, completed = 0;

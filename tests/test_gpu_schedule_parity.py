@@ -213,6 +213,36 @@ def test_async_flag_preemption_prefix_and_exactly_once(env):
     assert np.allclose(host(partial), want, rtol=2e-6, atol=0)
 
 
+def test_preemption_reaches_workers_that_fill_the_gpu(env):
+    """The largest worker count of the softmax kernel leaves no register free on any compute
+    unit: the flag must still reach the workers (the relay is resident before them) and the
+    job must drain long before it would have finished."""
+    import time
+    B, ctx, torch = env
+    from gpu_util import host
+    x = torch.randn((65536, 2048), device="cuda")
+    y = torch.zeros_like(x)
+    torch.cuda.synchronize()
+    k = B.softmax_f32(x, y)
+    w = ctx.max_workers(k)
+    job = ctx.launch_ptb(k, w, chunk=2)
+    t0 = time.perf_counter()
+    while job.progress()[0] < 64 and time.perf_counter() - t0 < 1.0:
+        pass
+    job.preempt()
+    assert job.wait() == B.JOB_STOPPED
+    done, total, _ = job.progress()
+    assert 0 < done < total // 2, (done, total)          # the whole kernel takes ~1.5 ms
+    job.resume()
+    assert job.wait() == B.JOB_COMPLETE
+    job.free()
+    torch.cuda.synchronize()
+    rows = host(y)[::4099]
+    h = host(x)[::4099].astype(np.float64)
+    e = np.exp(h - h.max(axis=1, keepdims=True))
+    assert np.allclose(rows, e / e.sum(axis=1, keepdims=True), rtol=1e-5, atol=1e-7)
+
+
 # ------------------------------------------------------------------ reduction, configuration 2 shape
 @pytest.mark.parametrize("slice_blocks", [1, 8, 64])
 def test_reduce_sliced_ragged(env, slice_blocks):
@@ -273,6 +303,10 @@ def test_error_paths(env):
     assert lib.tally_launch_sliced(ctx.h, C.byref(k.desc), 0, 1, 0, C.byref(j)) == B.ERR_INVALID_ARG
     assert lib.tally_launch_ptb(ctx.h, C.byref(k.desc), 0, 1, 0, C.byref(j)) == B.ERR_INVALID_ARG
     assert lib.tally_launch_ptb(ctx.h, C.byref(k.desc), 4, 0, 0, C.byref(j)) == B.ERR_INVALID_ARG
+    # more workers than are resident at once: the kernel could not be preempted promptly
+    mw = ctx.max_workers(k)
+    assert mw >= B.device_info()["num_cus"] and mw % B.device_info()["num_cus"] == 0
+    assert lib.tally_launch_ptb(ctx.h, C.byref(k.desc), mw + 1, 1, 0, C.byref(j)) == B.ERR_INVALID_ARG
     bad = B.KernelDesc(k.desc.kernel_id, k.desc.grid, k.desc.block, k.desc.args, k.desc.args_size)
     bad.grid.x += 1                                     # not the kernel's logical grid
     assert lib.tally_launch_native(ctx.h, C.byref(bad), 0) == B.ERR_INVALID_ARG
@@ -291,6 +325,8 @@ def test_error_paths(env):
     ka = B.attn_decode_bf16(q, kv, kv, out, scratch)
     assert lib.tally_launch_ptb(ctx.h, C.byref(ka.desc), 4, 1, 0, C.byref(j)) == B.ERR_UNSUPPORTED
     assert lib.tally_launch_sliced(ctx.h, C.byref(ka.desc), 4, 1, 0, C.byref(j)) == B.ERR_UNSUPPORTED
+    with pytest.raises(B.TallyError):
+        ctx.max_workers(ka)
     # state machine: resume of a complete job and preempt of a complete job are no-ops
     job = ctx.launch_ptb(k, 2)
     assert job.wait() == B.JOB_COMPLETE
