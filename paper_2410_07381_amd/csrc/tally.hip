@@ -304,6 +304,9 @@ struct tally_ctx {
   uint32_t num_cus;
   uint32_t lds_per_cu;
   uint32_t max_workers[TALLY_K_COUNT];  // persistent-worker workgroups resident at once, per kernel
+  // what one workgroup occupies on a compute unit (LDS bytes, waves, registers per lane):
+  // [0] persistent-worker form, [1] original form; asked of the runtime once, at creation
+  uint32_t foot[TALLY_K_COUNT][2][3];
   uint32_t yield_ticks;      // bound of a mid-block pause, 10 ns ticks
   int device;
   int live_jobs;
@@ -602,6 +605,16 @@ int tally_create(tally_ctx **out, void *hip_stream_hi, void *hip_stream_be) {
       g_last_hip = (int)e;
       tally_destroy(c);
       return TALLY_ERR_HIP;
+    }
+    for (int f = 0; f < 2; ++f) {
+      uint32_t *ft = c->foot[k][f];
+      ft[0] = 0; ft[1] = 4; ft[2] = 128;
+      auto fn = f == 0 ? kOps[k].footprint : kOps[k].footprint_native;
+      if (fn && (e = fn(&ft[0], &ft[1], &ft[2])) != hipSuccess) {
+        g_last_hip = (int)e;
+        tally_destroy(c);
+        return TALLY_ERR_HIP;
+      }
     }
     int per_cu = 0;
     c->max_workers[k] = 0;
@@ -1030,16 +1043,8 @@ int item_demand(tally_ctx *ctx, const tally_be_item *it, uint32_t *lds, uint32_t
   tally_dim3 g;
   int rc = check_desc(it->kernel, &ops, &g);
   if (rc) return rc;
-  // per kernel id, asked of the runtime once (the scheduling call before it starts its
-  // best-effort thread, then only that thread, come here)
-  static uint32_t known[TALLY_K_COUNT], fl[TALLY_K_COUNT], fw[TALLY_K_COUNT], fr[TALLY_K_COUNT];
-  const uint32_t id = it->kernel->kernel_id;
-  if (!known[id]) {
-    fl[id] = 0; fw[id] = 4; fr[id] = 128;
-    if (ops->footprint) HIPCHK(ops->footprint(&fl[id], &fw[id], &fr[id]));
-    known[id] = 1;
-  }
-  const uint32_t l = fl[id], w = fw[id], r = fr[id];
+  const uint32_t *ft = ctx->foot[it->kernel->kernel_id][it->config.kind == 0 ? 0 : 1];
+  const uint32_t l = ft[0], w = ft[1], r = ft[2];
   const uint64_t total = (uint64_t)g.x * g.y * g.z;
   uint64_t groups = it->config.kind == 2 ? total : it->config.param;
   if (groups > total) groups = total;
@@ -1264,9 +1269,8 @@ extern "C" int tally_sched_run(tally_ctx *ctx, tally_sched_run_t *run) {
   if (run->n_arrivals) {
     uint32_t hl = 0, hw = 0, hr = 0;  // largest demand of one high-priority workgroup
     for (uint32_t i = 0; i < run->n_hi_kernels; ++i) {
-      const KernelOps *ops = &kOps[run->hi_kernels[i].kernel_id];
-      uint32_t l = 0, w = 4, r = 128;
-      if (ops->footprint_native) HIPCHK(ops->footprint_native(&l, &w, &r));
+      const uint32_t *ft = ctx->foot[run->hi_kernels[i].kernel_id][1];
+      const uint32_t l = ft[0], w = ft[1], r = ft[2];
       hl = l > hl ? l : hl;
       hw = w > hw ? w : hw;
       const uint32_t per_simd = ((w + 3) / 4) * r;
