@@ -107,11 +107,11 @@ __global__ __launch_bounds__(Body::THREADS, Body::MIN_WAVES) void sliced_kernel(
 // ---- persistent-worker form (Section 4.1, preemption) --------------------------------
 // The host raises the flag with one store to pinned host memory (cheap to write, but a
 // load from it crosses PCIe, far too slow for hundreds of workers to poll every
-// iteration).  A one-wave relay kernel, launched beside the workers on a stream of its
-// own, polls that word, copies a request into a device-memory flag the workers can poll
-// cheaply, and mirrors the progress back to the host.  It leaves as soon as the request
-// is relayed or every worker of the segment has exited, so its lifetime is bounded by
-// the workers', which depend on nothing.
+// iteration).  A one-wave relay kernel, launched just before the workers on a stream of
+// its own, polls that word, copies every change of it into a device-memory flag the
+// workers can poll cheaply, and mirrors the progress back to the host.  It leaves when
+// every worker of the segment has exited, so its lifetime is bounded by the workers',
+// which depend on nothing.
 //
 // The relay polls with scalar loads that bypass the scalar cache: a vector load that
 // waits a microsecond on PCIe sits in the compute unit's vector-memory return queue in
@@ -123,8 +123,17 @@ __device__ __forceinline__ uint32_t scalar_load_coherent(const uint32_t *p) {
   return v;
 }
 
+constexpr unsigned long long kRelayGiveUpTicks = 2000000ull;  // 20 ms of the 100 MHz clock
+
 __global__ __launch_bounds__(64) void relay_kernel(PtbCtl c) {
   uint32_t last = 0xFFFFFFFFu;
+  // The relay is launched before its workers.  Where the two cannot run side by side
+  // (kernels executed strictly one after another) the workers cannot start until the
+  // relay has ended: it leaves when neither the task counter nor the exit counter has
+  // moved for 20 ms, and that launch segment then runs without the means to preempt it.
+  const unsigned long long born = wall_clock64();
+  const uint32_t ctr0 = scalar_load_coherent(c.counter), gone0 = scalar_load_coherent(c.exited);
+  bool alive = false;
   for (uint32_t n = 0;; ++n) {
     // forward every change of the host's word: a request (the segment's epoch) and, later,
     // its withdrawal, which lets workers that paused inside a long block carry on
@@ -144,7 +153,10 @@ __global__ __launch_bounds__(64) void relay_kernel(PtbCtl c) {
       gone = __hip_atomic_load(c.exited, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if ((int32_t)(gone - c.exit_target) >= 0) return;
     if ((n & 15u) == 0u) {
-      uint32_t ctr = scalar_load_coherent(c.counter) - c.counter_base;
+      const uint32_t raw = scalar_load_coherent(c.counter);
+      if (raw != ctr0 || gone != gone0) alive = true;
+      if (!alive && wall_clock64() - born > kRelayGiveUpTicks) return;
+      uint32_t ctr = raw - c.counter_base;
       if (threadIdx.x == 0)
         __hip_atomic_store(c.host_live, ctr < c.limit ? ctr : c.limit, __ATOMIC_RELAXED,
                            __HIP_MEMORY_SCOPE_SYSTEM);

@@ -462,8 +462,11 @@ int ptb_launch_segment(tally_job *j, uint32_t limit) {
   c.flag_copies = ctx->copy_pool + (size_t)slot * (kCopySlotBytes / sizeof(uint32_t));
   // The relay goes first, on its own stream: once the workers are on the GPU there may be
   // no wave slot or register left anywhere for it (four 128-register softmax workgroups
-  // fill a compute unit exactly), and without the relay a request is never seen.  Its exit
-  // depends only on the slot's exit counter reaching the target, so it may start early.
+  // fill a compute unit exactly; one slot kept free was taken by whichever workgroup came
+  // first), and without the relay a request is never seen.  Its exit depends only on the
+  // slot's exit counter reaching the target, so it may start early; where kernels are run
+  // strictly one at a time (counter collection under a profiler) it gives up when no
+  // worker has shown up for a while, and that one launch cannot be preempted.
   hipLaunchKernelGGL(relay_kernel, dim3(1), dim3(64), 0, j->ctl, c);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) {  // nothing was enqueued: the slot's bookkeeping is unchanged
@@ -1082,7 +1085,8 @@ void be_thread_main(tally_ctx *ctx, tally_sched_run_t *run, SchedShared *sh, BeC
     }
     uint32_t l, w, r;
     if (item_demand(ctx, it, &l, &w, &r) != TALLY_OK) return true;  // the launch reports it
-    if (others && (lds + l > ctx->lds_per_cu || waves + w > 32u || regs + r > 512u)) return false;
+    // (one wave slot and 32 registers are kept back for the newcomer's relay)
+    if (others && (lds + l > ctx->lds_per_cu || waves + w > 31u || regs + r > 480u)) return false;
     cl.lds = l;
     cl.waves = w;
     cl.regs = r;
