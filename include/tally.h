@@ -91,6 +91,10 @@ typedef struct {
   const uint16_t *A; const uint16_t *Bt; uint16_t *C;
   uint32_t m, n, k, batch;
   uint64_t stride_a, stride_b, stride_c;
+  uint32_t lda, ldb;  /* elements between consecutive rows of A / of Bt; 0 means k.  Rows
+                         that are a large power of two apart (k = 16384: 32 KB) crowd into a
+                         few cache sets and the tiled kernels lose 40 % of their rate; a
+                         padded leading dimension (k + 256) restores it.  Multiples of 8. */
 } tally_gemm_bf16_args;
 
 /* y[r] = sum_k W[r][k] x[k]; W is n x k row-major.  Block b owns rows [4b, 4b+4), one
@@ -168,6 +172,14 @@ int tally_launch_sliced(tally_ctx *ctx, const tally_kernel_desc *desc, uint32_t 
  * to start before the kernel ends.  TALLY_ERR_INVALID_ARG otherwise. */
 int tally_launch_ptb(tally_ctx *ctx, const tally_kernel_desc *desc, uint32_t num_workers,
                      uint32_t chunk, int coverage, tally_job **out);
+
+/* What one workgroup of a kernel occupies on a compute unit: LDS bytes, 64-lane waves,
+ * registers per lane (vector and accumulation registers together, as allocated).
+ * form 0: persistent-worker kernel, 1: original form.  The scheduler uses these figures
+ * for admission among best-effort clients and to decide whether paused best-effort
+ * workers leave room for the high-priority kernels. */
+int tally_kernel_footprint(tally_ctx *ctx, uint32_t kernel_id, int form, uint32_t *lds_bytes,
+                           uint32_t *waves, uint32_t *regs_per_lane);
 
 /* Largest worker count of the persistent-worker form of this kernel whose workgroups are
  * all resident at once on an otherwise idle GPU: compute units x workgroups per unit. */

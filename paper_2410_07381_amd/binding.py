@@ -42,7 +42,7 @@ EXPORTS = [
     "tally_resume", "tally_progress", "tally_pump", "tally_wait", "tally_job_free",
     "tally_launch_ptb_until", "tally_resume_until", "tally_coverage", "tally_marker",
     "tally_marker_read", "tally_last_preempt_latency_us", "tally_last_hip_error",
-    "tally_strerror", "tally_max_workers", "tally_device_info", "tally_ptb_turnaround_ms", "tally_select_config",
+    "tally_strerror", "tally_max_workers", "tally_kernel_footprint", "tally_device_info", "tally_ptb_turnaround_ms", "tally_select_config",
     "tally_profile", "tally_lookup_config", "tally_sched_run", "tally_set_yield_bound_us",
 ]
 
@@ -66,7 +66,8 @@ class ReduceFinalArgs(C.Structure):
 class GemmArgs(C.Structure):
     _fields_ = [("A", C.c_void_p), ("Bt", C.c_void_p), ("C", C.c_void_p),
                 ("m", C.c_uint32), ("n", C.c_uint32), ("k", C.c_uint32), ("batch", C.c_uint32),
-                ("stride_a", C.c_uint64), ("stride_b", C.c_uint64), ("stride_c", C.c_uint64)]
+                ("stride_a", C.c_uint64), ("stride_b", C.c_uint64), ("stride_c", C.c_uint64),
+                ("lda", C.c_uint32), ("ldb", C.c_uint32)]
 
 
 class GemvArgs(C.Structure):
@@ -248,11 +249,14 @@ def reduce_final(partial, total, count=None):
 
 def gemm_bf16(A, Bt, Cout, small=False, n128=False):
     """A [batch,m,k], Bt [batch,n,k], C [batch,m,n]; 16-bit storage tensors.  Tiles of
-    256 x 256 outputs, 256 x 128 with n128, 64 x 64 (ragged edges allowed) with small."""
+    256 x 256 outputs, 256 x 128 with n128, 32 x 32 (ragged edges allowed) with small.
+    A and Bt may be views with padded rows (last dimension contiguous): their row and
+    batch pitches are taken from the tensors; C must be contiguous."""
     batch, m, k = A.shape
     n = Bt.shape[1]
+    assert A.stride(2) == 1 and Bt.stride(2) == 1 and Cout.is_contiguous()
     args = GemmArgs(A.data_ptr(), Bt.data_ptr(), Cout.data_ptr(), m, n, k, batch,
-                    m * k, n * k, m * n)
+                    A.stride(0), Bt.stride(0), m * n, A.stride(1), Bt.stride(1))
     kid = K_GEMM_BF16_SMALL if small else (K_GEMM_BF16_N128 if n128 else K_GEMM_BF16)
     return Kernel(kid, args, (A, Bt, Cout))
 
@@ -384,6 +388,14 @@ class Context:
         out = [dict(kind=c.kind, param=c.param, chunk=c.chunk, latency_ms=c.latency_ms,
                     turnaround_ms=c.turnaround_ms) for c in arr]
         return out, chosen.value
+
+    def kernel_footprint(self, kernel_id, form):
+        """(LDS bytes, waves, registers per lane) of one workgroup; form 0 = persistent
+        workers, 1 = original form."""
+        a, b, c = C.c_uint32(), C.c_uint32(), C.c_uint32()
+        _check(_lib.tally_kernel_footprint(self.h, kernel_id, form, C.byref(a), C.byref(b), C.byref(c)),
+               "tally_kernel_footprint")
+        return a.value, b.value, c.value
 
     def max_workers(self, kernel):
         """Largest worker count whose workgroups are all resident at once."""

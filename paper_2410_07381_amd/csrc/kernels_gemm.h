@@ -79,41 +79,40 @@ struct GemmBodyT {
     const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const uint32_t wm = wave >> 1, wn = wave & 1;
     const uint32_t K = a.k;
+    const uint32_t LDA = a.lda ? a.lda : K, LDB = a.ldb ? a.ldb : K;   // row pitches
 
     // global side of the direct loads: wave w fills rows [64 w, 64 w + 64) of A with 4 loads
     // of 16 rows and rows [16 NB w, 16 NB (w + 1)) of B with NB loads; lane l supplies row
     // l/4, k-chunk (l%4) xor ((l/16)%4).  Addresses are split into a wave-uniform base that
     // advances by 64 bytes per k-step and per-lane byte offsets that never change.  The
     // loads of an operand share one LDS base (M0) and differ by the instruction's immediate
-    // offset, which also moves the global address; the lane offsets compensate for that.
+    // offset, which also moves the global address; the uniform bases compensate for that.
     const uint32_t ld_kc = (lane & 3) ^ ((lane >> 4) & 3);
     const unsigned char *uA =
-        reinterpret_cast<const unsigned char *>(a.A + bz * a.stride_a + (uint64_t)(by * TILE) * K);
+        reinterpret_cast<const unsigned char *>(a.A + bz * a.stride_a + (uint64_t)(by * TILE) * LDA);
     const unsigned char *uB =
-        reinterpret_cast<const unsigned char *>(a.Bt + bz * a.stride_b + (uint64_t)(bx * TILE_N) * K);
-    uint32_t voffA[4], voffB[NB];
-#pragma unroll
-    for (int j = 0; j < 4; ++j)
-      voffA[j] = ((wave * 64 + (lane >> 2) + 16 * j) * K + ld_kc * 8) * 2 - j * 1024;
-#pragma unroll
-    for (int j = 0; j < NB; ++j)
-      voffB[j] = ((wave * 16 * NB + (lane >> 2) + 16 * j) * K + ld_kc * 8) * 2 - j * 1024;
+        reinterpret_cast<const unsigned char *>(a.Bt + bz * a.stride_b + (uint64_t)(bx * TILE_N) * LDB);
+    // one per-lane offset per operand; what distinguishes the loads of an operand (16 rows
+    // further down, less the 1024 bytes the immediate adds) is uniform and goes to the base
+    const uint32_t voffA = ((wave * 64 + (lane >> 2)) * LDA + ld_kc * 8) * 2;
+    const uint32_t voffB = ((wave * 16 * NB + (lane >> 2)) * LDB + ld_kc * 8) * 2;
+    const uint64_t stepA = (uint64_t)32 * LDA - 1024, stepB = (uint64_t)32 * LDB - 1024;
     const uint32_t ldsA_wave = wave * 64 * BK * 2;        // byte offset of the wave's rows
     const uint32_t ldsB_wave = wave * 16 * NB * BK * 2;
 
     // one direct load: 16 rows of A (B) of the 64 (16 NB) a wave contributes to a stage
     auto load_a = [&](const unsigned char *g, lptr_t l, int j) {
-      if (j == 0) __builtin_amdgcn_global_load_lds((gptr_t)(g + voffA[0]), l, 16, 0, 0);
-      if (j == 1) __builtin_amdgcn_global_load_lds((gptr_t)(g + voffA[1]), l, 16, 1024, 0);
-      if (j == 2) __builtin_amdgcn_global_load_lds((gptr_t)(g + voffA[2]), l, 16, 2048, 0);
-      if (j == 3) __builtin_amdgcn_global_load_lds((gptr_t)(g + voffA[3]), l, 16, 3072, 0);
+      if (j == 0) __builtin_amdgcn_global_load_lds((gptr_t)(g + voffA), l, 16, 0, 0);
+      if (j == 1) __builtin_amdgcn_global_load_lds((gptr_t)(g + stepA + voffA), l, 16, 1024, 0);
+      if (j == 2) __builtin_amdgcn_global_load_lds((gptr_t)(g + 2 * stepA + voffA), l, 16, 2048, 0);
+      if (j == 3) __builtin_amdgcn_global_load_lds((gptr_t)(g + 3 * stepA + voffA), l, 16, 3072, 0);
     };
     auto load_b = [&](const unsigned char *g, lptr_t l, int j) {
-      if (j == 0) __builtin_amdgcn_global_load_lds((gptr_t)(g + voffB[0]), l, 16, 0, 0);
-      if (j == 1) __builtin_amdgcn_global_load_lds((gptr_t)(g + voffB[1]), l, 16, 1024, 0);
+      if (j == 0) __builtin_amdgcn_global_load_lds((gptr_t)(g + voffB), l, 16, 0, 0);
+      if (j == 1) __builtin_amdgcn_global_load_lds((gptr_t)(g + stepB + voffB), l, 16, 1024, 0);
       if constexpr (NB > 2) {
-        if (j == 2) __builtin_amdgcn_global_load_lds((gptr_t)(g + voffB[2]), l, 16, 2048, 0);
-        if (j == 3) __builtin_amdgcn_global_load_lds((gptr_t)(g + voffB[3]), l, 16, 3072, 0);
+        if (j == 2) __builtin_amdgcn_global_load_lds((gptr_t)(g + 2 * stepB + voffB), l, 16, 2048, 0);
+        if (j == 3) __builtin_amdgcn_global_load_lds((gptr_t)(g + 3 * stepB + voffB), l, 16, 3072, 0);
       }
     };
     auto issue_loads = [&](uint32_t kt) {
@@ -384,8 +383,9 @@ struct GemmSmallBody {
     const uint32_t brow = bx * TILE + (lane & 31);
     const bool aok = arow < a.m, bok = brow < a.n;
     // lane l holds row l%32, elements [8 (l/32), 8 (l/32) + 8) of a 16-wide k-chunk
-    const uint16_t *pA = a.A + bz * a.stride_a + (uint64_t)(aok ? arow : 0) * K + (lane >> 5) * 8;
-    const uint16_t *pB = a.Bt + bz * a.stride_b + (uint64_t)(bok ? brow : 0) * K + (lane >> 5) * 8;
+    const uint32_t LDA = a.lda ? a.lda : K, LDB = a.ldb ? a.ldb : K;
+    const uint16_t *pA = a.A + bz * a.stride_a + (uint64_t)(aok ? arow : 0) * LDA + (lane >> 5) * 8;
+    const uint16_t *pB = a.Bt + bz * a.stride_b + (uint64_t)(bok ? brow : 0) * LDB + (lane >> 5) * 8;
     const uint4 zero = make_uint4(0, 0, 0, 0);
     f32x16_t acc;
 #pragma unroll

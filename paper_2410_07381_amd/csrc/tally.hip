@@ -171,7 +171,12 @@ int grid_gemm_common(const tally_gemm_bf16_args *a) {
   if (!a->A || !a->Bt || !a->C || !a->m || !a->n || !a->k || !a->batch) return TALLY_ERR_INVALID_ARG;
   if (!aligned16(a->A) || !aligned16(a->Bt) || (a->stride_a % 8) || (a->stride_b % 8))
     return TALLY_ERR_INVALID_ARG;
-  if (a->batch > 1 && (a->stride_a < (uint64_t)a->m * a->k || a->stride_b < (uint64_t)a->n * a->k ||
+  if ((a->lda && (a->lda < a->k || (a->lda % 8))) || (a->ldb && (a->ldb < a->k || (a->ldb % 8))))
+    return TALLY_ERR_INVALID_ARG;
+  const uint64_t lda = a->lda ? a->lda : a->k, ldb = a->ldb ? a->ldb : a->k;
+  if (lda > (1u << 20) || ldb > (1u << 20)) return TALLY_ERR_INVALID_ARG;  // 32-bit byte offsets per tile
+  if (a->batch > 1 && (a->stride_a < (uint64_t)(a->m - 1) * lda + a->k ||
+                       a->stride_b < (uint64_t)(a->n - 1) * ldb + a->k ||
                        a->stride_c < (uint64_t)a->m * a->n))
     return TALLY_ERR_INVALID_ARG;
   return TALLY_OK;
@@ -717,6 +722,17 @@ int tally_launch_ptb_until(tally_ctx *ctx, const tally_kernel_desc *desc, uint32
 int tally_launch_ptb(tally_ctx *ctx, const tally_kernel_desc *desc, uint32_t num_workers,
                      uint32_t chunk, int coverage, tally_job **out) {
   return tally_launch_ptb_until(ctx, desc, num_workers, chunk, ~0ull, coverage, out);
+}
+
+int tally_kernel_footprint(tally_ctx *ctx, uint32_t kernel_id, int form, uint32_t *lds_bytes,
+                           uint32_t *waves, uint32_t *regs_per_lane) {
+  if (!ctx || kernel_id >= TALLY_K_COUNT || form < 0 || form > 1 || !lds_bytes || !waves || !regs_per_lane)
+    return TALLY_ERR_INVALID_ARG;
+  if (form == 0 && !kOps[kernel_id].transformable) return TALLY_ERR_UNSUPPORTED;
+  *lds_bytes = ctx->foot[kernel_id][form][0];
+  *waves = ctx->foot[kernel_id][form][1];
+  *regs_per_lane = ctx->foot[kernel_id][form][2];
+  return TALLY_OK;
 }
 
 int tally_max_workers(tally_ctx *ctx, const tally_kernel_desc *desc, uint32_t *max_workers) {

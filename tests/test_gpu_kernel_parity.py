@@ -143,6 +143,35 @@ def test_gemm_n128_attention_value_shape(env, k):
     assert_bf16_close(host(Cd), a["C"])
 
 
+@pytest.mark.parametrize("variant", ["big", "n128", "small"])
+def test_gemm_padded_leading_dimensions(env, variant):
+    """Operands stored with rows longer than k (views of padded buffers, batch pitch larger
+    than the matrix): same result as the oracle gets from the unpadded arrays."""
+    B, ctx, torch = env
+    from gpu_util import dev, host, assert_bf16_close
+    m, n, k, batch = (512, 512, 160, 2) if variant == "big" else ((256, 384, 96, 2) if variant == "n128"
+                                                                    else (100, 70, 64, 2))
+    name = {"big": "gemm_bf16", "n128": "gemm_bf16_n128", "small": "gemm_bf16_small"}[variant]
+    g = TI.gemm_inputs(m, n, k, config_index=3, batch=batch, scale=0.125)
+    a = dict(g, C=np.zeros((batch, m, n), np.uint16))
+    OS.run_native(name, OK.grid_of(name, a), a)
+    Ap = torch.full((batch, m + 3, k + 24), 0x7FC0, dtype=torch.int16, device="cuda")   # NaN padding
+    Bp = torch.full((batch, n + 1, k + 8), 0x7FC0, dtype=torch.int16, device="cuda")
+    Ap[:, :m, :k] = dev(g["A"])
+    Bp[:, :n, :k] = dev(g["Bt"])
+    Cd = torch.zeros((batch, m, n), dtype=torch.int16, device="cuda")
+    torch.cuda.synchronize()
+    kern = B.gemm_bf16(Ap[:, :m, :k], Bp[:, :n, :k], Cd, small=(variant == "small"),
+                       n128=(variant == "n128"))
+    job = ctx.launch_ptb(kern, 7)
+    assert job.wait() == B.JOB_COMPLETE
+    job.free()
+    assert_bf16_close(host(Cd), a["C"])
+    bad = torch.zeros((1, 256, 256 + 4), dtype=torch.int16, device="cuda")              # pitch not a multiple of 8
+    with pytest.raises(B.TallyError):
+        B.gemm_bf16(bad[:, :, :256], bad[:, :, :256], torch.zeros((1, 256, 256), dtype=torch.int16, device="cuda"))
+
+
 def test_gemm_rejects_unaligned_output(env):
     B, ctx, torch = env
     A = torch.zeros((1, 256, 64), dtype=torch.int16, device="cuda")

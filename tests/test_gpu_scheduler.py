@@ -101,6 +101,25 @@ def test_several_best_effort_clients_all_progress_and_stay_correct(env):
     assert (out["be_client_kernels_done"] > 1).all()
 
 
+def test_high_priority_kernels_fit_beside_a_paused_gemm_tile(env):
+    """The pause inside a GEMM tile only helps high-priority kernels that fit beside the
+    paused workgroup (512 registers per lane and the LDS of a compute unit are shared): the
+    kernels of the inference-like layer and of the decode step are written to fit."""
+    B, ctx, torch = env
+    lds_cu = B.device_info()["lds_bytes_per_cu"]
+    for be in (B.K_GEMM_BF16, B.K_GEMM_BF16_N128):
+        bl, bw, br = ctx.kernel_footprint(be, 0)
+        assert bw == 4 and br <= 384
+        for hi in (B.K_GEMM_BF16_SMALL, B.K_SOFTMAX_F32, B.K_LAYERNORM_F32, B.K_GEMV_BF16,
+                   B.K_ATTN_DECODE_BF16, B.K_SAXPY):
+            hl, hw, hr = ctx.kernel_footprint(hi, 1)
+            assert br + ((hw + 3) // 4) * hr <= 512, (be, hi, br, hr)
+            assert bl + hl <= lds_cu, (be, hi, bl, hl)
+            assert bw + hw <= 32
+    with pytest.raises(B.TallyError):
+        ctx.kernel_footprint(B.K_ATTN_DECODE_BF16, 0)      # no persistent-worker form
+
+
 def test_scheduler_rejects_bad_input(env):
     B, ctx, torch = env
     import ctypes as C

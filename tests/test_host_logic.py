@@ -29,7 +29,7 @@ def test_library_exports_every_declared_symbol(B):
 def test_struct_sizes_match_the_header(B):
     import ctypes as C
     assert C.sizeof(B.SaxpyArgs) == 24 and C.sizeof(B.ReduceSumArgs) == 24
-    assert C.sizeof(B.GemmArgs) == 64 and C.sizeof(B.GemvArgs) == 32
+    assert C.sizeof(B.GemmArgs) == 72 and C.sizeof(B.GemvArgs) == 32
     assert C.sizeof(B.CoverRec) == 24 and C.sizeof(B.Config) == 20
     assert C.sizeof(B.KernelDesc) == 48
 
