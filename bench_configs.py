@@ -80,6 +80,8 @@ def cfg0(torch, B, ctx, be_stream, args):
     nat = _time(torch, B, be_stream, lambda: (ctx.launch_native(k), None)[1])
     ptb = _time(torch, B, be_stream, lambda: ctx.launch_ptb(k, 256))
     ptb16 = _time(torch, B, be_stream, lambda: ctx.launch_ptb(k, 256, chunk=16))
+    wmax = ctx.max_workers(k)
+    ptbmax = _time(torch, B, be_stream, lambda: ctx.launch_ptb(k, wmax))
 
     def preempted_run():
         job = ctx.launch_ptb(k, 256, stop_at=pts[0])
@@ -92,6 +94,7 @@ def cfg0(torch, B, ctx, be_stream, args):
         "workload": "cfg0: fp32 SAXPY N=2^20, grid 4096x256, 256 persistent workers, 3 seeded "
                     f"preemptions at counter values {pts} each followed by a resume",
         "native_us": nat[0], "ptb_us": ptb[0], "ptb_chunk16_us": ptb16[0],
+        "ptb_max_workers": wmax, "ptb_max_workers_us": ptbmax[0],
         "ptb_3_preemptions_us": pre[0],
         "native_GBps": nbytes / nat[0] / 1e3, "ptb_GBps": nbytes / ptb[0] / 1e3,
         "note": "12 MB of traffic: launch- and latency-bound, not an HBM roofline case; one "
