@@ -1,7 +1,7 @@
 """Helpers for the GPU parity tests: device buffers from seeded host arrays, oracle runs
 on copies of the same bits, and the comparison rules.
 
-Tolerances (derived in the design doc):
+Tolerances (each follows from the arithmetic named beside it):
   fp32 elementwise (SAXPY)      1e-6 relative (one fused multiply-add vs fp64 rounded once)
   fp32 block sums               2e-6 relative (at most 23 fp32 roundings of 2^-24 each)
   softmax / LayerNorm           1e-5 relative + 1e-7 absolute (exp / rsqrt + reduction order)
