@@ -241,6 +241,7 @@ def main():
         torch, ctx, B, be_stream, lambda: ctx.launch_ptb(gemm, args.workers), args.roofline_reps)
     ms_gemv, _ = time_kernel_events(
         torch, ctx, B, be_stream, lambda: (ctx.launch_native(gemv), None)[1], args.roofline_reps)
+    ceiling = ctx.mfma_ceiling_tflops(10)
     tf_nat = flops / (ms_nat * 1e-3) / 1e12
     tf_ptb = flops / (ms_ptb * 1e-3) / 1e12
     gemv_bytes = 4096 * 4096 * 2 + 2 * 4096 * 2
@@ -255,6 +256,9 @@ def main():
         "avg_launch_ms": ms_ptb,
         "native": {"achieved": tf_nat, "frac": tf_nat / PEAK_BF16_TFLOPS, "avg_launch_ms": ms_nat},
         "transformed_over_native": tf_ptb / tf_nat,
+        # what the matrix pipe sustains on this device at its power-managed clock: a
+        # register-only loop of the same MFMAs on every compute unit, measured in this run
+        "measured_ceiling": {"peak": ceiling, "unit": "TFLOP/s", "frac": tf_ptb / ceiling},
         "hi_pri_gemv": {"bound": "hbm", "achieved": gemv_bytes / (ms_gemv * 1e-3) / 1e9,
                         "peak": PEAK_HBM_GBS, "unit": "GB/s",
                         "frac": gemv_bytes / (ms_gemv * 1e-3) / 1e9 / PEAK_HBM_GBS,

@@ -173,6 +173,12 @@ int tally_launch_sliced(tally_ctx *ctx, const tally_kernel_desc *desc, uint32_t 
 int tally_launch_ptb(tally_ctx *ctx, const tally_kernel_desc *desc, uint32_t num_workers,
                      uint32_t chunk, int coverage, tally_job **out);
 
+/* Measured ceiling of the bf16 matrix pipe on this device, for the roofline: a register-only
+ * loop of independent 32x32x16 MFMAs (random operand bits), one wave per SIMD on every
+ * compute unit, 4096 MFMAs per wave as in one 256x256x4096 tile; best of `reps` launches on
+ * the best-effort stream, timed with HIP events.  Allocates and frees a few KB. */
+int tally_mfma_ceiling_tflops(tally_ctx *ctx, uint32_t reps, double *tflops);
+
 /* What one workgroup of a kernel occupies on a compute unit: LDS bytes, 64-lane waves,
  * registers per lane (vector and accumulation registers together, as allocated).
  * form 0: persistent-worker kernel, 1: original form.  The scheduler uses these figures

@@ -42,7 +42,7 @@ EXPORTS = [
     "tally_resume", "tally_progress", "tally_pump", "tally_wait", "tally_job_free",
     "tally_launch_ptb_until", "tally_resume_until", "tally_coverage", "tally_marker",
     "tally_marker_read", "tally_last_preempt_latency_us", "tally_last_hip_error",
-    "tally_strerror", "tally_max_workers", "tally_kernel_footprint", "tally_device_info", "tally_ptb_turnaround_ms", "tally_select_config",
+    "tally_strerror", "tally_max_workers", "tally_kernel_footprint", "tally_mfma_ceiling_tflops", "tally_device_info", "tally_ptb_turnaround_ms", "tally_select_config",
     "tally_profile", "tally_lookup_config", "tally_sched_run", "tally_set_yield_bound_us",
 ]
 
@@ -172,7 +172,11 @@ def _load():
         "tally_lookup_config": ([vp, P(KernelDesc), P(Config)], i32),
         "tally_sched_run": ([vp, P(SchedRun)], i32),
         "tally_set_yield_bound_us": ([vp, u32], i32),
+        "tally_max_workers": ([vp, P(KernelDesc), P(u32)], i32),
+        "tally_kernel_footprint": ([vp, u32, i32, P(u32), P(u32), P(u32)], i32),
+        "tally_mfma_ceiling_tflops": ([vp, u32, P(dbl)], i32),
     }
+    assert set(sig) == set(EXPORTS), set(sig) ^ set(EXPORTS)
     for name, (argtypes, restype) in sig.items():
         fn = getattr(lib, name)
         fn.argtypes = argtypes
@@ -388,6 +392,12 @@ class Context:
         out = [dict(kind=c.kind, param=c.param, chunk=c.chunk, latency_ms=c.latency_ms,
                     turnaround_ms=c.turnaround_ms) for c in arr]
         return out, chosen.value
+
+    def mfma_ceiling_tflops(self, reps=10):
+        """Measured bf16 matrix-pipe ceiling (register-only MFMA loop on every compute unit)."""
+        v = C.c_double()
+        _check(_lib.tally_mfma_ceiling_tflops(self.h, reps, C.byref(v)), "tally_mfma_ceiling_tflops")
+        return v.value
 
     def kernel_footprint(self, kernel_id, form):
         """(LDS bytes, waves, registers per lane) of one workgroup; form 0 = persistent

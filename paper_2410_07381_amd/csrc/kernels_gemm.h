@@ -439,4 +439,29 @@ struct GemmSmallBody {
   }
 };
 
+// Measured ceiling of the matrix pipe: every wave issues independent 32x32x16 bf16 MFMAs on
+// register operands only (no LDS, no memory), one wave per SIMD on every compute unit, as
+// a GEMM tile does.  The shader clock is power-managed, so the rate depends on how many
+// units are busy and on the operand bits (random bits toggle more than zeros).
+__global__ __launch_bounds__(256) void mfma_ceiling_kernel(const uint4 *operands, float *sink,
+                                                           uint32_t iters) {
+  const uint4 va = operands[threadIdx.x & 63], vb = operands[64 + (threadIdx.x & 63)];
+  const bf16x8_t fa = __builtin_bit_cast(bf16x8_t, va), fb = __builtin_bit_cast(bf16x8_t, vb);
+  f32x16_t acc[16];
+#pragma unroll
+  for (int i = 0; i < 16; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+  for (uint32_t it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, fb, acc[i], 0, 0, 0);
+  }
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < 16; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) s += acc[i][r];
+  sink[blockIdx.x * 256 + threadIdx.x] = s;
+}
+
 }  // namespace tally

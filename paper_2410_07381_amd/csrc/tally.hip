@@ -724,6 +724,49 @@ int tally_launch_ptb(tally_ctx *ctx, const tally_kernel_desc *desc, uint32_t num
   return tally_launch_ptb_until(ctx, desc, num_workers, chunk, ~0ull, coverage, out);
 }
 
+int tally_mfma_ceiling_tflops(tally_ctx *ctx, uint32_t reps, double *tflops) {
+  if (!ctx || !tflops || reps == 0 || reps > 1000) return TALLY_ERR_INVALID_ARG;
+  uint4 *ops = nullptr;
+  float *sink = nullptr;
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  uint32_t bits[512];
+  uint32_t s = 1;
+  for (int i = 0; i < 512; ++i) {  // pairs of small bf16 values of either sign
+    s = s * 1664525u + 1013904223u;
+    bits[i] = (s & 0x807F807Fu) | 0x3C003C00u;
+  }
+  const uint32_t iters = 256;  // x 16 accumulators = 4096 MFMAs per wave
+  hipError_t e;
+  int rc = TALLY_OK;
+  float best_ms = 1e30f;
+  if ((e = hipMalloc((void **)&ops, sizeof(bits))) != hipSuccess ||
+      (e = hipMalloc((void **)&sink, (size_t)ctx->num_cus * 256 * sizeof(float))) != hipSuccess ||
+      (e = hipMemcpy(ops, bits, sizeof(bits), hipMemcpyHostToDevice)) != hipSuccess ||
+      (e = hipEventCreate(&e0)) != hipSuccess || (e = hipEventCreate(&e1)) != hipSuccess) {
+    g_last_hip = (int)e;
+    rc = TALLY_ERR_HIP;
+  }
+  for (uint32_t r = 0; rc == TALLY_OK && r < reps + 2; ++r) {  // two warm-up launches
+    (void)hipEventRecord(e0, ctx->be);
+    hipLaunchKernelGGL(mfma_ceiling_kernel, dim3(ctx->num_cus), dim3(256), 0, ctx->be, ops, sink, iters);
+    (void)hipEventRecord(e1, ctx->be);
+    float ms = 0.f;
+    if ((e = hipEventSynchronize(e1)) != hipSuccess || (e = hipEventElapsedTime(&ms, e0, e1)) != hipSuccess) {
+      g_last_hip = (int)e;
+      rc = TALLY_ERR_HIP;
+    } else if (r >= 2 && ms < best_ms) {
+      best_ms = ms;
+    }
+  }
+  if (rc == TALLY_OK)
+    *tflops = (double)ctx->num_cus * 4 * 16 * iters * 32768.0 / (best_ms * 1e-3) / 1e12;
+  if (e0) (void)hipEventDestroy(e0);
+  if (e1) (void)hipEventDestroy(e1);
+  if (ops) (void)hipFree(ops);
+  if (sink) (void)hipFree(sink);
+  return rc;
+}
+
 int tally_kernel_footprint(tally_ctx *ctx, uint32_t kernel_id, int form, uint32_t *lds_bytes,
                            uint32_t *waves, uint32_t *regs_per_lane) {
   if (!ctx || kernel_id >= TALLY_K_COUNT || form < 0 || form > 1 || !lds_bytes || !waves || !regs_per_lane)
