@@ -1248,9 +1248,6 @@ void be_thread_main(tally_ctx *ctx, tally_sched_run_t *run, SchedShared *sh, BeC
       }
     }
     done = idle == n_clients;
-    // both scheduling threads poll; where the host has fewer free cores than pollers the
-    // high-priority thread must not wait out a time slice (milliseconds) behind this one
-    std::this_thread::yield();
   }
   for (uint32_t c = 0; c < n_clients; ++c) {
     publish(c, nullptr);

@@ -37,10 +37,18 @@ def test_colocated_run_completes_and_stays_correct(env, policy, be_form):
     if policy != 0:
         cfg = (B.CFG_NATIVE, 1, 1)
     arrivals = TI.poisson_arrivals_us(5000.0, 200, config_index=2)
+    # the first launch of a kernel in a process loads its code (tens of milliseconds, as long
+    # as the whole window below): run every form once before the run that is checked
+    warm = ctx.sched_run([hi_k], arrivals[:3], [(be_k, cfg)], policy=policy, tail_us=100.0)
+    assert len(warm["latency_us"]) == 3
+    sy.zero_()
+    torch.cuda.synchronize()
     out = ctx.sched_run([hi_k], arrivals, [(be_k, cfg)], policy=policy, tail_us=200.0)
     lat = out["latency_us"]
     assert len(lat) == 200 and (lat > 0).all() and lat.max() < 5e4
-    assert out["be_kernels_done"] > 10
+    assert out["be_kernels_done"] > 10, (out["be_kernels_done"], out["n_preempts"], out["window_us"],
+                                         np.percentile(lat, [50, 99]).tolist(),
+                                         out["preempt_latency_us"][:8].tolist(), warm["be_kernels_done"])
     assert out["window_us"] >= arrivals[-1]
     torch.cuda.synchronize()
     assert (host(sy) == 200.0).all()              # every request ran exactly once
