@@ -21,7 +21,18 @@ try:
     _hwq = int(os.environ.get("GPU_MAX_HW_QUEUES", "4"))
 except ValueError:
     _hwq = 4
-if _hwq < 20:
+def _gpu_already_initialised():
+    import sys
+    t = sys.modules.get("torch")
+    try:
+        return bool(t is not None and t.cuda.is_initialized())
+    except Exception:
+        return False
+
+
+# (if the GPU runtime is up already the variable is left alone, so that a run with several
+# clients is refused rather than silently folded onto too few queues)
+if _hwq < 20 and not _gpu_already_initialised():
     os.environ["GPU_MAX_HW_QUEUES"] = "20"
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
