@@ -264,7 +264,7 @@ def main():
         "frac": tf_ptb / PEAK_BF16_TFLOPS,
         # HBM-side bytes per launch from the committed rocprofv3 counter runs
         # (profiles/gemm_bf16_cfg1_rocprofv3.txt): FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0
-        "traffic": 164570.6 * 1024 * 2.0 + 32784.1 * 1024,
+        "traffic": 164355.0 * 1024 * 2.0 + 32784.1 * 1024,
         "traffic_unit": "bytes per launch (algorithmic: 100663296)",
         "avg_launch_ms": ms_ptb,
         "native": {"achieved": tf_nat, "frac": tf_nat / PEAK_BF16_TFLOPS, "avg_launch_ms": ms_nat},
