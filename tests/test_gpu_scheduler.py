@@ -128,6 +128,16 @@ def test_high_priority_kernels_fit_beside_a_paused_gemm_tile(env):
         ctx.kernel_footprint(B.K_ATTN_DECODE_BF16, 0)      # no persistent-worker form
 
 
+def test_measured_matrix_pipe_ceiling_is_plausible(env):
+    """Register-only MFMA loop on every compute unit: below the 2.5 PFLOP/s sheet figure
+    (the clock is power-managed) and far above anything a mis-sized launch would give."""
+    B, ctx, torch = env
+    tf = ctx.mfma_ceiling_tflops(5)
+    assert 800.0 < tf < 2600.0, tf
+    with pytest.raises(B.TallyError):
+        ctx.mfma_ceiling_tflops(0)
+
+
 def test_scheduler_rejects_bad_input(env):
     B, ctx, torch = env
     import ctypes as C

@@ -60,3 +60,20 @@ def test_error_strings_and_null_handling(B):
     assert B.lib().tally_select_config(None, 0, 1.0) == B.ERR_INVALID_ARG
     assert B.lib().tally_preempt(None) == B.ERR_INVALID_ARG
     assert B.lib().tally_job_free(None) == B.ERR_INVALID_ARG
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """The method is a per-GPU mechanism and this build measures one GPU: asking for more
+    ends with a message and a non-zero status, before anything touches a GPU."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"],
+                       capture_output=True, text=True, timeout=60)
+    assert r.returncode == 2 and "one GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_entry_points_exist():
+    import importlib
+    g = importlib.import_module("__graft_entry__")
+    assert callable(g.build) and callable(g.smoke)
