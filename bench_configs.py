@@ -114,6 +114,22 @@ def cfg2(torch, B, ctx, be_stream, args):
     red = B.reduce_sum(x, partial)
     hi = B.saxpy(sx, sy, 1.5)
     nbytes = 4 * n
+    if getattr(args, "leg", "all") == "roofline":
+        # counter runs (rocprofv3 --pmc): a plain copy of known size calibrates FETCH_SIZE,
+        # then single launches of the sum in its original and persistent-worker forms
+        dst = torch.empty_like(x)
+        torch.cuda.synchronize()
+        for _ in range(3):
+            dst.copy_(x)
+        torch.cuda.synchronize()
+        for _ in range(args.roofline_reps):
+            ctx.launch_native(red)
+            be_stream.synchronize()
+            job = ctx.launch_ptb(red, 512, chunk=8)
+            assert job.wait() == B.JOB_COMPLETE
+            job.free()
+        return {"leg": "roofline", "workload": "cfg2", "reps": args.roofline_reps,
+                "copy_bytes_read": nbytes, "copy_bytes_written": nbytes, "sum_bytes_read": nbytes}
     count = args.steps
     arrivals = TI.poisson_arrivals_us(500.0, count, config_index=2)
     solo = ctx.sched_run([hi], arrivals, [])
