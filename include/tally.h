@@ -1,7 +1,7 @@
 /*
  * tally.h -- C ABI of the block-level kernel scheduling library for one MI355X (gfx950).
  *
- * Problem statement (Section 3, "Tally: system design"): one high-priority job and
+ * Problem statement (Section 4, "Tally: system design"): one high-priority job and
  * best-effort job(s) share a single GPU.  High-priority kernels are dispatched at once
  * in their original form; best-effort kernels are run at thread-block granularity,
  * either as sliced launches or as preemptible persistent-worker kernels, so that they
