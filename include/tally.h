@@ -135,7 +135,7 @@ typedef struct tally_job tally_job; /* one best-effort kernel instance and its p
 /* ---- context ---------------------------------------------------------------------- */
 
 /* Create a context on the current device for one high-priority and one best-effort
- * stream (Section 3: one high-priority task next to best-effort tasks). */
+ * stream (Section 4: one high-priority task next to best-effort tasks). */
 int tally_create(tally_ctx **out, void *hip_stream_hi, void *hip_stream_be);
 int tally_destroy(tally_ctx *ctx); /* all jobs must have been freed */
 
