@@ -115,6 +115,35 @@ def test_saxpy_native_and_sliced(env):
     assert (host(y2).view(np.uint32) == host(y).view(np.uint32)).all()
 
 
+@pytest.mark.parametrize("in_flight", [2, 3, 8])
+def test_sliced_several_slices_in_flight(env, in_flight):
+    """More than one sub-kernel enqueued at a time (the paper enqueues one): coverage and
+    results are those of the one-at-a-time schedule, and a preemption drains every slice
+    that was already enqueued before the job reports STOPPED."""
+    B, ctx, torch = env
+    from gpu_util import dev, host, assert_cover_equal, assert_close_rel
+    base = TI.saxpy_inputs(n=256 * 33 + 17, config_index=0)        # 34 blocks, ragged tail
+    grid = OK.grid_of("saxpy", base)
+    x, y = dev(base["x"]), dev(base["y"])
+    torch.cuda.synchronize()
+    job = ctx.launch_sliced(B.saxpy(x, y, base["a"]), 5, max_in_flight=in_flight, coverage=True)
+    job.preempt()
+    all_enqueued = 5 * in_flight >= 34                             # then nothing is left to stop
+    assert job.wait() == (B.JOB_COMPLETE if all_enqueued else B.JOB_STOPPED)
+    done = job.progress()[0]
+    assert done == min(5 * in_flight, 34)                          # exactly the enqueued slices
+    job.resume()                                                   # no-op on a complete job
+    assert job.wait() == B.JOB_COMPLETE
+    rec = job.coverage()
+    job.free()
+    first = min(in_flight, 7)                                      # slices before the preemption
+    want_y, (cov, resumes) = _saxpy_oracle(
+        base, lambda a: OS.run_sliced("saxpy", grid, a, 5, preempt_after_slices=[first]))
+    assert resumes == ([] if all_enqueued else [done])
+    assert_cover_equal(rec, cov)
+    assert_close_rel(host(y), want_y, 1e-6)
+
+
 def test_sliced_preempt_and_resume_segments(env):
     B, ctx, torch = env
     from gpu_util import dev, host, assert_cover_equal, assert_close_rel
