@@ -204,7 +204,8 @@ def test_ptb_three_dimensional_grid_mapping(env):
 
 
 # ------------------------------------------------------------------ asynchronous preemption
-def test_async_flag_preemption_prefix_and_exactly_once(env):
+@pytest.mark.parametrize("workers,chunk", [(256, 1), (512, 8)])
+def test_async_flag_preemption_prefix_and_exactly_once(env, workers, chunk):
     """Raise the real flag from the host while workers run.  The observed progress value is
     fed to the oracle as its preemption point; at the drain exactly the prefix has run."""
     B, ctx, torch = env
@@ -216,15 +217,15 @@ def test_async_flag_preemption_prefix_and_exactly_once(env):
     torch.cuda.synchronize()
     k = B.reduce_sum(x, partial)
     pts = []
-    job = ctx.launch_ptb(k, 256, coverage=True)
+    job = ctx.launch_ptb(k, workers, chunk=chunk, coverage=True)
     for attempt in range(3):
-        time.sleep(0.0001)
+        time.sleep(0.0001 if chunk == 1 else 0.00004)
         job.preempt()
         st = job.wait()
         done, total, _ = job.progress()
         if st == B.JOB_COMPLETE:
             break
-        assert st == B.JOB_STOPPED and 0 <= done < total
+        assert st == B.JOB_STOPPED and 0 <= done < total and done % chunk == 0
         lat = job.preempt_latency_us()
         assert 0 < lat < 5e4
         rec = job.coverage()
@@ -235,7 +236,7 @@ def test_async_flag_preemption_prefix_and_exactly_once(env):
     rec = job.coverage()
     job.free()
     assert len(pts) >= 1, "the kernel finished before any preemption landed"
-    cov, log = OS.run_ptb(None, (nb, 1, 1), {}, 256, preempt_points=pts, seed=7)
+    cov, log = OS.run_ptb(None, (nb, 1, 1), {}, workers, preempt_points=pts, seed=7, chunk=chunk)
     assert log == pts + [nb]
     assert_cover_equal(rec, cov)
     want = host(x).reshape(nb, 4096).sum(axis=1, dtype=np.float64)
