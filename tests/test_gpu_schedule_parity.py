@@ -94,6 +94,60 @@ def test_saxpy_ptb_small(env, n, workers, chunk, pts):
     assert_close_rel(host(y), want_y, 1e-6)
 
 
+def test_degenerate_schedules(env):
+    """A zero-block segment (preempted before the first fetch), one worker, a chunk and a
+    slice larger than the whole grid, an empty input."""
+    B, ctx, torch = env
+    from gpu_util import dev, host, assert_cover_equal, assert_close_rel
+    base = TI.saxpy_inputs(n=256 * 7 + 3, config_index=0)          # 8 blocks
+    grid = OK.grid_of("saxpy", base)
+    want_y, (cov0, _) = _saxpy_oracle(base, lambda a: OS.run_ptb("saxpy", grid, a, 1, preempt_points=[], seed=0))
+
+    def fresh():
+        x, y = dev(base["x"]), dev(base["y"])
+        torch.cuda.synchronize()
+        return B.saxpy(x, y, base["a"]), y
+
+    k, y = fresh()                                                  # stop before anything ran
+    job = ctx.launch_ptb(k, 4, coverage=True, stop_at=0)
+    assert job.wait() == B.JOB_STOPPED and job.progress()[0] == 0
+    assert (job.coverage()["count"] == 0).all()
+    job.resume()
+    assert job.wait() == B.JOB_COMPLETE
+    rec = job.coverage()
+    job.free()
+    assert (rec["count"] == 1).all() and (rec["segment"] == 1).all()
+    assert_close_rel(host(y), want_y, 1e-6)
+
+    k, y = fresh()                                                  # one worker, in order
+    job = ctx.launch_ptb(k, 1, coverage=True)
+    assert job.wait() == B.JOB_COMPLETE
+    rec = job.coverage()
+    job.free()
+    assert_cover_equal(rec, cov0)
+    assert (rec["worker"] == 0).all()
+    assert_close_rel(host(y), want_y, 1e-6)
+
+    k, y = fresh()                                                  # one fetch takes the grid
+    job = ctx.launch_ptb(k, 3, chunk=1000, coverage=True)
+    assert job.wait() == B.JOB_COMPLETE
+    rec = job.coverage()
+    job.free()
+    assert (rec["count"] == 1).all() and len(set(rec["worker"].tolist())) == 1
+    assert_close_rel(host(y), want_y, 1e-6)
+
+    k, y = fresh()                                                  # one slice takes the grid
+    job = ctx.launch_sliced(k, 1000, coverage=True)
+    assert job.wait() == B.JOB_COMPLETE
+    assert (job.coverage()["count"] == 1).all()
+    job.free()
+    assert_close_rel(host(y), want_y, 1e-6)
+
+    empty = torch.zeros(0, device="cuda")
+    with pytest.raises(B.TallyError):
+        B.saxpy(empty, empty, 1.0)
+
+
 def test_saxpy_native_and_sliced(env):
     B, ctx, torch = env
     from gpu_util import dev, host, assert_cover_equal, assert_close_rel
