@@ -77,3 +77,29 @@ def test_entry_points_exist():
     import importlib
     g = importlib.import_module("__graft_entry__")
     assert callable(g.build) and callable(g.smoke)
+
+
+def test_header_is_plain_c():
+    """The boundary is a C ABI: the header compiles as C99 (and as C++) on its own, and a C
+    program that only includes it sees the struct sizes the binding assumes."""
+    import subprocess
+    import tempfile
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    hdr = os.path.join(root, "include", "tally.h")
+    for cc, std, lang in (("gcc", "-std=c99", "c"), ("g++", "-std=c++11", "c++")):
+        r = subprocess.run([cc, std, "-Wall", "-Wextra", "-pedantic", "-fsyntax-only", "-x", lang, hdr],
+                           capture_output=True, text=True, timeout=60)
+        assert r.returncode == 0 and r.stderr.strip() == "", r.stderr
+    prog = ('#include <stdio.h>\n#include "tally.h"\nint main(void){printf("%zu %zu %zu %zu %zu\\n",'
+            'sizeof(tally_gemm_bf16_args),sizeof(tally_kernel_desc),sizeof(tally_cover_rec),'
+            'sizeof(tally_config),sizeof(tally_sched_run_t));return 0;}\n')
+    with tempfile.TemporaryDirectory() as d:
+        src, exe = os.path.join(d, "s.c"), os.path.join(d, "s")
+        open(src, "w").write(prog)
+        subprocess.run(["gcc", "-std=c99", "-I", os.path.join(root, "include"), src, "-o", exe],
+                       check=True, timeout=60)
+        out = subprocess.run([exe], capture_output=True, text=True, timeout=10).stdout.split()
+    import ctypes as C
+    import paper_2410_07381_amd.binding as B
+    assert [int(v) for v in out] == [C.sizeof(B.GemmArgs), C.sizeof(B.KernelDesc), C.sizeof(B.CoverRec),
+                                     C.sizeof(B.Config), C.sizeof(B.SchedRun)]
