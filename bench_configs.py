@@ -159,6 +159,20 @@ def cfg2(torch, B, ctx, be_stream, args):
             "be_kernels_done": int(co["be_kernels_done"]),
             "preempt_p50_us": pct(co["preempt_latency_us"], 50),
         }
+    # slices enqueued two and three at a time: the launch round trip hides behind the slice
+    # that is running, the turnaround grows to as many slices
+    for sl, q in ((4096, 2), (2048, 3), (512, 4)):
+        t = _time(torch, B, be_stream, lambda: ctx.launch_sliced(red, sl, max_in_flight=q), reps=5,
+                  warm=1, wait_before_stop=True)
+        co = ctx.sched_run([hi], arrivals, [(red, (B.CFG_SLICED, sl, q))], tail_us=0.0)
+        lat = co["latency_us"][args.warmup:]
+        out.setdefault("slices_in_flight", {})[f"{sl}x{q}"] = {
+            "total_us": t[0], "GBps": nbytes / t[0] / 1e3, "of_native": nat[0] / t[0],
+            "hi_p50_us": pct(lat, 50), "hi_p99_us": pct(lat, 99),
+            "hi_p99_overhead_pct": (pct(lat, 99) - p99_solo) / p99_solo * 100.0,
+            "be_kernels_done": int(co["be_kernels_done"]),
+            "preempt_p50_us": pct(co["preempt_latency_us"], 50),
+        }
     # the persistent-worker alternative the profiler weighs against slicing
     for w, c in ((512, 32), (512, 8), (1024, 2)):
         t = _time(torch, B, be_stream, lambda: ctx.launch_ptb(red, w, chunk=c))
@@ -173,8 +187,10 @@ def cfg2(torch, B, ctx, be_stream, args):
             "n_preempts": int(co["n_preempts"]), "preempt_p50_us": pct(pre, 50),
             "preempt_p99_us": pct(pre, 99), "be_kernels_done": int(co["be_kernels_done"]),
         }
+    # (for a sliced candidate the third number is the count of slices enqueued at a time)
     cands = [(B.CFG_PTB, 512, 32), (B.CFG_PTB, 512, 8), (B.CFG_PTB, 1024, 2), (B.CFG_PTB, 256, 1),
-             (B.CFG_SLICED, 4096, 1), (B.CFG_SLICED, 512, 1)]
+             (B.CFG_SLICED, 4096, 1), (B.CFG_SLICED, 512, 1), (B.CFG_SLICED, 4096, 2),
+             (B.CFG_SLICED, 2048, 3)]
     meas, chosen = ctx.profile(red, _cap(B, ctx, red, cands), runs=10, threshold_ms=0.0316)
     out["profile_guided_choice"] = {"threshold_ms": 0.0316, "chosen": meas[chosen],
                                     "candidates": meas}

@@ -258,9 +258,11 @@ int tally_device_info(uint32_t *num_cus, uint32_t *lds_bytes_per_cu, uint32_t *w
 typedef struct {
   uint32_t kind;          /* 0 = persistent workers, 1 = sliced                          */
   uint32_t param;         /* worker count, or blocks per slice                            */
-  uint32_t chunk;         /* task indices per fetch (persistent workers), else 1          */
+  uint32_t chunk;         /* persistent workers: task indices per fetch; sliced: slices
+                             enqueued at a time (0 and 1 both mean one, as in the paper)   */
   float latency_ms;       /* mean whole-kernel latency over the profiling runs            */
-  float turnaround_ms;    /* Eq. 1 for persistent workers; one slice's time when sliced   */
+  float turnaround_ms;    /* Eq. 1 for persistent workers; sliced: one slice's time times
+                             the slices enqueued at a time                                 */
 } tally_config;
 
 /* Eq. 1: kernel_latency * worker_blocks / total_blocks (times `chunk`). */

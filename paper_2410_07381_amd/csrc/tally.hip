@@ -1009,8 +1009,11 @@ int tally_profile(tally_ctx *ctx, const tally_kernel_desc *desc, tally_config *c
         cands[i].turnaround_ms = (float)(tally_ptb_turnaround_ms(cands[i].latency_ms, cands[i].param,
                                                                  1, total) * share);
     } else {
+      // one slice's time, times the number of slices that may be enqueued at once
       uint64_t slices = (total + cands[i].param - 1) / cands[i].param;
-      cands[i].turnaround_ms = (float)(cands[i].latency_ms / (double)slices);
+      uint64_t inflight = cands[i].chunk ? cands[i].chunk : 1;
+      if (inflight > slices) inflight = slices;
+      cands[i].turnaround_ms = (float)(cands[i].latency_ms / (double)slices * (double)inflight);
     }
   }
   int pick = tally_select_config(cands, n, threshold_ms);
@@ -1036,7 +1039,7 @@ namespace {
 int launch_be_item(tally_ctx *ctx, const tally_be_item *it, tally_job **out) {
   const tally_config &c = it->config;
   if (c.kind == 0) return tally_launch_ptb(ctx, it->kernel, c.param, c.chunk ? c.chunk : 1, 0, out);
-  if (c.kind == 1) return tally_launch_sliced(ctx, it->kernel, c.param, 1, 0, out);
+  if (c.kind == 1) return tally_launch_sliced(ctx, it->kernel, c.param, c.chunk ? c.chunk : 1, 0, out);
   if (c.kind != 2) return TALLY_ERR_INVALID_ARG;
   tally_job *j;
   int rc = new_job(ctx, it->kernel, KIND_NATIVE, 0, &j);
