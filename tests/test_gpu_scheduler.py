@@ -165,17 +165,18 @@ def test_profile_picks_a_config_under_the_threshold(env):
     k = B.reduce_sum(x, partial)
     assert ctx.lookup_config(k) is None
     cands = [(B.CFG_PTB, 256, 1), (B.CFG_PTB, 1024, 4), (B.CFG_SLICED, 4096, 1),
-             (B.CFG_SLICED, 64, 1)]
+             (B.CFG_SLICED, 64, 1), (B.CFG_SLICED, 4096, 2)]       # the last: two slices in flight
+    from oracle import profiler as OP
     meas, chosen = ctx.profile(k, cands, runs=3, threshold_ms=0.0316)
     assert all(m["latency_ms"] > 0 and m["turnaround_ms"] > 0 for m in meas)
     for m in meas:                                   # Eq. 1 / one-slice time
         if m["kind"] == B.CFG_PTB:
             want = m["latency_ms"] * m["param"] * m["chunk"] / k.total_blocks
         else:
-            want = m["latency_ms"] / -(-k.total_blocks // m["param"])
+            slices = -(-k.total_blocks // m["param"])
+            want = OP.sliced_turnaround_ms(m["latency_ms"] / slices, min(m["chunk"], slices))
         assert abs(m["turnaround_ms"] - want) <= 1e-5 * want + 1e-9
     # the library's choice equals the oracle's selection rule on the same measurements
-    from oracle import profiler as OP
     o = OP.select_config([{"kind": "ptb" if m["kind"] == 0 else "sliced", "param": m["param"],
                            "latency_ms": m["latency_ms"], "turnaround_ms": m["turnaround_ms"]}
                           for m in meas], 0.0316)
