@@ -26,9 +26,15 @@ def ptb_turnaround_ms(kernel_latency_ms, worker_blocks, total_blocks):
     return kernel_latency_ms * worker_blocks / total_blocks
 
 
-def sliced_turnaround_ms(slice_latency_ms, in_flight=1):
-    """Completion time of the slices that cannot be recalled once enqueued."""
-    return slice_latency_ms * in_flight
+def sliced_turnaround_ms(slice_latency_ms, in_flight=1, n_slices=None):
+    """Section 4.2: the completion time of a single slice.  Where more than one slice is
+    kept enqueued (`in_flight`; the paper enqueues one), none of them can be recalled, so
+    the estimate is the completion time of all of them; a kernel never has more slices in
+    flight than it has slices."""
+    if in_flight < 1:
+        raise ValueError("in_flight must be positive")
+    q = in_flight if n_slices is None else min(in_flight, n_slices)
+    return slice_latency_ms * q
 
 
 def ptb_candidates(total_blocks, num_cus, max_blocks_per_cu):

@@ -115,9 +115,10 @@ class PtbMachine:
         self.total = int(total)
         self.W = int(workers)
         self.order = order
-        # task indices taken per fetch (1 is the paper's form): an int, or a function of the
-        # number of indices not yet handed out, for schedules that shrink towards the end
-        self.chunk = chunk if callable(chunk) else int(chunk)
+        # consecutive task indices taken per fetch (1 is the paper's form)
+        self.chunk = int(chunk)
+        if self.chunk < 1:
+            raise ValueError("chunk must be positive")
         self.held_end = [-1] * self.W
         self.counter = 0
         self.flag = False
@@ -151,11 +152,6 @@ class PtbMachine:
     def complete(self):
         return self.drained() and self.progress() == self.total
 
-    def _ask(self):
-        if callable(self.chunk):
-            return max(1, int(self.chunk(max(self.total - self.counter, 0))))
-        return self.chunk
-
     # -- transitions --------------------------------------------------------------------
     def raise_flag(self):
         self.flag = True
@@ -170,7 +166,7 @@ class PtbMachine:
                     self.state[w] = EXITED
                     return
                 idx = self.counter
-                n = self._ask()
+                n = self.chunk
                 self.counter += n
                 if idx >= self.total:
                     self.state[w] = EXITED
@@ -179,7 +175,7 @@ class PtbMachine:
                 self.held_end[w] = min(idx + n, self.total)
             else:  # wrong order: fetch first, then honour the flag and drop the index
                 idx = self.counter
-                n = self._ask()
+                n = self.chunk
                 self.counter += n
                 if idx >= self.total or self.flag:
                     self.state[w] = EXITED

@@ -27,6 +27,45 @@ def test_eq1_limits():
     assert P.ptb_turnaround_ms(1.0, 512, 4096) == 2 * P.ptb_turnaround_ms(1.0, 256, 4096)
 
 
+def test_sliced_turnaround_hand_table():
+    # one slice at a time (the paper's form): the time of one slice
+    assert P.sliced_turnaround_ms(0.010) == 0.010
+    # three slices of 10 us kept enqueued: all three must finish, 30 us
+    assert P.sliced_turnaround_ms(0.010, 3) == pytest.approx(0.030)
+    # a kernel of two slices cannot have three in flight
+    assert P.sliced_turnaround_ms(0.010, 3, n_slices=2) == pytest.approx(0.020)
+    assert P.sliced_turnaround_ms(0.010, 8, n_slices=1) == pytest.approx(0.010)
+    with pytest.raises(ValueError):
+        P.sliced_turnaround_ms(0.010, 0)
+
+
+@pytest.mark.parametrize("d,q,n", [(4, 1, 6), (3, 2, 7), (5, 3, 4), (2, 4, 3), (1, 2, 9)])
+def test_sliced_turnaround_is_the_worst_drain_of_a_simulated_queue(d, q, n):
+    """A queue simulated tick by tick: n slices of d ticks each run one after another, the
+    driver keeps at most q enqueued and stops enqueueing when the request arrives.  The
+    longest wait, over every arrival tick, for the enqueued slices to finish is what the
+    estimate must equal."""
+    worst = 0
+    for t_req in range(n * d + 1):
+        issued = finished = busy_left = t = 0
+        while True:
+            # within a tick: the driver tops the queue up, then (at t_req) the request arrives
+            if t <= t_req:
+                while issued < n and issued - finished < q:
+                    issued += 1
+            if busy_left == 0 and issued > finished:
+                busy_left = d                    # the next enqueued slice starts
+            if t >= t_req and issued == finished:
+                break                            # nothing enqueued is left: drained
+            if busy_left > 0:
+                busy_left -= 1
+                if busy_left == 0:
+                    finished += 1
+            t += 1
+        worst = max(worst, t - t_req)
+    assert worst == P.sliced_turnaround_ms(d, q, n_slices=n)
+
+
 def test_candidates():
     assert P.ptb_candidates(65536, 256, 4) == [256, 512, 768, 1024]
     assert P.ptb_candidates(256, 256, 8) == [256]            # capped at the grid size

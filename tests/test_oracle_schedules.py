@@ -146,16 +146,6 @@ def test_exactly_once_with_chunked_fetch(total, workers, chunk):
     assert not f["lost"] and not f["dup"] and not f["prefix_broken"]
 
 
-def test_exactly_once_with_shrinking_fetch_sizes():
-    # requests that shrink with the work left (any positive size keeps the invariants)
-    f = _explore(7, 2, "check_then_fetch", max_preempts=2, chunk=lambda rem: min(3, rem // 2))
-    assert f["finals"] > 0
-    assert not f["lost"] and not f["dup"] and not f["prefix_broken"]
-    cov, log = S.run_ptb(None, (101, 1, 1), {}, 5, preempt_points=[40], seed=3,
-                         chunk=lambda rem: min(8, rem // 10))
-    assert cov.exactly_once() and log[-1] == 101 and 40 <= log[0] < 48
-
-
 def test_chunked_fetch_drains_on_a_chunk_boundary():
     cov, log = S.run_ptb(None, (37, 1, 1), {}, 3, preempt_points=[5, 18], seed=2, chunk=4)
     assert cov.exactly_once()
