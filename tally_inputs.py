@@ -106,6 +106,18 @@ def attn_decode_inputs(tokens=2048, heads=32, dim=128, scale=0.02, config_index=
     }
 
 
+def rolled_blocks_bf16(rng, blocks, rows, cols, scale):
+    """A [blocks, rows, cols] bf16 tensor for operands too large to draw element by element
+    in a test: one seeded N(0, scale) block of rows x cols, and for block z a copy rolled by
+    (13 z + 1) rows and (29 z + 5) columns, so that the blocks differ from one another while
+    every element keeps the distribution of the first."""
+    base = normal_bf16(rng, (rows, cols), scale)
+    out = np.empty((blocks, rows, cols), dtype=np.uint16)
+    for z in range(blocks):
+        out[z] = np.roll(base, (13 * z + 1, 29 * z + 5), axis=(0, 1))
+    return out
+
+
 def poisson_arrivals_us(rate_per_s, count, config_index, stream=7):
     """Open-loop arrival times (microseconds from t0) of a Poisson process."""
     rng = rng_for(config_index, stream)

@@ -8,6 +8,11 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 
+# The tests with several best-effort clients need 2 + 2n hardware queues; HIP reads the
+# variable when it initialises, so it is set here, before any test imports torch.
+os.environ.setdefault("GPU_MAX_HW_QUEUES", "20")
+
+
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
 

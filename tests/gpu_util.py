@@ -72,3 +72,24 @@ def run_job_to_completion(job, max_resumes=100000):
             return states
         job.resume()
     raise AssertionError("job did not complete")
+
+
+def oracle_block_sums(x_host, blocks=None):
+    """Per-block partial sums of the reduction kernel from the oracle, for all logical
+    blocks or for the listed ones.  Returns (block indices, partials)."""
+    n = int(x_host.size)
+    nb = OK.grid_of("reduce_sum", {"n": n})[0]
+    idx = np.arange(nb) if blocks is None else np.asarray(sorted(set(int(b) for b in blocks)))
+    a = {"x": x_host.reshape(-1), "n": n, "partial": np.zeros(nb, np.float32)}
+    for b in idx:
+        OK.exec_block("reduce_sum", (int(b), 0, 0), (nb, 1, 1), a)
+    return idx, a["partial"][idx]
+
+
+def oracle_softmax_rows(x_rows):
+    """Row softmax of a [rows, cols] fp32 array through the oracle's logical blocks."""
+    rows, cols = x_rows.shape
+    a = {"x": np.ascontiguousarray(x_rows), "y": np.zeros((rows, cols), np.float32), "rows": rows,
+         "cols": cols}
+    OS.run_native("softmax_f32", OK.grid_of("softmax_f32", a), a)
+    return a["y"]

@@ -293,8 +293,10 @@ def test_async_flag_preemption_prefix_and_exactly_once(env, workers, chunk):
     cov, log = OS.run_ptb(None, (nb, 1, 1), {}, workers, preempt_points=pts, seed=7, chunk=chunk)
     assert log == pts + [nb]
     assert_cover_equal(rec, cov)
-    want = host(x).reshape(nb, 4096).sum(axis=1, dtype=np.float64)
-    assert np.allclose(host(partial), want, rtol=2e-6, atol=0)
+    from gpu_util import oracle_block_sums, assert_close_rel
+    sample = [0, nb - 1] + [int(v) for v in np.random.default_rng(3).integers(nb, size=1500)]
+    idx, want = oracle_block_sums(host(x), sample)
+    assert_close_rel(host(partial)[idx], want, 2e-6)
 
 
 def test_preemption_reaches_workers_that_fill_the_gpu(env):
@@ -321,10 +323,8 @@ def test_preemption_reaches_workers_that_fill_the_gpu(env):
     assert job.wait() == B.JOB_COMPLETE
     job.free()
     torch.cuda.synchronize()
-    rows = host(y)[::4099]
-    h = host(x)[::4099].astype(np.float64)
-    e = np.exp(h - h.max(axis=1, keepdims=True))
-    assert np.allclose(rows, e / e.sum(axis=1, keepdims=True), rtol=1e-5, atol=1e-7)
+    from gpu_util import oracle_softmax_rows, assert_close_rel
+    assert_close_rel(host(y)[::4099], oracle_softmax_rows(host(x)[::4099]), 1e-5, 1e-7)
 
 
 # ------------------------------------------------------------------ reduction, configuration 2 shape
