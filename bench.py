@@ -5,13 +5,17 @@ Workload (`config.workload` = "cfg1"): a best-effort bf16 GEMM, M = N = K = 4096
 256x256 logical tiles, run back to back as a preemptible persistent-worker kernel,
 next to a high-priority bf16 GEMV (1x4096 by 4096x4096) that arrives every 1 ms.
 
-A "step" is one high-priority period: one arrival, its preempt + native launch, and the
-best-effort work scheduled around it.  K steps are timed, after W warm-up steps, for
-  (1) the high-priority job alone, (2) the best-effort job alone, (3) both co-located
-under the priority scheduler; the pair (1), (3) is run `--repeats` times, alternating, and
-the reported percentiles are the medians over the repeats (pooled ones beside them).  From those: p50/p99 of the high-priority
-latency alone and co-located, the p99 overhead, best-effort throughput retained,
-preemption latency.
+A "step" is PERIODS_PER_STEP (100) high-priority periods: 100 arrivals, each with its
+preempt + native launch, and the best-effort work scheduled around them, so that the
+default 20 steps give the configuration's 2000 arrivals per run.  K steps are timed, after
+W warm-up steps, for (1) the high-priority job alone, (2) the best-effort job alone, (3) both
+co-located under the priority scheduler; the pair (1), (3) is run `--repeats` times,
+alternating, and the reported percentiles are the medians over the repeats (pooled ones
+beside them).  From those: p50/p99 of the high-priority latency alone and co-located, the
+p99 overhead, best-effort throughput retained, preemption latency.  A p99 is only reported
+from 1000 samples per run upwards; below that the fields are null and the line says why.
+Two latencies are given per request: the host clock's (scheduled arrival to completion
+observed) and the device-side one (the part after the host's launch calls returned).
 A separate leg times single launches of the dominant kernel (GEMM, native and
 persistent-worker form) with HIP events for the roofline figures, and the CPU oracle is
 timed on a bounded sample of the same work.
@@ -69,14 +73,9 @@ def time_kernel_events(torch, ctx, B, be_stream, launch, reps, warm=3, batch=10)
     return float(np.mean(ms)), float(np.min(ms))
 
 
-def cpu_baseline(g, gv, budget_s=15.0):
-    """The CPU oracle, as it stands, on a bounded sample of the same workload."""
+def _oracle_leg(g, gv, budget_s):
+    """Logical GEMM tiles through the oracle until the budget is used, then three GEMV calls."""
     from oracle import kernels as OK
-    try:
-        from threadpoolctl import threadpool_info
-        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
-    except Exception:
-        cores = 1
     a = dict(g, C=np.zeros((1, g["m"], g["n"]), np.uint16))
     t0 = time.perf_counter()
     tiles = 0
@@ -86,35 +85,76 @@ def cpu_baseline(g, gv, budget_s=15.0):
     t_gemm = time.perf_counter() - t0
     v = dict(gv, y=np.zeros(gv["n"], np.uint16))
     t1 = time.perf_counter()
-    reps = 0
-    while reps < 3:
+    for _ in range(3):
         for b in range(OK.grid_of("gemv_bf16", v)[0]):
             OK.exec_block("gemv_bf16", (b, 0, 0), None, v)
-        reps += 1
-    t_gemv = (time.perf_counter() - t1) / reps
-    flops = tiles * 2.0 * 256 * 256 * g["k"]
+    t_gemv = (time.perf_counter() - t1) / 3
+    return tiles, t_gemm, t_gemv
+
+
+def cpu_baseline(g, gv, budget_s=9.0):
+    """The CPU oracle, as it stands, on a bounded sample of the same workload: once on one
+    thread and once on every core this process may use (the oracle's matrix products run in
+    NumPy's BLAS, whose thread pool is what spreads a logical tile over the cores)."""
+    from threadpoolctl import threadpool_info, threadpool_limits
+    allowed = len(os.sched_getaffinity(0))
+    pool = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    with threadpool_limits(limits=1):
+        tiles1, t1, gv1 = _oracle_leg(g, gv, budget_s)
+    tilesn, tn, gvn = _oracle_leg(g, gv, budget_s)
+    per_tile = 2.0 * 256 * 256 * g["k"]
     return {
-        "value": flops / t_gemm / 1e9, "unit": "GFLOP/s (best-effort GEMM tiles)",
-        "cores": int(cores), "kind": "oracle",
-        "sample": f"{tiles} of 256 logical GEMM tiles in {t_gemm:.1f} s; "
-                  f"hi-pri GEMV {t_gemv * 1e3:.1f} ms per call (3 calls)",
-        "gemv_latency_us": t_gemv * 1e6,
+        "value": tilesn * per_tile / tn / 1e9, "unit": "GFLOP/s (best-effort GEMM tiles)",
+        "cores": int(min(pool, allowed)), "kind": "oracle",
+        "sample": f"{tilesn} of 256 logical GEMM tiles in {tn:.1f} s on all cores; "
+                  f"hi-pri GEMV {gvn * 1e3:.1f} ms per call (3 calls)",
+        "affinity_cores": allowed, "blas_threads": int(pool),
+        "gemv_latency_us": gvn * 1e6,
+        "single_thread": {"value": tiles1 * per_tile / t1 / 1e9, "cores": 1,
+                          "sample": f"{tiles1} of 256 logical GEMM tiles in {t1:.1f} s",
+                          "gemv_latency_us": gv1 * 1e6},
     }
+
+
+def profile_traffic():
+    """HBM-side bytes of one persistent-worker GEMM launch, from the committed rocprofv3
+    counter summary (the line that starts with TRAFFIC): FETCH_SIZE and WRITE_SIZE in KiB per
+    dispatch, each scaled by what the same counter read for a plain copy of known size."""
+    path = os.path.join(ROOT, "profiles", "gemm_bf16_cfg1_rocprofv3.txt")
+    try:
+        with open(path) as f:
+            for line in f:
+                if line.startswith("TRAFFIC gemm_ptb"):
+                    kv = dict(t.split("=") for t in line.split()[2:])
+                    return (float(kv["fetch_kib"]) * 1024 * float(kv["fetch_scale"]) +
+                            float(kv["write_kib"]) * 1024 * float(kv["write_scale"]),
+                            os.path.relpath(path, ROOT))
+    except (OSError, KeyError, ValueError):
+        pass
+    return None, None
+
+
+PERIODS_PER_STEP = 100     # arrivals of the high-priority job in one step
+MIN_P99_SAMPLES = 1000     # a nearest-rank p99 of fewer samples is one of its ten largest
+HW_QUEUES = 20             # hardware queues asked of HIP (its default is 4), see main()
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=None)
-    ap.add_argument("--warmup", type=int, default=None)
+    ap.add_argument("--steps", type=int, default=None,
+                    help=f"timed steps; one step = {PERIODS_PER_STEP} high-priority arrivals")
+    ap.add_argument("--warmup", type=int, default=None, help="untimed steps before them")
     ap.add_argument("--workload", choices=["cfg0", "cfg1", "cfg2", "cfg3", "cfg4", "sweep_threshold", "sweep_load", "multi_be"], default="cfg1",
                     help="cfg1 is the headline workload; the others print one JSON line each "
                          "with that configuration's figures")
     ap.add_argument("--period-us", type=float, default=1000.0)
     ap.add_argument("--workers", type=int, default=256)
+    ap.add_argument("--threshold-ms", type=float, default=None,
+                    help="turnaround-latency threshold of the profile-guided choice (cfg3, cfg4)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--roofline-reps", type=int, default=20)
-    ap.add_argument("--repeats", type=int, default=3,
+    ap.add_argument("--repeats", type=int, default=5,
                     help="cfg1: the (alone, co-located) pair of K-step runs is made this many times, "
                          "alternating, and the median over the repeats of each percentile is "
                          "reported; the p99 of one 2000-sample run moves by several microseconds")
@@ -123,9 +163,9 @@ def main():
                          "copy of known size (for rocprofv3 counter runs); coloc: only the "
                          "co-located scheduling run")
     args = ap.parse_args()
-    defaults = {"cfg0": (1, 0), "cfg1": (2000, 100), "cfg2": (1500, 100), "cfg3": (500, 50),
-                "cfg4": (1000, 100), "sweep_threshold": (1500, 100),
-                "sweep_load": (2000, 100), "multi_be": (2000, 100)}[args.workload]
+    defaults = {"cfg0": (1, 0), "cfg1": (20, 5), "cfg2": (20, 1), "cfg3": (20, 1),
+                "cfg4": (20, 1), "sweep_threshold": (15, 1),
+                "sweep_load": (20, 1), "multi_be": (20, 1)}[args.workload]
     if args.steps is None:
         args.steps = defaults[0]
     if args.warmup is None:
@@ -134,6 +174,16 @@ def main():
         print("bench.py: this build measures one GPU only (the method is a per-GPU mechanism); "
               "run with --gpus 1", file=sys.stderr)
         sys.exit(2)
+    args.n_arrivals = args.steps * PERIODS_PER_STEP      # timed arrivals per run
+    args.n_warm = args.warmup * PERIODS_PER_STEP         # untimed arrivals before them
+
+    # The scheduler needs a hardware queue each for the high-priority stream, the best-effort
+    # stream and the relay stream (two more per further best-effort client) beside the null
+    # stream's; HIP folds a process's streams onto GPU_MAX_HW_QUEUES queues (4 unless set) and
+    # reads the variable when it initialises.  This program asks for 20 unless the caller set
+    # something else, and every JSON line records the value in effect.
+    os.environ.setdefault("GPU_MAX_HW_QUEUES", str(HW_QUEUES))
+    hwq = os.environ["GPU_MAX_HW_QUEUES"]
 
     import torch
     import tally_inputs as TI
@@ -147,7 +197,8 @@ def main():
     if args.workload != "cfg1":
         import bench_configs
         out = bench_configs.WORKLOADS[args.workload](torch, B, ctx, be_stream, args)
-        out.update({"n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "data": "synthetic"})
+        out.update({"n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "data": "synthetic",
+                    "arrivals_per_step": PERIODS_PER_STEP, "gpu_max_hw_queues": hwq})
         ctx.close()
         print(json.dumps(out))
         return
@@ -190,20 +241,20 @@ def main():
                           "copy_bytes_read": 4 << 28, "copy_bytes_written": 4 << 28}))
         return
 
-    K, Wm = args.steps, args.warmup
+    K, Wm = args.n_arrivals, args.n_warm
     arrivals = TI.periodic_arrivals_us(args.period_us, K + Wm)
     if args.leg == "coloc":
         co = ctx.sched_run([gemv], arrivals, [(gemm, be_cfg)], policy=B.POLICY_TALLY, tail_us=0.0)
         lat = co["latency_us"][Wm:]
         ctx.close()
-        print(json.dumps({"leg": "coloc", "p50": pct(lat, 50), "p90": pct(lat, 90),
-                          "p99": pct(lat, 99), "max": float(lat.max()),
+        print(json.dumps({"leg": "coloc", "n": int(len(lat)), "p50": pct(lat, 50), "p90": pct(lat, 90),
+                          "p99": pct(lat, 99) if len(lat) >= MIN_P99_SAMPLES else None,
+                          "max": float(lat.max()),
                           "be_kernels": int(co["be_kernels_done"])}))
         return
-    window_us = float(arrivals[-1])
 
     # ---- (2) best-effort alone -----------------------------------------------------------
-    ctx.sched_run([], [], [(gemm, be_cfg)], tail_us=Wm * args.period_us)          # warm-up
+    ctx.sched_run([], [], [(gemm, be_cfg)], tail_us=max(Wm, 100) * args.period_us)   # warm-up
     be_solo = ctx.sched_run([], [], [(gemm, be_cfg)], tail_us=K * args.period_us)
     tput_solo = be_solo["be_kernels_done"] / (be_solo["window_us"] * 1e-6)
     # ---- (1) high-priority alone and (3) co-located under the priority scheduler, alternating
@@ -215,33 +266,52 @@ def main():
         co_runs.append(ctx.sched_run([gemv], arrivals, [(gemm, be_cfg)], policy=B.POLICY_TALLY,
                                      tail_us=0.0))
         t_wall += time.perf_counter() - t_wall0
-    lat_solo = np.concatenate([r["latency_us"][Wm:] for r in solo_runs])
-    lat_co = np.concatenate([r["latency_us"][Wm:] for r in co_runs])
+    host_lat = lambda r: r["latency_us"][Wm:]
     # the part of a latency that follows the host's launch calls (device side and completion)
-    dev_solo = np.concatenate([(r["latency_us"] - r["issue_us"])[Wm:] for r in solo_runs])
-    dev_co = np.concatenate([(r["latency_us"] - r["issue_us"])[Wm:] for r in co_runs])
+    dev_lat = lambda r: (r["latency_us"] - r["issue_us"])[Wm:]
     co = {"window_us": sum(r["window_us"] for r in co_runs),
           "be_kernels_done": sum(r["be_kernels_done"] for r in co_runs),
           "n_preempts": sum(r["n_preempts"] for r in co_runs),
           "preempt_latency_us": np.concatenate([r["preempt_latency_us"] for r in co_runs])}
     tput_co = co["be_kernels_done"] / (co["window_us"] * 1e-6)
-    per_repeat = [(pct(c["latency_us"][Wm:], 99) / pct(s_["latency_us"][Wm:], 99) - 1.0) * 100.0
-                  for s_, c in zip(solo_runs, co_runs)]
+    n_run = int(len(host_lat(co_runs[0])))
+    p99_ok = n_run >= MIN_P99_SAMPLES
     # ---- decomposition: same load with native best-effort kernels, and with no scheduling -
-    nat = ctx.sched_run([gemv], arrivals[: Wm + max(K // 4, 200)], [(gemm, (B.CFG_NATIVE, 1, 1))],
+    n_dec = Wm + max(K // 2, min(K, MIN_P99_SAMPLES))
+    nat = ctx.sched_run([gemv], arrivals[:n_dec], [(gemm, (B.CFG_NATIVE, 1, 1))],
                         policy=B.POLICY_PRIORITY_NATIVE, tail_us=0.0)
-    nos = ctx.sched_run([gemv], arrivals[: Wm + max(K // 4, 200)], [(gemm, (B.CFG_NATIVE, 1, 1))],
+    nos = ctx.sched_run([gemv], arrivals[:n_dec], [(gemm, (B.CFG_NATIVE, 1, 1))],
                         policy=B.POLICY_NONE, tail_us=0.0)
 
     # Percentiles: the median over the repeats of each run's own p50 / p99.  The p99 of one
     # 2000-sample run is its 20th largest value; an otherwise idle GPU answers a handful of
-    # requests late (40-50 us) in some runs and not in others, which moves the p99 of the
-    # ALONE run between 18 and 48 us, so one bad run must not decide the figure (pooling
-    # the samples lets it).  The pooled percentiles are reported beside these.
-    med = lambda runs, q: float(np.median([pct(r["latency_us"][Wm:], q) for r in runs]))
-    p50s, p99s = med(solo_runs, 50), med(solo_runs, 99)
-    p50c, p99c = med(co_runs, 50), med(co_runs, 99)
-    overhead = (p99c - p99s) / p99s * 100.0
+    # requests late (40-50 us) in some runs and not in others, so one bad run must not decide
+    # the figure (pooling the samples lets it).  The pooled percentiles are reported beside
+    # these.  Below MIN_P99_SAMPLES samples per run no p99 is reported at all.
+    def summary(get):
+        med = lambda runs, q: float(np.median([pct(get(r), q) for r in runs]))
+        o = {"solo_p50": med(solo_runs, 50), "coloc_p50": med(co_runs, 50), "n_per_run": n_run,
+             "runs": len(co_runs)}
+        o["p50_overhead_pct"] = (o["coloc_p50"] - o["solo_p50"]) / o["solo_p50"] * 100.0
+        if p99_ok:
+            o["solo_p99"], o["coloc_p99"] = med(solo_runs, 99), med(co_runs, 99)
+            o["p99_overhead_pct"] = (o["coloc_p99"] - o["solo_p99"]) / o["solo_p99"] * 100.0
+            o["p99_us_per_repeat"] = {"solo": [pct(get(r), 99) for r in solo_runs],
+                                      "coloc": [pct(get(r), 99) for r in co_runs]}
+            o["p99_overhead_pct_per_repeat"] = [
+                (pct(get(c), 99) / pct(get(s_), 99) - 1.0) * 100.0 for s_, c in zip(solo_runs, co_runs)]
+            ps = np.concatenate([get(r) for r in solo_runs])
+            pc = np.concatenate([get(r) for r in co_runs])
+            o["pooled"] = {"n": int(len(pc)), "solo_p50": pct(ps, 50), "solo_p99": pct(ps, 99),
+                           "coloc_p50": pct(pc, 50), "coloc_p99": pct(pc, 99),
+                           "p99_overhead_pct": (pct(pc, 99) / pct(ps, 99) - 1.0) * 100.0}
+        else:
+            o["solo_p99"] = o["coloc_p99"] = o["p99_overhead_pct"] = None
+            o["p99_undefined"] = (f"{n_run} samples per run: a p99 needs at least {MIN_P99_SAMPLES} "
+                                  f"(--steps {MIN_P99_SAMPLES // PERIODS_PER_STEP} or more)")
+        return o
+    host_side, device_side = summary(host_lat), summary(dev_lat)
+    overhead = host_side["p99_overhead_pct"]
     retained = tput_co / tput_solo * 100.0
     pre = co["preempt_latency_us"]
 
@@ -258,13 +328,14 @@ def main():
     tf_nat = flops / (ms_nat * 1e-3) / 1e12
     tf_ptb = flops / (ms_ptb * 1e-3) / 1e12
     gemv_bytes = 4096 * 4096 * 2 + 2 * 4096 * 2
+    traffic, traffic_src = profile_traffic()
     roofline = {
         "bound": "mfma", "kernel": "ptb_kernel<GemmBody> (best-effort GEMM, persistent workers)",
         "achieved": tf_ptb, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
         "frac": tf_ptb / PEAK_BF16_TFLOPS,
-        # HBM-side bytes per launch from the committed rocprofv3 counter runs
-        # (profiles/gemm_bf16_cfg1_rocprofv3.txt): FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0
-        "traffic": 164355.0 * 1024 * 2.0 + 32784.1 * 1024,
+        # L2-side bytes per launch, not measured in this run: read from the committed
+        # rocprofv3 counter summary named in traffic_source (FETCH_SIZE, WRITE_SIZE, scaled)
+        "traffic": traffic, "traffic_source": traffic_src,
         "traffic_unit": "bytes per launch (algorithmic: 100663296)",
         "avg_launch_ms": ms_ptb,
         "native": {"achieved": tf_nat, "frac": tf_nat / PEAK_BF16_TFLOPS, "avg_launch_ms": ms_nat},
@@ -278,44 +349,43 @@ def main():
                         "avg_launch_ms": ms_gemv},
     }
 
+    dec_p99 = lambda r: pct(r["latency_us"][Wm:], 99) if len(r["latency_us"][Wm:]) >= MIN_P99_SAMPLES else None
     out = {
         "metric": METRIC,
         "value": overhead,
-        "unit": "% (hi-pri p99 latency overhead, co-located vs alone)",
-        "n_gpus": 1, "steps": K, "warmup": Wm,
-        "ms_per_step": co["window_us"] / ((K + Wm) * len(co_runs)) / 1e3,
+        "unit": "% (hi-pri p99 latency overhead, co-located vs alone; host clock, scheduled "
+                "arrival to completion observed)",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": co["window_us"] / (args.steps + args.warmup) / len(co_runs) / 1e3,
         "repeats": len(co_runs),
         "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "cfg1: best-effort bf16 GEMM 4096^3 (256x256 logical tiles, "
                                f"persistent workers W={args.workers}) + hi-pri bf16 GEMV 4096x4096 "
                                f"every {args.period_us:.0f} us",
+                   "step": f"{PERIODS_PER_STEP} high-priority periods (arrivals) and the best-effort "
+                           "work scheduled around them",
+                   "arrivals_per_step": PERIODS_PER_STEP, "timed_arrivals_per_run": n_run,
                    "be_form": "ptb", "workers": args.workers, "chunk": 1,
-                   "period_us": args.period_us},
-        "hi_pri_latency_us": {"solo_p50": p50s, "solo_p99": p99s, "coloc_p50": p50c,
-                              "coloc_p99": p99c, "n": int(len(lat_co)),
-                              "after_launch_calls": {"solo_p50": pct(dev_solo, 50),
-                                                     "solo_p99": pct(dev_solo, 99),
-                                                     "coloc_p50": pct(dev_co, 50),
-                                                     "coloc_p99": pct(dev_co, 99)}},
-        "p99_overhead_pct_per_repeat": per_repeat,
-        "pooled_latency_us": {"solo_p50": pct(lat_solo, 50), "solo_p99": pct(lat_solo, 99),
-                              "coloc_p50": pct(lat_co, 50), "coloc_p99": pct(lat_co, 99)},
-        "p99_us_per_repeat": {"solo": [pct(r["latency_us"][Wm:], 99) for r in solo_runs],
-                              "coloc": [pct(r["latency_us"][Wm:], 99) for r in co_runs]},
+                   "period_us": args.period_us, "gpu_max_hw_queues": hwq},
+        "hi_pri_latency_us": host_side,
+        "hi_pri_device_side_latency_us": dict(
+            device_side, definition="completion observed minus the moment the request's launch "
+                                    "calls had returned on the host: the GPU's share of the latency"),
         "p99_overhead_pct": overhead,
-        "p50_overhead_pct": (p50c - p50s) / p50s * 100.0,
+        "p99_overhead_pct_device_side": device_side["p99_overhead_pct"],
+        "p50_overhead_pct": host_side["p50_overhead_pct"],
         "be_tput_retained_pct": retained,
         "be_tput": {"solo_kernels_per_s": tput_solo, "coloc_kernels_per_s": tput_co,
                     "solo_tflops": tput_solo * flops / 1e12, "coloc_tflops": tput_co * flops / 1e12},
         "preempt_latency_us": {"n": int(co["n_preempts"]),
                                "p50": pct(pre, 50) if len(pre) else None,
-                               "p99": pct(pre, 99) if len(pre) else None,
+                               "p99": pct(pre, 99) if len(pre) >= MIN_P99_SAMPLES else None,
                                "max": float(pre.max()) if len(pre) else None},
         "decomposition_p99_us": {
-            "ideal": p99s, "full": p99c,
-            "priority_native_be": pct(nat["latency_us"][Wm:], 99),
-            "no_scheduling": pct(nos["latency_us"][Wm:], 99)},
+            "ideal": host_side["solo_p99"], "full": host_side["coloc_p99"],
+            "priority_native_be": dec_p99(nat), "no_scheduling": dec_p99(nos),
+            "n": int(len(nat["latency_us"][Wm:]))},
         "transform_overhead_pct": (ms_ptb / ms_nat - 1.0) * 100.0,
         "roofline": roofline,
         "paper_context": "Tally on A100-40GB: 7.2% avg p99 overhead (TGS 188.9%), >=80% of TGS "

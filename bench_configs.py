@@ -24,11 +24,25 @@ PEAK_HBM_GBS = 8000.0
 PEAK_BF16_TFLOPS = 2500.0
 
 
+MIN_P99_SAMPLES = 1000     # below that a nearest-rank p99 is one of the ten largest samples
+
+
 def pct(a, q):
+    """Nearest-rank percentile; None for an empty sample."""
     s = np.sort(np.asarray(a))
     if len(s) == 0:
         return None
     return float(s[max(int(np.ceil(q / 100.0 * len(s))) - 1, 0)])
+
+
+def p99(a):
+    """The 99th percentile, or None where the sample is too small for one."""
+    return p99(a) if len(a) >= MIN_P99_SAMPLES else None
+
+
+def ovh(x, base):
+    """Overhead of x over base in percent; None if either is missing."""
+    return None if x is None or base is None else (x - base) / base * 100.0
 
 
 def _time(torch, B, stream, launch, reps=10, warm=2, wait_before_stop=False):
@@ -130,17 +144,17 @@ def cfg2(torch, B, ctx, be_stream, args):
             job.free()
         return {"leg": "roofline", "workload": "cfg2", "reps": args.roofline_reps,
                 "copy_bytes_read": nbytes, "copy_bytes_written": nbytes, "sum_bytes_read": nbytes}
-    count = args.steps
+    count = args.n_arrivals + args.n_warm
     arrivals = TI.poisson_arrivals_us(500.0, count, config_index=2)
     solo = ctx.sched_run([hi], arrivals, [])
-    p99_solo = pct(solo["latency_us"][args.warmup:], 99)
+    p99_solo = p99(solo["latency_us"][args.n_warm:])
     nat = _time(torch, B, be_stream, lambda: (ctx.launch_native(red), None)[1])
     out = {
         "workload": "cfg2: fp32 sum of 2^28 U(0,1) (65536 blocks x 256 threads) as sliced launches "
                     "against a hi-pri 2^20 SAXPY, Poisson 500/s",
         "native_us": nat[0], "native_GBps": nbytes / nat[0] / 1e3,
         "native_hbm_frac": nbytes / nat[0] / 1e3 / PEAK_HBM_GBS,
-        "hi_solo_p50_us": pct(solo["latency_us"][args.warmup:], 50), "hi_solo_p99_us": p99_solo,
+        "hi_solo_p50_us": pct(solo["latency_us"][args.n_warm:], 50), "hi_solo_p99_us": p99_solo,
         "slices": {},
     }
     for s in (4096, 512, 64, 8, 1):
@@ -149,13 +163,13 @@ def cfg2(torch, B, ctx, be_stream, args):
         t = _time(torch, B, be_stream, lambda: ctx.launch_sliced(red, s), reps=reps, warm=1,
                   wait_before_stop=True)
         co = ctx.sched_run([hi], arrivals, [(red, (B.CFG_SLICED, s, 1))], tail_us=0.0)
-        lat = co["latency_us"][args.warmup:]
+        lat = co["latency_us"][args.n_warm:]
         out["slices"][str(s)] = {
             "launches": nslices, "total_us": t[0],
             "per_slice_overhead_us": (t[0] - nat[0]) / nslices,
             "GBps": nbytes / t[0] / 1e3,
-            "hi_p50_us": pct(lat, 50), "hi_p99_us": pct(lat, 99),
-            "hi_p99_overhead_pct": (pct(lat, 99) - p99_solo) / p99_solo * 100.0,
+            "hi_p50_us": pct(lat, 50), "hi_p99_us": p99(lat),
+            "hi_p99_overhead_pct": ovh(p99(lat), p99_solo),
             "be_kernels_done": int(co["be_kernels_done"]),
             "preempt_p50_us": pct(co["preempt_latency_us"], 50),
         }
@@ -165,11 +179,11 @@ def cfg2(torch, B, ctx, be_stream, args):
         t = _time(torch, B, be_stream, lambda: ctx.launch_sliced(red, sl, max_in_flight=q), reps=5,
                   warm=1, wait_before_stop=True)
         co = ctx.sched_run([hi], arrivals, [(red, (B.CFG_SLICED, sl, q))], tail_us=0.0)
-        lat = co["latency_us"][args.warmup:]
+        lat = co["latency_us"][args.n_warm:]
         out.setdefault("slices_in_flight", {})[f"{sl}x{q}"] = {
             "total_us": t[0], "GBps": nbytes / t[0] / 1e3, "of_native": nat[0] / t[0],
-            "hi_p50_us": pct(lat, 50), "hi_p99_us": pct(lat, 99),
-            "hi_p99_overhead_pct": (pct(lat, 99) - p99_solo) / p99_solo * 100.0,
+            "hi_p50_us": pct(lat, 50), "hi_p99_us": p99(lat),
+            "hi_p99_overhead_pct": ovh(p99(lat), p99_solo),
             "be_kernels_done": int(co["be_kernels_done"]),
             "preempt_p50_us": pct(co["preempt_latency_us"], 50),
         }
@@ -177,15 +191,15 @@ def cfg2(torch, B, ctx, be_stream, args):
     for w, c in ((512, 32), (512, 8), (1024, 2)):
         t = _time(torch, B, be_stream, lambda: ctx.launch_ptb(red, w, chunk=c))
         co = ctx.sched_run([hi], arrivals, [(red, (B.CFG_PTB, w, c))], tail_us=0.0)
-        lat = co["latency_us"][args.warmup:]
+        lat = co["latency_us"][args.n_warm:]
         pre = co["preempt_latency_us"]
         out.setdefault("ptb", {})[f"W{w}_chunk{c}"] = {
             "total_us": t[0], "GBps": nbytes / t[0] / 1e3, "of_native": nat[0] / t[0],
             "eq1_turnaround_us": B.ptb_turnaround_ms(t[0] / 1e3, w, c, 65536) * 1e3,
-            "hi_p50_us": pct(lat, 50), "hi_p99_us": pct(lat, 99),
-            "hi_p99_overhead_pct": (pct(lat, 99) - p99_solo) / p99_solo * 100.0,
+            "hi_p50_us": pct(lat, 50), "hi_p99_us": p99(lat),
+            "hi_p99_overhead_pct": ovh(p99(lat), p99_solo),
             "n_preempts": int(co["n_preempts"]), "preempt_p50_us": pct(pre, 50),
-            "preempt_p99_us": pct(pre, 99), "be_kernels_done": int(co["be_kernels_done"]),
+            "preempt_p99_us": p99(pre), "be_kernels_done": int(co["be_kernels_done"]),
         }
     # (for a sliced candidate the third number is the count of slices enqueued at a time)
     cands = [(B.CFG_PTB, 512, 32), (B.CFG_PTB, 512, 8), (B.CFG_PTB, 1024, 2), (B.CFG_PTB, 256, 1),
@@ -334,17 +348,17 @@ def _colocate(torch, B, ctx, be_stream, args, hi, rate, cfg_index, label):
     info = B.device_info()
     step = _be_step(torch, B)
     table, items = _choose_configs(torch, B, ctx, be_stream, step, info["num_cus"])
-    count = args.steps
+    count = args.n_arrivals + args.n_warm
+    w = args.n_warm
     arrivals = TI.poisson_arrivals_us(rate, count, config_index=cfg_index)
     dur_us = float(arrivals[-1])
     solo_hi = ctx.sched_run(hi, arrivals, [])
     solo_be = ctx.sched_run([], [], items, tail_us=min(dur_us, 3e6))
     co = ctx.sched_run(hi, arrivals, items, policy=B.POLICY_TALLY)
     nat_items = [(k, (B.CFG_NATIVE, 1, 1)) for k, _ in items]
-    sub = arrivals[: max(count // 4, 100)]
+    sub = arrivals[: max(count // 2, MIN_P99_SAMPLES + min(w, 20))]
     nat = ctx.sched_run(hi, sub, nat_items, policy=B.POLICY_PRIORITY_NATIVE)
     nos = ctx.sched_run(hi, sub, nat_items, policy=B.POLICY_NONE)
-    w = args.warmup
     ls, lc = solo_hi["latency_us"][w:], co["latency_us"][w:]
     tput_solo = solo_be["be_kernels_done"] / solo_be["window_us"]
     tput_co = co["be_kernels_done"] / co["window_us"]
@@ -353,28 +367,28 @@ def _colocate(torch, B, ctx, be_stream, args, hi, rate, cfg_index, label):
     flops = sum(f for _, _, f, _ in step)
     return {
         "workload": label,
-        "hi_pri_latency_us": {"solo_p50": pct(ls, 50), "solo_p99": pct(ls, 99),
-                              "coloc_p50": pct(lc, 50), "coloc_p99": pct(lc, 99), "n": len(lc),
+        "hi_pri_latency_us": {"solo_p50": pct(ls, 50), "solo_p99": p99(ls),
+                              "coloc_p50": pct(lc, 50), "coloc_p99": p99(lc), "n": len(lc),
                               # host share: scheduled arrival -> launch calls returned (includes
                               # waiting behind the previous request); the rest is the device's
-                              "issue_solo_p99": pct(solo_hi["issue_us"][w:], 99),
-                              "issue_coloc_p99": pct(co["issue_us"][w:], 99),
+                              "issue_solo_p99": p99(solo_hi["issue_us"][w:]),
+                              "issue_coloc_p99": p99(co["issue_us"][w:]),
                               "after_launch_calls_solo_p99":
-                                  pct((solo_hi["latency_us"] - solo_hi["issue_us"])[w:], 99),
+                                  p99((solo_hi["latency_us"] - solo_hi["issue_us"])[w:]),
                               "after_launch_calls_coloc_p99":
-                                  pct((co["latency_us"] - co["issue_us"])[w:], 99)},
-        "p99_overhead_pct": (pct(lc, 99) - pct(ls, 99)) / pct(ls, 99) * 100.0,
+                                  p99((co["latency_us"] - co["issue_us"])[w:])},
+        "p99_overhead_pct": ovh(p99(lc), p99(ls)),
         "p50_overhead_pct": (pct(lc, 50) - pct(ls, 50)) / pct(ls, 50) * 100.0,
         "be_tput_retained_pct": tput_co / tput_solo * 100.0,
         "be_steps_per_s": {"solo": solo_be["be_steps_done"] / solo_be["window_us"] * 1e6,
                            "coloc": co["be_steps_done"] / co["window_us"] * 1e6},
         "be_step_TFLOPs_solo": flops * (solo_be["be_steps_done"] / solo_be["window_us"]) / 1e6,
-        "preempt_latency_us": {"n": int(co["n_preempts"]), "p50": pct(pre, 50), "p99": pct(pre, 99),
+        "preempt_latency_us": {"n": int(co["n_preempts"]), "p50": pct(pre, 50), "p99": p99(pre),
                                "histogram_edges_us": [0, 5, 10, 20, 40, 80, 160, 320, "inf"],
                                "histogram": [int(h) for h in hist]},
-        "decomposition_p99_us": {"ideal": pct(ls, 99), "full": pct(lc, 99),
-                                 "priority_native_be": pct(nat["latency_us"][min(w, 20):], 99),
-                                 "no_scheduling": pct(nos["latency_us"][min(w, 20):], 99)},
+        "decomposition_p99_us": {"ideal": p99(ls), "full": p99(lc),
+                                 "priority_native_be": p99(nat["latency_us"][min(w, 20):]),
+                                 "no_scheduling": p99(nos["latency_us"][min(w, 20):])},
         "be_kernels": table,
     }
 
@@ -401,11 +415,11 @@ def _coloc_stats(B, ctx, hi, arrivals, items, warm, solo_p99, tput_solo):
     lat = co["latency_us"][warm:]
     pre = co["preempt_latency_us"]
     return {
-        "hi_p50_us": pct(lat, 50), "hi_p99_us": pct(lat, 99),
-        "hi_p99_overhead_pct": (pct(lat, 99) - solo_p99) / solo_p99 * 100.0,
+        "hi_p50_us": pct(lat, 50), "hi_p99_us": p99(lat),
+        "hi_p99_overhead_pct": ovh(p99(lat), solo_p99),
         "be_tput_retained_pct": co["be_kernels_done"] / co["window_us"] / tput_solo * 100.0,
         "n_preempts": int(co["n_preempts"]), "preempt_p50_us": pct(pre, 50),
-        "preempt_p99_us": pct(pre, 99),
+        "preempt_p99_us": p99(pre),
     }
 
 
@@ -424,10 +438,10 @@ def sweep_threshold(torch, B, ctx, be_stream, args):
     torch.cuda.synchronize()
     red = B.reduce_sum(x, partial)
     hi = [B.saxpy(sx, sy, 1.5)]
-    arrivals = TI.poisson_arrivals_us(500.0, args.steps, config_index=2)
-    w = args.warmup
+    arrivals = TI.poisson_arrivals_us(500.0, args.n_arrivals + args.n_warm, config_index=2)
+    w = args.n_warm
     solo = ctx.sched_run(hi, arrivals, [])
-    solo_p99 = pct(solo["latency_us"][w:], 99)
+    solo_p99 = p99(solo["latency_us"][w:])
     cands = [(B.CFG_SLICED, 4096, 1), (B.CFG_SLICED, 512, 1), (B.CFG_SLICED, 64, 1),
              (B.CFG_PTB, 256, 1), (B.CFG_PTB, 1024, 1), (B.CFG_PTB, 2048, 1),
              (B.CFG_PTB, 1024, 2), (B.CFG_PTB, 512, 8), (B.CFG_PTB, 2048, 4),
@@ -454,10 +468,10 @@ def sweep_threshold(torch, B, ctx, be_stream, args):
     cu = info["num_cus"]
     step = _be_step(torch, B)
     hi_b = _hi_layer(torch, B)
-    arr_b = TI.poisson_arrivals_us(100.0, max(args.steps // 5, 200), config_index=3)
-    wb = min(w, 20)
+    arr_b = TI.poisson_arrivals_us(100.0, args.n_arrivals + args.n_warm, config_index=3)
+    wb = w
     solo_b = ctx.sched_run(hi_b, arr_b, [])
-    solo_b_p99 = pct(solo_b["latency_us"][wb:], 99)
+    solo_b_p99 = p99(solo_b["latency_us"][wb:])
     tables = []
     for name, k, flops, nbytes in step:
         if k.kernel_id in (B.K_GEMM_BF16, B.K_GEMM_BF16_N128):
@@ -513,26 +527,26 @@ def sweep_load(torch, B, ctx, be_stream, args):
     svc_us = pct(probe["latency_us"][50:], 50)
     be_solo = ctx.sched_run([], [], items, tail_us=1e6)
     tput_solo = be_solo["be_kernels_done"] / be_solo["window_us"]
-    n = args.steps
-    w = args.warmup
+    n = args.n_arrivals + args.n_warm
+    w = args.n_warm
     rows = {}
     for duty in (0.1, 0.3, 0.5, 0.7, 0.9):
         rate = duty / (svc_us * 1e-6)
         arr = TI.poisson_arrivals_us(rate, n, config_index=1)
         solo = ctx.sched_run(hi, arr, [])
-        sp99 = pct(solo["latency_us"][w:], 99)
+        sp99 = p99(solo["latency_us"][w:])
         row = _coloc_stats(B, ctx, hi, arr, items, w, sp99, tput_solo)
         row.update({"arrivals_per_s": rate, "hi_solo_p50_us": pct(solo["latency_us"][w:], 50),
                     "hi_solo_p99_us": sp99})
-        nat = ctx.sched_run(hi, arr[: max(n // 4, 200)], [(gemm, (B.CFG_NATIVE, 1, 1))],
+        nat = ctx.sched_run(hi, arr[: max(n // 2, MIN_P99_SAMPLES + min(w, 20))], [(gemm, (B.CFG_NATIVE, 1, 1))],
                             policy=B.POLICY_NONE)
-        row["no_scheduling_p99_us"] = pct(nat["latency_us"][min(w, 20):], 99)
+        row["no_scheduling_p99_us"] = p99(nat["latency_us"][min(w, 20):])
         rows["%d%%" % round(duty * 100)] = row
     rate = 0.3 / (svc_us * 1e-6)
     arr = TI.bursty_arrivals_us(rate, 2 * n, config_index=1, burst=10.0, p_on=0.05,
                                 mean_segment_us=2000.0)
     solo = ctx.sched_run(hi, arr, [])
-    sp99 = pct(solo["latency_us"][w:], 99)
+    sp99 = p99(solo["latency_us"][w:])
     bursty = _coloc_stats(B, ctx, hi, arr, items, w, sp99, tput_solo)
     bursty.update({"mean_arrivals_per_s": len(arr) / (arr[-1] * 1e-6), "hi_solo_p99_us": sp99,
                    "hi_solo_p50_us": pct(solo["latency_us"][w:], 50)})
@@ -574,27 +588,27 @@ def multi_be(torch, B, ctx, be_stream, args):
         ("softmax_65536x2048", B.softmax_f32(sx, so), (B.CFG_PTB, 2 * cu, 4)),
         ("gemm_b", B.gemm_bf16(A, Bt, C1), (B.CFG_PTB, cu, 1)),
     ]
-    arrivals = TI.periodic_arrivals_us(1000.0, args.steps + args.warmup)
-    w = args.warmup
+    arrivals = TI.periodic_arrivals_us(1000.0, args.n_arrivals + args.n_warm)
+    w = args.n_warm
     alone = {}
     for name, k, cfg in clients:
         r = ctx.sched_run([], [], [(k, cfg)], tail_us=0.5e6)
         alone[name] = r["be_kernels_done"] / r["window_us"] * 1e6
     solo = ctx.sched_run(hi, arrivals, [])
-    solo_p50, solo_p99 = pct(solo["latency_us"][w:], 50), pct(solo["latency_us"][w:], 99)
+    solo_p50, solo_p99 = pct(solo["latency_us"][w:], 50), p99(solo["latency_us"][w:])
     rows = {}
     for n in (1, 2, 3, 4):
         items = [(k, cfg) for _, k, cfg in clients[:n]]
         co = ctx.sched_run(hi, arrivals, items, policy=B.POLICY_TALLY, be_clients=[1] * n)
-        nos = ctx.sched_run(hi, arrivals[: w + max(args.steps // 4, 200)],
+        nos = ctx.sched_run(hi, arrivals[: w + max(args.n_arrivals // 2, MIN_P99_SAMPLES)],
                             [(k, (B.CFG_NATIVE, 1, 1)) for _, k, _ in clients[:n]],
                             policy=B.POLICY_NONE, be_clients=[1] * n)
         lat = co["latency_us"][w:]
         per = co["be_client_kernels_done"] / co["window_us"] * 1e6
         rows[str(n)] = {
-            "hi_p50_us": pct(lat, 50), "hi_p99_us": pct(lat, 99),
-            "hi_p99_overhead_pct": (pct(lat, 99) - solo_p99) / solo_p99 * 100.0,
-            "no_scheduling_p99_us": pct(nos["latency_us"][w:], 99),
+            "hi_p50_us": pct(lat, 50), "hi_p99_us": p99(lat),
+            "hi_p99_overhead_pct": ovh(p99(lat), solo_p99),
+            "no_scheduling_p99_us": p99(nos["latency_us"][w:]),
             "n_preempts": int(co["n_preempts"]),
             "preempt_p50_us": pct(co["preempt_latency_us"], 50),
             "client_kernels_per_s": {clients[i][0]: float(per[i]) for i in range(n)},

@@ -12,28 +12,21 @@ import os
 
 import numpy as np
 
-# Several best-effort clients need two hardware queues each (see tally_sched_run: 2 + 2n
-# for n clients, n <= 8); HIP folds the process's streams onto GPU_MAX_HW_QUEUES hardware
-# queues (default 4) and reads the variable when it initialises, so raising it only helps
-# if this module is imported before the first GPU call of the process.  A larger value
-# already in the environment is kept.
-try:
-    _hwq = int(os.environ.get("GPU_MAX_HW_QUEUES", "4"))
-except ValueError:
-    _hwq = 4
-def _gpu_already_initialised():
-    import sys
-    t = sys.modules.get("torch")
+# Hardware queues.  HIP folds a process's streams onto GPU_MAX_HW_QUEUES hardware queues
+# (4 unless the environment says otherwise) and reads the variable when it initialises;
+# streams that share a queue run in order.  The scheduler needs one queue each for the
+# high-priority stream, the best-effort stream and the relay stream beside the null
+# stream's, and two more per further best-effort client (2 + 2n for n clients).  This
+# module does not touch the environment: a program that wants several clients sets the
+# variable itself before its first GPU call, and the library refuses a run whose clients
+# would not get queues of their own.
+def hw_queues():
+    """The number of hardware queues this process asked HIP for (its default is 4)."""
     try:
-        return bool(t is not None and t.cuda.is_initialized())
-    except Exception:
-        return False
+        return int(os.environ.get("GPU_MAX_HW_QUEUES", "4"))
+    except ValueError:
+        return 4
 
-
-# (if the GPU runtime is up already the variable is left alone, so that a run with several
-# clients is refused rather than silently folded onto too few queues)
-if _hwq < 20 and not _gpu_already_initialised():
-    os.environ["GPU_MAX_HW_QUEUES"] = "20"
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libtally.so")

@@ -1305,7 +1305,7 @@ extern "C" int tally_sched_run(tally_ctx *ctx, tally_sched_run_t *run) {
   // the high-priority stream's.  HIP folds streams onto GPU_MAX_HW_QUEUES hardware queues
   // (4 unless the environment says otherwise), and streams that share one run in order:
   // a high-priority kernel behind a relay would wait for a whole best-effort kernel.
-  if (n_clients > 1) {
+  if (n_clients >= 1) {
     const char *env = getenv("GPU_MAX_HW_QUEUES");
     const long have = env ? strtol(env, nullptr, 10) : 4;
     if (have < (long)(2 + 2 * n_clients)) return TALLY_ERR_UNSUPPORTED;
