@@ -180,9 +180,14 @@ def main():
     # The scheduler needs a hardware queue each for the high-priority stream, the best-effort
     # stream and the relay stream (two more per further best-effort client) beside the null
     # stream's; HIP folds a process's streams onto GPU_MAX_HW_QUEUES queues (4 unless set) and
-    # reads the variable when it initialises.  This program asks for 20 unless the caller set
-    # something else, and every JSON line records the value in effect.
-    os.environ.setdefault("GPU_MAX_HW_QUEUES", str(HW_QUEUES))
+    # reads the variable when it initialises.  This program raises a smaller (or absent) value
+    # to 20, keeps a larger one, and every JSON line records the value in effect.
+    try:
+        have = int(os.environ.get("GPU_MAX_HW_QUEUES", "4"))
+    except ValueError:
+        have = 4
+    if have < HW_QUEUES:
+        os.environ["GPU_MAX_HW_QUEUES"] = str(HW_QUEUES)
     hwq = os.environ["GPU_MAX_HW_QUEUES"]
 
     import torch

@@ -151,6 +151,21 @@ size_t tally_attn_decode_scratch_bytes(uint32_t heads);
  * kernels are launched with the default configuration).  Asynchronous. */
 int tally_launch_native(tally_ctx *ctx, const tally_kernel_desc *desc, int on_hi_stream);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc): the decode-attention launch of
+ * tally_launch_native with its split records kept in a device array that is part of the
+ * library instead of caller-provided scratch.  args->scratch is ignored (may be NULL);
+ * everything else is as for TALLY_K_ATTN_DECODE_BF16.  The call allocates nothing and calls
+ * no allocating routine.  Limit: heads <= TALLY_ATTN_STATIC_MAX_HEADS (the array takes
+ * about 1 MiB on every GPU the library runs on, until the process ends);
+ * TALLY_ERR_INVALID_ARG beyond it, TALLY_ERR_BAD_STATE if the current device is not the
+ * context's.  Nothing in the array has to start at zero (every record is written before it
+ * is read).  All calls on one GPU share the array: two calls whose kernels overlap in time
+ * (e.g. one per stream) race; calls on one stream are ordered by the stream. */
+#define TALLY_ATTN_STATIC_MAX_HEADS 128
+int tally_launch_attn_decode_static(tally_ctx *ctx, const tally_attn_decode_args *args,
+                                    int on_hi_stream);
+
 /* Sliced form (Section 4.1, slicing transformation): the grid is cut into sub-kernels
  * of slice_blocks consecutive logical blocks (last one: the remainder); each sub-kernel
  * receives a block offset and rebuilds its logical block index as offset + blockIdx.

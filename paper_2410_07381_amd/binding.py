@@ -48,6 +48,7 @@ EXPORTS = [
     "tally_marker_read", "tally_last_preempt_latency_us", "tally_last_hip_error",
     "tally_strerror", "tally_max_workers", "tally_kernel_footprint", "tally_mfma_ceiling_tflops", "tally_device_info", "tally_ptb_turnaround_ms", "tally_select_config",
     "tally_profile", "tally_lookup_config", "tally_sched_run", "tally_set_yield_bound_us",
+    "tally_launch_attn_decode_static",
 ]
 
 
@@ -153,6 +154,7 @@ def _load():
         "tally_logical_grid": ([u32, vp, C.c_size_t, P(Dim3), P(Dim3)], i32),
         "tally_attn_decode_scratch_bytes": ([u32], C.c_size_t),
         "tally_launch_native": ([vp, P(KernelDesc), i32], i32),
+        "tally_launch_attn_decode_static": ([vp, P(AttnDecodeArgs), i32], i32),
         "tally_launch_sliced": ([vp, P(KernelDesc), u32, u32, i32, P(vp)], i32),
         "tally_launch_ptb": ([vp, P(KernelDesc), u32, u32, i32, P(vp)], i32),
         "tally_preempt": ([vp], i32),
@@ -358,6 +360,14 @@ class Context:
     def launch_native(self, kernel, hi=False):
         _check(_lib.tally_launch_native(self.h, C.byref(kernel.desc), 1 if hi else 0),
                "tally_launch_native")
+
+    def launch_attn_decode_static(self, q, Kc, Vc, out, hi=False):
+        """Decode attention with the library's own static split records (allocates nothing)."""
+        tokens, heads, dim = Kc.shape
+        args = AttnDecodeArgs(q.data_ptr(), Kc.data_ptr(), Vc.data_ptr(), out.data_ptr(), None,
+                              tokens, heads, dim)
+        _check(_lib.tally_launch_attn_decode_static(self.h, C.byref(args), 1 if hi else 0),
+               "tally_launch_attn_decode_static")
 
     def launch_sliced(self, kernel, slice_blocks, max_in_flight=1, coverage=False):
         j = C.c_void_p()

@@ -287,7 +287,19 @@ constexpr size_t kCopySlotBytes = kFlagCopies * kFlagCopyStride * sizeof(uint32_
 
 enum JobKind { KIND_PTB = 0, KIND_SLICED = 1, KIND_NATIVE = 2 };
 
+constexpr uint32_t kStaticAttnMaxHeads = TALLY_ATTN_STATIC_MAX_HEADS;
+constexpr size_t kStaticAttnBytes =
+    (size_t)kStaticAttnMaxHeads * kAttnSplits * kAttnRec * sizeof(float);
+
 }  // namespace
+
+// Split records of the decode-attention kernels for callers that may not allocate: device
+// memory that belongs to the library's code object, one copy per GPU, held until the
+// process ends.  In host code this name is only a handle for hipGetSymbolAddress; the
+// address kernels receive is the one that call returns, kept per context.  (File scope,
+// not an unnamed namespace: there the device symbol stays local to the code object and the
+// runtime cannot look it up.)
+static __device__ __align__(256) unsigned char static_scratch[kStaticAttnBytes];
 
 struct tally_ctx {
   hipStream_t hi, be;
@@ -313,6 +325,7 @@ struct tally_ctx {
   // [0] persistent-worker form, [1] original form; asked of the runtime once, at creation
   uint32_t foot[TALLY_K_COUNT][2][3];
   uint32_t yield_ticks;      // bound of a mid-block pause, 10 ns ticks
+  void *static_attn_scratch; // this device's address of static_scratch
   int device;
   int live_jobs;
   std::map<std::tuple<uint32_t, uint32_t, uint32_t, uint32_t, uint32_t>, tally_config> chosen;
@@ -572,6 +585,7 @@ int tally_create(tally_ctx **out, void *hip_stream_hi, void *hip_stream_be) {
   c->copy_pool = nullptr;
   c->host_pool = nullptr;
   c->marker_host = nullptr;
+  c->static_attn_scratch = nullptr;
   memset(c->slot_used, 0, sizeof(c->slot_used));
   memset(c->slot_counter, 0, sizeof(c->slot_counter));
   memset(c->slot_exited, 0, sizeof(c->slot_exited));
@@ -589,6 +603,7 @@ int tally_create(tally_ctx **out, void *hip_stream_hi, void *hip_stream_be) {
       (e = hipMemset(c->copy_pool, 0, kSlots * kCopySlotBytes)) != hipSuccess ||
       (e = hipHostMalloc((void **)&c->host_pool, kSlots * kHostSlotBytes, hipHostMallocDefault)) != hipSuccess ||
       (e = hipHostGetDevicePointer((void **)&c->host_pool_dev, c->host_pool, 0)) != hipSuccess ||
+      (e = hipGetSymbolAddress(&c->static_attn_scratch, HIP_SYMBOL(static_scratch))) != hipSuccess ||
       (e = hipHostMalloc((void **)&c->marker_host, 256, hipHostMallocDefault)) != hipSuccess ||
       (e = hipHostGetDevicePointer((void **)&c->marker_dev, c->marker_host, 0)) != hipSuccess) {
     g_last_hip = (int)e;
@@ -683,6 +698,22 @@ int tally_launch_native(tally_ctx *ctx, const tally_kernel_desc *desc, int on_hi
   int rc = check_desc(desc, &ops, &g);
   if (rc) return rc;
   HIPCHK(ops->native(on_hi_stream ? ctx->hi : ctx->be, desc->args, g, on_hi_stream ? 1u : 0u));
+  return TALLY_OK;
+}
+
+int tally_launch_attn_decode_static(tally_ctx *ctx, const tally_attn_decode_args *args,
+                                    int on_hi_stream) {
+  if (!ctx || !args) return TALLY_ERR_INVALID_ARG;
+  if (args->heads > kStaticAttnMaxHeads) return TALLY_ERR_INVALID_ARG;
+  tally_attn_decode_args a = *args;
+  a.scratch = ctx->static_attn_scratch;  // the address obtained at tally_create, never the symbol
+  tally_dim3 g, b;
+  int rc = grid_attn(&a, &g, &b);
+  if (rc) return rc;
+  int dev = -1;
+  HIPCHK(hipGetDevice(&dev));
+  if (dev != ctx->device) return TALLY_ERR_BAD_STATE;  // each GPU has its own copy of the array
+  HIPCHK(launch_attn_decode(on_hi_stream ? ctx->hi : ctx->be, &a, g, on_hi_stream ? 1u : 0u));
   return TALLY_OK;
 }
 

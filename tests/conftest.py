@@ -10,7 +10,13 @@ if ROOT not in sys.path:
 
 # The tests with several best-effort clients need 2 + 2n hardware queues; HIP reads the
 # variable when it initialises, so it is set here, before any test imports torch.
-os.environ.setdefault("GPU_MAX_HW_QUEUES", "20")
+# (an inherited smaller value, such as a machine-wide default of 4, is raised)
+try:
+    _have = int(os.environ.get("GPU_MAX_HW_QUEUES", "4"))
+except ValueError:
+    _have = 4
+if _have < 20:
+    os.environ["GPU_MAX_HW_QUEUES"] = "20"
 
 
 def pytest_configure(config):

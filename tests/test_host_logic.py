@@ -103,3 +103,25 @@ def test_header_is_plain_c():
     import paper_2410_07381_amd.binding as B
     assert [int(v) for v in out] == [C.sizeof(B.GemmArgs), C.sizeof(B.KernelDesc), C.sizeof(B.CoverRec),
                                      C.sizeof(B.Config), C.sizeof(B.SchedRun)]
+
+
+def test_static_scratch_is_a_global_symbol_of_the_device_code(B, tmp_path):
+    """The runtime finds a device variable by name among the code object's global symbols.
+    A file-scope static device array referenced from host code is given global binding by
+    the compiler; attributes that keep it local (an unnamed namespace, `used`) make the
+    lookup at context creation fail.  Checked on the built library, no GPU needed."""
+    import shutil
+    import subprocess
+    llvm = "/opt/rocm/llvm/bin"
+    tools = [os.path.join(llvm, t) for t in ("llvm-objcopy", "clang-offload-bundler", "llvm-readelf")]
+    if not all(os.path.exists(t) for t in tools):
+        pytest.skip("LLVM binary tools not installed")
+    fat, co = str(tmp_path / "fat.bin"), str(tmp_path / "dev.co")
+    subprocess.run([tools[0], "-O", "binary", "--only-section=.hip_fatbin", B.LIB_PATH, fat], check=True)
+    subprocess.run([tools[1], "--unbundle", "--type=o", f"--input={fat}",
+                    "--targets=hipv4-amdgcn-amd-amdhsa--gfx950", f"--output={co}"], check=True)
+    syms = subprocess.run([tools[2], "-s", co], check=True, capture_output=True, text=True).stdout
+    rows = [l.split() for l in syms.splitlines() if "static_scratch" in l]
+    assert rows, "the static scratch array is missing from the device code"
+    assert all(r[4] == "GLOBAL" and r[3] == "OBJECT" for r in rows), rows
+    assert int(rows[0][2]) == 128 * 16 * 130 * 4
