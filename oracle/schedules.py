@@ -139,6 +139,11 @@ class PtbMachine:
         m.progress_log = list(self.progress_log)
         return m
 
+    def key(self):
+        """Everything the future of the machine depends on (for exhaustive search)."""
+        return (self.counter, self.flag, tuple(self.state), tuple(self.held), tuple(self.held_end),
+                self.segment)
+
     # -- queries ------------------------------------------------------------------------
     def live(self):
         return [w for w in range(self.W) if self.state[w] != EXITED]
@@ -206,11 +211,138 @@ class PtbMachine:
         return True
 
 
-def run_ptb(name, grid, args, workers, preempt_points=(), seed=0, chunk=1):
+WORD = 1 << 32            # the shared word is 32 bits wide and wraps
+PREEMPT_STEP = 1 << 31    # what a preemption request adds to it
+
+
+class FoldedPtbMachine(PtbMachine):
+    """The same worker loop with the flag folded into the counter: ONE shared 32-bit word.
+
+    The paper keeps two variables, a task counter and a boolean flag, and a worker reads the
+    flag, then fetches and increments the counter.  Here a worker does one fetch-and-add on
+    one word and compares what it got with the end of the grid; a preemption request is
+    itself a fetch-and-add, of 2^31, on that word, after which every fetch returns an index
+    beyond any grid and the worker leaves exactly as it would on seeing the flag.  What the
+    request's own fetch-and-add returned is the number of indices handed out before it:
+    the progress.  Fetches that fail after the request still add to the word, so the word no
+    longer shows the progress; instead of resetting it, the host moves its `base` (the value
+    of the word that stands for task index 0) so that the next index handed out is again
+    `progress`.  The word is never reset and wraps modulo 2^32; indices are differences
+    modulo 2^32, so the grid must be smaller than 2^31 blocks.
+
+    `single_pass`: when the workers' first fetches alone cover every index left
+    (chunk x workers >= blocks left at the start of the segment), a worker that has run what
+    it fetched leaves without a second, necessarily failing, fetch.
+
+    `variant` selects deliberately wrong forms, kept as negative controls for the
+    exhaustive checker: "stale_base" resumes without moving the base, "counter_progress"
+    reads the progress off the word after a request.
+    """
+
+    def __init__(self, total, workers, on_exec=None, chunk=1, word0=0, variant="right",
+                 single_pass=True):
+        super().__init__(total, workers, on_exec=on_exec, chunk=chunk)
+        if self.total >= PREEMPT_STEP:
+            raise ValueError("grid too large for a 32-bit word with a folded request")
+        self.word = int(word0) % WORD
+        self.base = self.word
+        self.variant = variant
+        self.allow_single = bool(single_pass)
+        self.flag_progress = None
+        self._open_segment(0)
+
+    def _open_segment(self, start):
+        self.seg_start = start
+        self.single = self.allow_single and self.chunk * self.W >= self.total - start
+
+    def clone(self, on_exec=None):
+        m = FoldedPtbMachine.__new__(FoldedPtbMachine)
+        m.__dict__.update(self.__dict__)
+        m.held_end, m.state, m.held = list(self.held_end), list(self.state), list(self.held)
+        m.progress_log = list(self.progress_log)
+        m.on_exec = on_exec
+        return m
+
+    def key(self):
+        return (self.word, self.base, self.flag, self.flag_progress, tuple(self.state),
+                tuple(self.held), tuple(self.held_end), self.segment, self.single)
+
+    @property
+    def counter(self):
+        """Task indices handed out, as the paper's counter would show them (for callers
+        that watch the counter to decide when to raise the request)."""
+        if self.flag:
+            return self.flag_progress_raw
+        return (self.word - self.base) % WORD
+
+    @counter.setter
+    def counter(self, v):      # the base class initialises the attribute; the word is the state
+        pass
+
+    def progress(self):
+        if self.flag and self.variant != "counter_progress":
+            return self.flag_progress
+        return min((self.word - self.base) % WORD, self.total)
+
+    def raise_flag(self):
+        if self.flag:
+            return
+        old = self.word
+        self.word = (self.word + PREEMPT_STEP) % WORD
+        self.flag = True
+        self.flag_progress_raw = (old - self.base) % WORD
+        self.flag_progress = min(self.flag_progress_raw, self.total)
+
+    def step(self, w):
+        s = self.state[w]
+        if s == EXITED:
+            raise RuntimeError("stepping an exited worker")
+        if s == CHECK:
+            old = self.word
+            self.word = (self.word + self.chunk) % WORD
+            idx = (old - self.base) % WORD
+            if idx >= self.total:              # grid exhausted, or a request folded in
+                self.state[w] = EXITED
+                return
+            self.state[w], self.held[w] = FETCHED, idx
+            self.held_end[w] = min(idx + self.chunk, self.total)
+        else:
+            idx = self.held[w]
+            if self.on_exec is not None:
+                self.on_exec(idx, self.segment, w)
+            if idx + 1 < self.held_end[w]:
+                self.held[w] = idx + 1
+            elif self.single:
+                self.state[w], self.held[w], self.held_end[w] = EXITED, -1, -1
+            else:
+                self.state[w], self.held[w], self.held_end[w] = CHECK, -1, -1
+
+    def resume(self):
+        if not self.drained():
+            raise RuntimeError("resume before drain")
+        p = self.progress()
+        self.progress_log.append(p)
+        if p >= self.total:
+            return False
+        if self.variant != "stale_base":
+            self.base = (self.word - p) % WORD   # the next index handed out is p again
+        self.flag = False
+        self.flag_progress = None
+        self.segment += 1
+        self.state = [CHECK] * self.W
+        self.held = [-1] * self.W
+        self.held_end = [-1] * self.W
+        self._open_segment(p)
+        return True
+
+
+def run_ptb(name, grid, args, workers, preempt_points=(), seed=0, chunk=1, machine="folded",
+            word0=0):
     """Run a kernel as `workers` persistent workers under a seeded random
-    interleaving.  The flag is raised when the counter first reaches (or, with
-    chunk > 1, first passes) each value in `preempt_points` (ascending); after every
-    drain the kernel is resumed.
+    interleaving, on the one-word machine the GPU path uses (machine="folded") or on the
+    paper's two-variable one (machine="paper"); both give the same coverage and progress.
+    The flag is raised when the counter first reaches (or, with chunk > 1, first passes)
+    each value in `preempt_points` (ascending); after every drain the kernel is resumed.
     Returns (coverage, progress value observed at each drain)."""
     total = G.total_blocks(grid)
     cov = Coverage(grid)
@@ -218,7 +350,10 @@ def run_ptb(name, grid, args, workers, preempt_points=(), seed=0, chunk=1):
     def on_exec(idx, segment, w):
         _run_block(name, idx, grid, args, cov, segment)
 
-    m = PtbMachine(total, workers, on_exec=on_exec, chunk=chunk)
+    if machine == "folded":
+        m = FoldedPtbMachine(total, workers, on_exec=on_exec, chunk=chunk, word0=word0)
+    else:
+        m = PtbMachine(total, workers, on_exec=on_exec, chunk=chunk)
     rng = np.random.Generator(np.random.PCG64(seed))
     pts = sorted(int(p) for p in preempt_points)
     nxt = 0

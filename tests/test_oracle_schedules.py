@@ -77,18 +77,17 @@ def test_slice_remainder_and_resume_offsets():
 
 
 # ------------------------------------------------------------------ brute force
-def _explore(total, workers, order, max_preempts, chunk=1):
+def _explore(make, max_preempts):
     """Walk EVERY interleaving of worker micro-steps and EVERY moment at which the flag
-    may be raised (up to max_preempts times).  Returns a dict of findings."""
+    may be raised (up to max_preempts times) of the machine `make()` builds.  Returns a
+    dict of findings."""
     found = {"lost": False, "dup": False, "prefix_broken": False, "finals": 0, "max_depth": 0}
     seen = set()
-
-    def key(m, counts, used):
-        return (m.counter, m.flag, tuple(m.state), tuple(m.held), tuple(m.held_end), counts, used,
-                m.segment)
+    m0 = make()
+    total = m0.total
 
     def rec(m, counts, used, depth):
-        k = key(m, counts, used)
+        k = (m.key(), counts, used)
         if k in seen:
             return
         seen.add(k)
@@ -125,25 +124,39 @@ def _explore(total, workers, order, max_preempts, chunk=1):
             m2.on_exec = None
             rec(m2, c2, used, depth + 1)
 
-    rec(S.PtbMachine(total, workers, order=order, chunk=chunk), (0,) * total, 0, 0)
+    rec(m0, (0,) * total, 0, 0)
     found["states"] = len(seen)
     return found
 
 
+def _paper(total, workers, order="check_then_fetch", chunk=1):
+    return lambda: S.PtbMachine(total, workers, order=order, chunk=chunk)
+
+
+def _folded(total, workers, chunk=1, **kw):
+    return lambda: S.FoldedPtbMachine(total, workers, chunk=chunk, **kw)
+
+
 @pytest.mark.parametrize("total,workers", [(1, 1), (2, 3), (4, 2), (5, 3), (6, 2), (6, 3)])
 def test_exactly_once_under_every_interleaving_and_preemption_point(total, workers):
-    f = _explore(total, workers, "check_then_fetch", max_preempts=2)
-    assert f["finals"] > 0
-    assert not f["lost"] and not f["dup"] and not f["prefix_broken"]
+    for make in (_paper(total, workers), _folded(total, workers),
+                 _folded(total, workers, single_pass=False),
+                 _folded(total, workers, word0=(1 << 32) - 2)):     # the word wraps mid-run
+        f = _explore(make, max_preempts=2)
+        assert f["finals"] > 0
+        assert not f["lost"] and not f["dup"] and not f["prefix_broken"]
 
 
 @pytest.mark.parametrize("total,workers,chunk", [(5, 2, 2), (6, 3, 2), (7, 2, 3), (3, 2, 4)])
 def test_exactly_once_with_chunked_fetch(total, workers, chunk):
     # taking several consecutive task indices per fetch keeps exactly-once and the prefix
     # property as long as every fetched index is run before the worker leaves
-    f = _explore(total, workers, "check_then_fetch", max_preempts=2, chunk=chunk)
-    assert f["finals"] > 0
-    assert not f["lost"] and not f["dup"] and not f["prefix_broken"]
+    for make in (_paper(total, workers, chunk=chunk), _folded(total, workers, chunk=chunk),
+                 _folded(total, workers, chunk=chunk, single_pass=False),
+                 _folded(total, workers, chunk=chunk, word0=(1 << 32) - 3)):
+        f = _explore(make, max_preempts=2)
+        assert f["finals"] > 0
+        assert not f["lost"] and not f["dup"] and not f["prefix_broken"]
 
 
 def test_chunked_fetch_drains_on_a_chunk_boundary():
@@ -155,9 +168,79 @@ def test_chunked_fetch_drains_on_a_chunk_boundary():
 
 
 def test_brute_force_detects_the_wrong_order():
-    f = _explore(4, 2, "fetch_then_check", max_preempts=1)
+    f = _explore(_paper(4, 2, order="fetch_then_check"), max_preempts=1)
     assert f["lost"], "fetch-before-check must lose a block on some interleaving"
     assert f["prefix_broken"]
+
+
+def test_brute_force_detects_wrong_one_word_forms():
+    # resuming without moving the base: the fetches that failed after the request have
+    # advanced the word, so indices are skipped
+    f = _explore(_folded(4, 2, variant="stale_base"), max_preempts=1)
+    assert f["lost"]
+    # reading the progress off the word after a request counts those failed fetches as work
+    f = _explore(_folded(4, 2, variant="counter_progress"), max_preempts=1)
+    assert f["prefix_broken"] or f["lost"]
+
+
+@pytest.mark.parametrize("total,workers,chunk", [(5, 2, 1), (6, 3, 2), (7, 2, 3), (4, 3, 1)])
+def test_one_word_machine_is_the_papers_machine_step_for_step(total, workers, chunk):
+    """Driven by the same sequence of worker steps and flag raises, the one-word machine
+    and the paper's counter-plus-flag machine run the same blocks in the same segments and
+    report the same progress at every drain (every schedule, by exhaustive walk)."""
+    seen = set()
+
+    def rec(a, b, used, depth):
+        k = (a.key(), b.key(), used)
+        if k in seen:
+            return
+        seen.add(k)
+        assert depth < 200
+        assert a.live() == b.live() and a.flag == b.flag
+        live = a.live()
+        if not live:
+            assert a.progress() == b.progress()
+            a2, b2 = a.clone(), b.clone()
+            ra, rb = a2.resume(), b2.resume()
+            assert ra == rb and a2.progress_log == b2.progress_log
+            if ra:
+                rec(a2, b2, used, depth + 1)
+            return
+        if not a.flag and used < 2:
+            a2, b2 = a.clone(), b.clone()
+            a2.raise_flag()
+            b2.raise_flag()
+            rec(a2, b2, used + 1, depth + 1)
+        for w in live:
+            xa, xb = [], []
+            a2 = a.clone(on_exec=lambda i, s_, ww: xa.append((i, s_, ww)))
+            b2 = b.clone(on_exec=lambda i, s_, ww: xb.append((i, s_, ww)))
+            a2.step(w)
+            b2.step(w)
+            assert xa == xb
+            rec(a2, b2, used, depth + 1)
+
+    # (without the single-pass shortcut the two machines have the same states throughout)
+    rec(S.PtbMachine(total, workers, chunk=chunk),
+        S.FoldedPtbMachine(total, workers, chunk=chunk, single_pass=False, word0=(1 << 32) - 1),
+        0, 0)
+    assert len(seen) > 50
+
+
+def test_single_pass_leaves_without_a_second_fetch():
+    m = S.FoldedPtbMachine(8, 4, chunk=2)              # 4 workers x 2 cover all 8 blocks
+    assert m.single
+    ran = []
+    m.on_exec = lambda i, s_, w: ran.append(i)
+    for w in range(4):
+        m.step(w)                                      # one fetch each
+    for _ in range(2):
+        for w in range(4):
+            m.step(w)
+    assert m.drained() and sorted(ran) == list(range(8))
+    assert (m.word - m.base) % S.WORD == 8             # no failing fetch was made
+    m = S.FoldedPtbMachine(9, 4, chunk=2)              # one block too many for a single pass
+    assert not m.single
 
 
 # ------------------------------------------------------------------ seeded runs
