@@ -310,85 +310,97 @@ def _hi_decode(torch, B):
             B.gemv_bf16(xd, Wdn, ydn)]
 
 
-def _choose_configs(torch, B, ctx, be_stream, step, num_cus):
-    """Per kernel: native time, a few persistent-worker candidates, Eq.-1 selection."""
+def _profile_step(torch, B, ctx, be_stream, step, threshold_ms, runs=3):
+    """Per kernel of the step: native time, then the library's whole Section 4.2 candidate
+    set measured by the profiler (every candidate really runs the kernel), and the choice
+    under the threshold.  Returns (table for the report, items that leave the choice to the
+    scheduler's lookup of these measurements)."""
     table, items = {}, []
     for name, k, flops, nbytes in step:
         nat = _time(torch, B, be_stream, lambda: (ctx.launch_native(k), None)[1], reps=3, warm=1)
-        tot = k.total_blocks
-        if "gemm" in name and k.kernel_id in (B.K_GEMM_BF16, B.K_GEMM_BF16_N128):
-            cands = [(B.CFG_PTB, num_cus, 1)]
-        elif "gemm" in name:
-            cands = [(B.CFG_PTB, 4 * num_cus, 1), (B.CFG_PTB, 4 * num_cus, 4)]
-        else:
-            cands = [(B.CFG_PTB, 2 * num_cus, 4), (B.CFG_PTB, 4 * num_cus, 2),
-                     (B.CFG_PTB, 2 * num_cus, 16)]
-        meas, chosen = ctx.profile(k, _cap(B, ctx, k, cands), runs=3, threshold_ms=0.0316)
+        cands = ctx.candidate_configs(k)
+        meas, chosen = ctx.profile(k, cands, runs=runs, threshold_ms=threshold_ms)
         c = meas[chosen]
-        ptb = _time(torch, B, be_stream, lambda: ctx.launch_ptb(k, c["param"], chunk=c["chunk"]),
-                    reps=3, warm=1)
-        row = {"blocks": tot, "native_us": nat[0], "ptb_us": ptb[0], "of_native": nat[0] / ptb[0],
-               "workers": c["param"], "chunk": c["chunk"],
-               "eq1_turnaround_us": c["turnaround_ms"] * 1e3}
+        row = {"blocks": k.total_blocks, "native_us": nat[0], "candidates": len(cands),
+               "chosen": {"form": "ptb" if c["kind"] == B.CFG_PTB else "sliced", "param": c["param"],
+                          "chunk": c["chunk"]},
+               "chosen_us": c["latency_ms"] * 1e3, "of_native": nat[0] / (c["latency_ms"] * 1e3),
+               "turnaround_estimate_us": c["turnaround_ms"] * 1e3,
+               "fastest_candidate_us": min(m["latency_ms"] for m in meas) * 1e3}
         if flops:
             row["native_TFLOPs"] = flops / nat[0] / 1e6
-            row["ptb_TFLOPs"] = flops / ptb[0] / 1e6
-            row["ptb_mfma_frac"] = row["ptb_TFLOPs"] / PEAK_BF16_TFLOPS
+            row["chosen_TFLOPs"] = flops / (c["latency_ms"] * 1e3) / 1e6
+            row["chosen_mfma_frac"] = row["chosen_TFLOPs"] / PEAK_BF16_TFLOPS
         if nbytes:
             row["native_GBps"] = nbytes / nat[0] / 1e3
-            row["ptb_GBps"] = nbytes / ptb[0] / 1e3
-            row["ptb_hbm_frac"] = row["ptb_GBps"] / PEAK_HBM_GBS
+            row["chosen_GBps"] = nbytes / (c["latency_ms"] * 1e3) / 1e3
+            row["chosen_hbm_frac"] = row["chosen_GBps"] / PEAK_HBM_GBS
         table[name] = row
-        items.append((k, (B.CFG_PTB, c["param"], c["chunk"])))
+        items.append((k, (B.CFG_AUTO, 0, 0)))
     return table, items
 
 
 def _colocate(torch, B, ctx, be_stream, args, hi, rate, cfg_index, label):
     import tally_inputs as TI
-    info = B.device_info()
     step = _be_step(torch, B)
-    table, items = _choose_configs(torch, B, ctx, be_stream, step, info["num_cus"])
     count = args.n_arrivals + args.n_warm
     w = args.n_warm
     arrivals = TI.poisson_arrivals_us(rate, count, config_index=cfg_index)
     dur_us = float(arrivals[-1])
     solo_hi = ctx.sched_run(hi, arrivals, [])
-    solo_be = ctx.sched_run([], [], items, tail_us=min(dur_us, 3e6))
-    co = ctx.sched_run(hi, arrivals, items, policy=B.POLICY_TALLY)
+    ls = solo_hi["latency_us"][w:]
+    # Turnaround-latency threshold (Section 4.2 leaves it a knob; Section 5.6 sweeps it): the
+    # paper's 0.0316 ms suits requests of milliseconds.  Unless given, it is a tenth of the
+    # request's own median latency alone, and never more than the paper's default.
+    thr = args.threshold_ms
+    rule = "given"
+    if thr is None:
+        thr = min(0.0316, 0.1 * pct(ls, 50) * 1e-3)
+        rule = "min(0.0316 ms, a tenth of the request's median latency alone)"
+    table, items = _profile_step(torch, B, ctx, be_stream, step, thr)
+    solo_be = ctx.sched_run([], [], items, tail_us=min(dur_us, 3e6), threshold_ms=thr)
+    co = ctx.sched_run(hi, arrivals, items, policy=B.POLICY_TALLY, threshold_ms=thr)
     nat_items = [(k, (B.CFG_NATIVE, 1, 1)) for k, _ in items]
-    sub = arrivals[: max(count // 2, MIN_P99_SAMPLES + min(w, 20))]
+    sub = arrivals[: max(count // 2, MIN_P99_SAMPLES + w)]
     nat = ctx.sched_run(hi, sub, nat_items, policy=B.POLICY_PRIORITY_NATIVE)
     nos = ctx.sched_run(hi, sub, nat_items, policy=B.POLICY_NONE)
-    ls, lc = solo_hi["latency_us"][w:], co["latency_us"][w:]
+    solo_nat = ctx.sched_run([], [], nat_items, policy=B.POLICY_NONE, tail_us=min(dur_us, 2e6))
+    lc = co["latency_us"][w:]
+    ds, dc = (solo_hi["latency_us"] - solo_hi["issue_us"])[w:], (co["latency_us"] - co["issue_us"])[w:]
     tput_solo = solo_be["be_kernels_done"] / solo_be["window_us"]
     tput_co = co["be_kernels_done"] / co["window_us"]
+    tput_nat = solo_nat["be_kernels_done"] / solo_nat["window_us"]
     pre = co["preempt_latency_us"]
     hist, edges = np.histogram(pre, bins=[0, 5, 10, 20, 40, 80, 160, 320, 1e9]) if len(pre) else ([], [])
     flops = sum(f for _, _, f, _ in step)
     return {
         "workload": label,
+        "turnaround_threshold_ms": thr, "turnaround_threshold_rule": rule,
         "hi_pri_latency_us": {"solo_p50": pct(ls, 50), "solo_p99": p99(ls),
                               "coloc_p50": pct(lc, 50), "coloc_p99": p99(lc), "n": len(lc),
                               # host share: scheduled arrival -> launch calls returned (includes
                               # waiting behind the previous request); the rest is the device's
                               "issue_solo_p99": p99(solo_hi["issue_us"][w:]),
-                              "issue_coloc_p99": p99(co["issue_us"][w:]),
-                              "after_launch_calls_solo_p99":
-                                  p99((solo_hi["latency_us"] - solo_hi["issue_us"])[w:]),
-                              "after_launch_calls_coloc_p99":
-                                  p99((co["latency_us"] - co["issue_us"])[w:])},
+                              "issue_coloc_p99": p99(co["issue_us"][w:])},
+        "hi_pri_device_side_latency_us": {"solo_p50": pct(ds, 50), "solo_p99": p99(ds),
+                                          "coloc_p50": pct(dc, 50), "coloc_p99": p99(dc),
+                                          "p99_overhead_pct": ovh(p99(dc), p99(ds))},
         "p99_overhead_pct": ovh(p99(lc), p99(ls)),
         "p50_overhead_pct": (pct(lc, 50) - pct(ls, 50)) / pct(ls, 50) * 100.0,
         "be_tput_retained_pct": tput_co / tput_solo * 100.0,
+        "be_tput_retained_vs_native_alone_pct": tput_co / tput_nat * 100.0,
         "be_steps_per_s": {"solo": solo_be["be_steps_done"] / solo_be["window_us"] * 1e6,
-                           "coloc": co["be_steps_done"] / co["window_us"] * 1e6},
+                           "coloc": co["be_steps_done"] / co["window_us"] * 1e6,
+                           "native_alone": solo_nat["be_steps_done"] / solo_nat["window_us"] * 1e6},
         "be_step_TFLOPs_solo": flops * (solo_be["be_steps_done"] / solo_be["window_us"]) / 1e6,
         "preempt_latency_us": {"n": int(co["n_preempts"]), "p50": pct(pre, 50), "p99": p99(pre),
+                               "max": float(pre.max()) if len(pre) else None,
                                "histogram_edges_us": [0, 5, 10, 20, 40, 80, 160, 320, "inf"],
                                "histogram": [int(h) for h in hist]},
         "decomposition_p99_us": {"ideal": p99(ls), "full": p99(lc),
-                                 "priority_native_be": p99(nat["latency_us"][min(w, 20):]),
-                                 "no_scheduling": p99(nos["latency_us"][min(w, 20):])},
+                                 "priority_native_be": p99(nat["latency_us"][w:]),
+                                 "no_scheduling": p99(nos["latency_us"][w:]),
+                                 "n": len(nat["latency_us"][w:])},
         "be_kernels": table,
     }
 
@@ -474,14 +486,7 @@ def sweep_threshold(torch, B, ctx, be_stream, args):
     solo_b_p99 = p99(solo_b["latency_us"][wb:])
     tables = []
     for name, k, flops, nbytes in step:
-        if k.kernel_id in (B.K_GEMM_BF16, B.K_GEMM_BF16_N128):
-            cs = [(B.CFG_PTB, cu, 1), (B.CFG_SLICED, cu, 1), (B.CFG_SLICED, 4 * cu, 1)]
-        elif "gemm" in name:
-            cs = [(B.CFG_PTB, 4 * cu, 1), (B.CFG_PTB, 4 * cu, 4), (B.CFG_PTB, 4 * cu, 16),
-                  (B.CFG_SLICED, 16 * cu, 1)]
-        else:
-            cs = [(B.CFG_PTB, 2 * cu, 1), (B.CFG_PTB, 2 * cu, 4), (B.CFG_PTB, 2 * cu, 16),
-                  (B.CFG_PTB, 4 * cu, 64), (B.CFG_SLICED, 16 * cu, 1)]
+        cs = ctx.candidate_configs(k)          # the library's Section 4.2 candidate set
         m, _ = ctx.profile(k, _cap(B, ctx, k, cs), runs=3, threshold_ms=0.0316)
         tables.append((name, k, m))
     nat_items = [(k, (B.CFG_NATIVE, 1, 1)) for _, k, _, _ in step]

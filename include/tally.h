@@ -206,37 +206,58 @@ int tally_kernel_footprint(tally_ctx *ctx, uint32_t kernel_id, int form, uint32_
  * all resident at once on an otherwise idle GPU: compute units x workgroups per unit. */
 int tally_max_workers(tally_ctx *ctx, const tally_kernel_desc *desc, uint32_t *max_workers);
 
-/* Non-blocking.  Persistent-worker job: raise its preemption flag (one host store);
- * workers finish their current block(s) and exit.  Sliced job: stop issuing
- * sub-kernels.  No-op on STOPPED / COMPLETE jobs. */
+/* preempt_best_effort_kernel() of the scheduling algorithm (Section 4.2, Figure 4), acting
+ * as Section 4.1 describes: non-blocking.  Persistent-worker job: raise its preemption
+ * signal (one host store; the device folds it into the global task counter, so that every
+ * later fetch of a task index fails); workers finish the block(s) they hold and exit,
+ * leaving the progress in the task index.  Sliced job: stop issuing sub-kernels (those
+ * already enqueued finish).  No-op on STOPPED / COMPLETE jobs.  Callable from any thread. */
 int tally_preempt(tally_job *job);
 
-/* Continue a STOPPED job from its saved task counter / block offset (Section 4.1:
- * progress is held in the global task index).  On a persistent-worker job that is
- * still RUNNING with a preemption request raised, the request is withdrawn instead
- * (workers pausing inside a long block go on; see tally_set_yield_bound_us).  Otherwise
- * BAD_STATE while RUNNING; no-op when COMPLETE. */
+/* Extension for blocks that last far longer than the turnaround threshold (a 256x256 GEMM
+ * tile over a long K lasts 120 us and more): tally_preempt() plus a request that workers of
+ * kernels which support it pause INSIDE their block, keeping registers and LDS, so that the
+ * high-priority kernel runs beside them undisturbed.  The pause ends when tally_end_pause()
+ * withdraws it or when a block's pause budget (tally_set_yield_bound_us) is spent.  Only
+ * use it when the high-priority kernels fit beside the paused workgroups
+ * (tally_kernel_footprint); otherwise they wait for the pause to end.  Other kernels and
+ * sliced jobs: same as tally_preempt(). */
+int tally_preempt_pausing(tally_job *job);
+
+/* kernel.resume() of Figure 4: continue a STOPPED job from its saved task counter / block
+ * offset (Section 4.1: the progress of the execution is held in the global task index; a
+ * kernel that terminated early is resumed from the point at which it ended).  The task
+ * counter is not reset.  BAD_STATE while RUNNING; no-op when COMPLETE. */
 int tally_resume(tally_job *job);
 
-/* Extension for blocks that last far longer than the turnaround threshold (a 256x256
- * GEMM tile over a long K): while a preemption request stands, workers of such kernels
- * pause INSIDE the block, keeping their registers and LDS, for at most `us`
- * microseconds (default 1000; 0 disables), so that the high-priority kernel runs beside
- * them undisturbed.  Workers between blocks still exit as in Section 4.1.  The bound
- * keeps a high-priority kernel that does not fit beside the paused workers from waiting
- * for ever. */
+/* Budget of tally_preempt_pausing(): the longest time one block may spend paused, all its
+ * pauses together, in microseconds (default 1000; 0 disables pausing).  It keeps a
+ * high-priority kernel that does not fit beside the paused workers from waiting for ever.
+ * Applies to jobs launched after the call. */
 int tally_set_yield_bound_us(tally_ctx *ctx, uint32_t us);
 
-/* Non-blocking snapshot.  done_blocks = min(counter, total) as last published by the
- * device; exact once the job is STOPPED or COMPLETE.  Any out pointer may be null. */
+/* End the pause of tally_preempt_pausing(): paused workers go on and finish their block.
+ * The preemption itself stands (its signal is in the task counter): workers still leave at
+ * their next block boundary and the job becomes STOPPED.  No-op otherwise.  Any thread. */
+int tally_end_pause(tally_job *job);
+
+/* running() / stopped() of Figure 4, and the progress Section 4.1 keeps in the task index:
+ * non-blocking snapshot.  done_blocks = task indices handed out so far, at most total, as
+ * last published by the device; exact once the job is STOPPED or COMPLETE, when every block
+ * below it has run and none above it (the prefix property).  Any out pointer may be null.
+ * Callable from any thread. */
 int tally_progress(tally_job *job, uint64_t *done_blocks, uint64_t *total_blocks, int *state);
 
-/* Sliced jobs: retire finished sub-kernels and, unless preempted, enqueue the next
- * ones.  Persistent-worker jobs: refresh the state.  Non-blocking. */
+/* One visit of a best-effort client in the loop of Figure 4 (Section 4.2: sub-kernels are
+ * launched one at a time).  Sliced jobs: retire finished sub-kernels and, unless preempted,
+ * enqueue the next ones.  Persistent-worker jobs: refresh the state.  Non-blocking. */
 int tally_pump(tally_job *job);
 
-/* Block (host spin) until the job is STOPPED or COMPLETE, then synchronise the
- * best-effort stream so outputs are visible. */
+/* Wait for the drain Section 4.1 describes (after a preemption signal every worker finishes
+ * its current block and exits) or for completion: blocks (host spin, pumping a sliced job)
+ * until the job is STOPPED or COMPLETE, then synchronises the best-effort stream so that
+ * outputs are visible.  TALLY_ERR_BAD_STATE if the device could not report the progress of
+ * a preempted segment (never seen; the job then cannot be resumed). */
 int tally_wait(tally_job *job, int *state);
 int tally_job_free(tally_job *job); /* waits for in-flight launches of the job first */
 
@@ -298,14 +319,109 @@ int tally_select_config(const tally_config *cands, uint32_t n, double threshold_
  * between two pause points, since that is when the execution units are handed over. */
 int tally_profile(tally_ctx *ctx, const tally_kernel_desc *desc, tally_config *cands, uint32_t n,
                   uint32_t runs, double threshold_ms, uint32_t *chosen);
-/* Cached choice for (kernel, grid, block); TALLY_ERR_BAD_STATE if not profiled yet. */
+/* lookup_launch_config() of Figure 4: the fixed choice for (kernel, grid, block);
+ * TALLY_ERR_BAD_STATE while none is fixed. */
 int tally_lookup_config(tally_ctx *ctx, const tally_kernel_desc *desc, tally_config *out);
+
+/* get_candidate_configs() of Figure 4 (Section 4.2): persistent-worker counts that are
+ * multiples of the compute-unit count up to tally_max_workers(), each with 1, 4 and 16 task
+ * indices per fetch where every worker then still has a fetch to make, and slices of
+ * 1/2, 1/4, ... 1/256 of the grid.  Writes at most cap entries (latency and turnaround zero)
+ * and their number. */
+int tally_candidate_configs(tally_ctx *ctx, const tally_kernel_desc *desc, tally_config *out,
+                            uint32_t cap, uint32_t *n);
+
+/* The profiling record of (kernel, grid, block) as it stands: candidates (latency = mean of
+ * the samples so far), samples per candidate, index of the fixed choice or -1.  *n = 0 if
+ * the kernel has never been seen.  out / samples may be NULL. */
+int tally_profile_table(tally_ctx *ctx, const tally_kernel_desc *desc, tally_config *out, uint32_t cap,
+                        uint32_t *n, uint32_t *samples, int *chosen);
+int tally_profile_reset(tally_ctx *ctx);   /* forget every measurement and choice */
 
 /* ---- two-stream priority scheduler (Section 4.2, Figure 4) ------------------------- */
 
+/* The priority-aware scheduler as a running service.  Clients hand it kernels: the
+ * high-priority client's are dispatched at once in their original form after the running
+ * best-effort kernels have been told to give way (Figure 4, the high-priority branch);
+ * best-effort clients' kernels are queued per client and launched, resumed or continued
+ * slice by slice only while no high-priority request is in flight (the best-effort branch).
+ * A best-effort kernel submitted without a configuration gets one as Section 4.2 describes:
+ * lookup_launch_config(), and while none is fixed launch_and_profile(): each real
+ * invocation of the kernel runs under the next unmeasured candidate of its candidate set
+ * and is that candidate's measurement; when every candidate has `profile_runs` samples the
+ * best-performing one whose turnaround estimate is within the threshold is fixed and reused.
+ * The scheduler is built on the calls above (launch, preempt, resume, pump, progress).
+ *
+ * Threads: the best-effort clients are served by a thread the scheduler owns (it sleeps
+ * while no client has work).  tally_sched_submit_hi / tally_sched_poll must come from one
+ * thread (the high-priority client's); tally_sched_submit_be / tally_sched_stats from any.
+ * While a scheduler exists, do not call launch functions on its context yourself. */
+typedef struct tally_sched tally_sched;
+
+#define TALLY_SCHED_NO_PAUSE 1u      /* never ask workers to pause inside their blocks        */
+typedef struct {
+  uint32_t policy;          /* 0 = priority scheduling with preemption (the method)
+                               1 = priority scheduling, best-effort kernels as submitted
+                               2 = no scheduling: everything dispatched on arrival          */
+  uint32_t n_be_clients;    /* 0 .. 8; client 0 uses the context's best-effort stream, the
+                               others a stream pair of their own.  n clients need 2 + 2n
+                               hardware queues: the process must have been started with
+                               GPU_MAX_HW_QUEUES at least that (HIP's default is 4), else
+                               TALLY_ERR_UNSUPPORTED                                        */
+  double threshold_ms;      /* turnaround-latency threshold of the profile-guided choice;
+                               0 = the paper's default, 0.0316 ms                           */
+  uint32_t profile_runs;    /* invocations averaged per candidate; 0 = 10 (Section 4.2)     */
+  uint32_t flags;           /* TALLY_SCHED_*                                                */
+} tally_sched_opts;
+
+int tally_sched_create(tally_ctx *ctx, const tally_sched_opts *opts, tally_sched **out);
+/* Stops the best-effort thread (kernels in flight are preempted at block boundaries and
+ * dropped where they stand, queued ones discarded), waits for the streams, frees. */
+int tally_sched_destroy(tally_sched *s);
+
+#define TALLY_SUBMIT_LOOP 1u         /* when the kernel completes it goes to the back of its
+                                        client's queue again (a training loop's step)        */
+#define TALLY_SUBMIT_END_OF_STEP 2u  /* completing it counts one step of the client           */
+/* Queue one best-effort kernel for `client`.  The descriptor and its args struct are copied;
+ * the device buffers they point to stay the caller's and must outlive the kernel.  config:
+ * persistent workers / sliced / native (kind 0 / 1 / 2) as given, or NULL to have the
+ * profiler choose. */
+int tally_sched_submit_be(tally_sched *s, uint32_t client, const tally_kernel_desc *kernel,
+                          const tally_config *config, uint32_t flags);
+
+/* One high-priority request of n kernels: preempt_best_effort_kernel() for every
+ * best-effort client (workers pause inside long blocks if all n kernels fit beside them,
+ * else they only give way at block boundaries), then launch the kernels in their original
+ * form on the high-priority stream.  One request at a time: TALLY_ERR_BAD_STATE while the
+ * previous one is in flight. */
+int tally_sched_submit_hi(tally_sched *s, const tally_kernel_desc *kernels, uint32_t n);
+
+/* Non-blocking: has the request in flight completed?  When it has, the best-effort clients
+ * are released (and paused workers go on) unless more_pending says that another request
+ * follows at once.  Also reports an error of the best-effort thread. */
+int tally_sched_poll(tally_sched *s, int more_pending, int *hi_in_flight);
+
+/* Switch the best-effort side off (running kernels are preempted and stay stopped) or on. */
+int tally_sched_enable_be(tally_sched *s, int enable);
+
+typedef struct {
+  uint64_t hi_requests_done;
+  uint64_t be_kernels_done;            /* over all clients                                   */
+  uint64_t be_steps_done;              /* client 0: kernels flagged END_OF_STEP completed    */
+  uint64_t be_client_kernels_done[8];
+  uint64_t n_preempts;                 /* drains that followed a preemption request          */
+  uint64_t profile_samples;            /* invocations that served as a candidate's measurement */
+  uint64_t configs_fixed;              /* kernels whose configuration the profiler has fixed  */
+} tally_sched_stats_t;
+int tally_sched_stats(tally_sched *s, tally_sched_stats_t *out);
+/* Move up to cap recorded preemption latencies (request -> drained, microseconds, host
+ * clock) into out; the scheduler keeps the 4096 oldest not yet taken. */
+int tally_sched_take_preempt_latencies(tally_sched *s, double *out, uint32_t cap, uint32_t *n);
+
 typedef struct {
   const tally_kernel_desc *kernel; /* one best-effort kernel of the step                   */
-  tally_config config;             /* kind 0/1 as above; kind 2 = native (untransformed)   */
+  tally_config config;             /* kind 0/1 as above; kind 2 = native (untransformed);
+                                      kind 3 = chosen by the profiler                       */
 } tally_be_item;
 
 typedef struct {
@@ -313,37 +429,32 @@ typedef struct {
   const tally_kernel_desc *hi_kernels; uint32_t n_hi_kernels; /* one high-priority request  */
   const double *arrivals_us; uint32_t n_arrivals; /* open-loop arrival times from t0        */
   const tally_be_item *be_items; uint32_t n_be_items; /* one best-effort step, repeated      */
-  uint32_t policy;            /* 0 = priority scheduling with preemption (the method)
-                                 1 = priority scheduling, best-effort kernels native
-                                 2 = no scheduling: both dispatched on arrival              */
+  uint32_t policy;            /* as tally_sched_opts.policy                                  */
   double tail_us;             /* keep feeding best-effort work this long after last arrival  */
   /* outputs (host arrays owned by the caller) */
   double *latency_us;         /* n_arrivals: scheduled arrival -> completion observed        */
   double *preempt_latency_us; uint32_t preempt_cap; uint32_t n_preempts; /* per preemption   */
   uint64_t be_kernels_done;   /* best-effort kernels completed inside the window             */
   uint64_t be_steps_done;
-  double window_us;           /* wall time of the run                                        */
+  double window_us;           /* wall time of the run (start of the clock to the last request
+                                 completed and the tail elapsed; teardown is not in it)      */
   double *issue_us;           /* optional (may be NULL), n_arrivals: scheduled arrival -> the
                                  request's launch calls have returned on the host            */
   /* several best-effort clients (Figure 4 loops over them): be_items is the concatenation
-   * of the clients' steps, client c owning be_client_items[c] consecutive items; each
-   * client has one kernel in flight at a time on a stream pair of its own (client 0 uses
-   * the context's best-effort stream).  NULL / 0 = one client owning every item; at most
-   * 8 clients.  be_steps_done counts client 0's steps.  A kernel is launched only when
-   * the workgroups it brings fit beside the other clients' resident ones (clients wait
-   * first come, first served).  n clients need 2 + 2n hardware queues: the process must
-   * have been started with GPU_MAX_HW_QUEUES at least that (HIP's default is 4), else
-   * TALLY_ERR_UNSUPPORTED. */
+   * of the clients' steps, client c owning be_client_items[c] consecutive items.  NULL / 0 =
+   * one client owning every item; at most 8 clients.  be_steps_done counts client 0's. */
   const uint32_t *be_client_items; uint32_t n_be_clients;
   uint64_t *be_client_kernels_done; /* optional output, n_be_clients entries                */
+  /* profile-guided items (kind 3) */
+  double threshold_ms; uint32_t profile_runs; uint32_t sched_flags;   /* as tally_sched_opts */
+  uint64_t profile_samples, configs_fixed;                            /* outputs             */
 } tally_sched_run_t;
 
-/* Run the scheduling loop on the calling thread until every arrival has completed and
- * tail_us has elapsed.  Best-effort workers pause inside their blocks while preempted
- * (where the kernel supports it) only if every high-priority kernel of the request fits
- * beside the paused workers on a compute unit; otherwise that item's workers give way at
- * block boundaries only.  n_arrivals == 0 runs the best-effort job alone for tail_us;
- * n_be_items == 0 runs the high-priority job alone. */
+/* Replay driver over the scheduler: creates one, submits every best-effort item as a looping
+ * step, then plays the arrival list on the calling thread (tally_sched_submit_hi at each
+ * arrival time, tally_sched_poll until it completes) until every arrival has completed and
+ * tail_us has elapsed, and destroys the scheduler.  n_arrivals == 0 runs the best-effort job
+ * alone for tail_us; n_be_items == 0 runs the high-priority job alone. */
 int tally_sched_run(tally_ctx *ctx, tally_sched_run_t *run);
 
 #ifdef __cplusplus

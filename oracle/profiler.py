@@ -92,11 +92,19 @@ class ProfileCache:
         return None
 
     def record(self, key, cand, latency_ms, total_blocks, slice_latency_ms=None):
-        kind, param = cand
+        """cand = (kind, param) or (kind, param, n): n task indices per fetch for persistent
+        workers (each worker then holds n blocks, so Eq. 1 is taken with n times the worker
+        blocks), n slices kept enqueued for a sliced candidate.  The time of one slice
+        defaults to the kernel's time divided by its number of slices."""
+        kind, param = cand[0], cand[1]
+        n = cand[2] if len(cand) > 2 else 1
         if kind == "ptb":
-            t = ptb_turnaround_ms(latency_ms, param, total_blocks)
+            t = ptb_turnaround_ms(latency_ms, param * n, total_blocks)
         else:
-            t = sliced_turnaround_ms(slice_latency_ms)
+            slices = -(-total_blocks // param)
+            if slice_latency_ms is None:
+                slice_latency_ms = latency_ms / slices
+            t = sliced_turnaround_ms(slice_latency_ms, n, n_slices=slices)
         self.meas.setdefault(key, {})[cand] = {
             "kind": kind, "param": param, "latency_ms": latency_ms, "turnaround_ms": t}
 

@@ -37,7 +37,9 @@ K_SOFTMAX_F32, K_LAYERNORM_F32, K_ATTN_DECODE_BF16, K_GEMM_BF16_SMALL = 5, 6, 7,
 K_GEMM_BF16_N128 = 9
 JOB_QUEUED, JOB_RUNNING, JOB_STOPPED, JOB_COMPLETE = 0, 1, 2, 3
 OK, ERR_INVALID_ARG, ERR_BAD_STATE, ERR_HIP, ERR_NOMEM, ERR_UNSUPPORTED = 0, -1, -2, -3, -4, -5
-CFG_PTB, CFG_SLICED, CFG_NATIVE = 0, 1, 2
+CFG_PTB, CFG_SLICED, CFG_NATIVE, CFG_AUTO = 0, 1, 2, 3
+SUBMIT_LOOP, SUBMIT_END_OF_STEP = 1, 2
+SCHED_NO_PAUSE = 1
 POLICY_TALLY, POLICY_PRIORITY_NATIVE, POLICY_NONE = 0, 1, 2
 
 EXPORTS = [
@@ -48,7 +50,11 @@ EXPORTS = [
     "tally_marker_read", "tally_last_preempt_latency_us", "tally_last_hip_error",
     "tally_strerror", "tally_max_workers", "tally_kernel_footprint", "tally_mfma_ceiling_tflops", "tally_device_info", "tally_ptb_turnaround_ms", "tally_select_config",
     "tally_profile", "tally_lookup_config", "tally_sched_run", "tally_set_yield_bound_us",
-    "tally_launch_attn_decode_static",
+    "tally_launch_attn_decode_static", "tally_preempt_pausing", "tally_end_pause",
+    "tally_candidate_configs", "tally_profile_table", "tally_profile_reset",
+    "tally_sched_create", "tally_sched_destroy", "tally_sched_submit_be", "tally_sched_submit_hi",
+    "tally_sched_poll", "tally_sched_enable_be", "tally_sched_stats",
+    "tally_sched_take_preempt_latencies",
 ]
 
 
@@ -129,7 +135,22 @@ class SchedRun(C.Structure):
                 ("be_kernels_done", C.c_uint64), ("be_steps_done", C.c_uint64),
                 ("window_us", C.c_double), ("issue_us", C.POINTER(C.c_double)),
                 ("be_client_items", C.POINTER(C.c_uint32)), ("n_be_clients", C.c_uint32),
-                ("be_client_kernels_done", C.POINTER(C.c_uint64))]
+                ("be_client_kernels_done", C.POINTER(C.c_uint64)),
+                ("threshold_ms", C.c_double), ("profile_runs", C.c_uint32),
+                ("sched_flags", C.c_uint32),
+                ("profile_samples", C.c_uint64), ("configs_fixed", C.c_uint64)]
+
+
+class SchedOpts(C.Structure):
+    _fields_ = [("policy", C.c_uint32), ("n_be_clients", C.c_uint32), ("threshold_ms", C.c_double),
+                ("profile_runs", C.c_uint32), ("flags", C.c_uint32)]
+
+
+class SchedStats(C.Structure):
+    _fields_ = [("hi_requests_done", C.c_uint64), ("be_kernels_done", C.c_uint64),
+                ("be_steps_done", C.c_uint64), ("be_client_kernels_done", C.c_uint64 * 8),
+                ("n_preempts", C.c_uint64), ("profile_samples", C.c_uint64),
+                ("configs_fixed", C.c_uint64)]
 
 
 class TallyError(RuntimeError):
@@ -181,6 +202,19 @@ def _load():
         "tally_max_workers": ([vp, P(KernelDesc), P(u32)], i32),
         "tally_kernel_footprint": ([vp, u32, i32, P(u32), P(u32), P(u32)], i32),
         "tally_mfma_ceiling_tflops": ([vp, u32, P(dbl)], i32),
+        "tally_preempt_pausing": ([vp], i32),
+        "tally_end_pause": ([vp], i32),
+        "tally_candidate_configs": ([vp, P(KernelDesc), P(Config), u32, P(u32)], i32),
+        "tally_profile_table": ([vp, P(KernelDesc), P(Config), u32, P(u32), P(u32), P(i32)], i32),
+        "tally_profile_reset": ([vp], i32),
+        "tally_sched_create": ([vp, P(SchedOpts), P(vp)], i32),
+        "tally_sched_destroy": ([vp], i32),
+        "tally_sched_submit_be": ([vp, u32, P(KernelDesc), P(Config), u32], i32),
+        "tally_sched_submit_hi": ([vp, P(KernelDesc), u32], i32),
+        "tally_sched_poll": ([vp, i32, P(i32)], i32),
+        "tally_sched_enable_be": ([vp, i32], i32),
+        "tally_sched_stats": ([vp, P(SchedStats)], i32),
+        "tally_sched_take_preempt_latencies": ([vp, P(dbl), u32, P(u32)], i32),
     }
     assert set(sig) == set(EXPORTS), set(sig) ^ set(EXPORTS)
     for name, (argtypes, restype) in sig.items():
@@ -305,8 +339,15 @@ class Job:
         self.h = handle
         self.kernel = kernel
 
-    def preempt(self):
-        _check(_lib.tally_preempt(self.h), "tally_preempt")
+    def preempt(self, pause=False):
+        """Raise the preemption signal; with pause, also ask workers to pause inside long blocks."""
+        if pause:
+            _check(_lib.tally_preempt_pausing(self.h), "tally_preempt_pausing")
+        else:
+            _check(_lib.tally_preempt(self.h), "tally_preempt")
+
+    def end_pause(self):
+        _check(_lib.tally_end_pause(self.h), "tally_end_pause")
 
     def resume(self, stop_at=None):
         if stop_at is None:
@@ -407,6 +448,32 @@ class Context:
                     turnaround_ms=c.turnaround_ms) for c in arr]
         return out, chosen.value
 
+    def candidate_configs(self, kernel, cap=64):
+        """The Section 4.2 candidate set of a kernel as a list of (kind, param, chunk)."""
+        arr = (Config * cap)()
+        n = C.c_uint32()
+        _check(_lib.tally_candidate_configs(self.h, C.byref(kernel.desc), arr, cap, C.byref(n)),
+               "tally_candidate_configs")
+        return [(arr[i].kind, arr[i].param, arr[i].chunk) for i in range(n.value)]
+
+    def profile_table(self, kernel, cap=64):
+        """(list of candidate dicts with their sample counts, index of the fixed choice or -1)."""
+        arr = (Config * cap)()
+        smp = (C.c_uint32 * cap)()
+        n, chosen = C.c_uint32(), C.c_int()
+        _check(_lib.tally_profile_table(self.h, C.byref(kernel.desc), arr, cap, C.byref(n), smp,
+                                        C.byref(chosen)), "tally_profile_table")
+        rows = [dict(kind=arr[i].kind, param=arr[i].param, chunk=arr[i].chunk,
+                     latency_ms=arr[i].latency_ms, turnaround_ms=arr[i].turnaround_ms,
+                     samples=smp[i]) for i in range(min(n.value, cap))]
+        return rows, chosen.value
+
+    def profile_reset(self):
+        _check(_lib.tally_profile_reset(self.h), "tally_profile_reset")
+
+    def scheduler(self, policy=POLICY_TALLY, be_clients=1, threshold_ms=0.0, profile_runs=0, flags=0):
+        return Scheduler(self, policy, be_clients, threshold_ms, profile_runs, flags)
+
     def mfma_ceiling_tflops(self, reps=10):
         """Measured bf16 matrix-pipe ceiling (register-only MFMA loop on every compute unit)."""
         v = C.c_double()
@@ -437,7 +504,7 @@ class Context:
                     turnaround_ms=c.turnaround_ms)
 
     def sched_run(self, hi_kernels, arrivals_us, be_items, policy=POLICY_TALLY, tail_us=0.0,
-                  be_clients=None):
+                  be_clients=None, threshold_ms=0.0, profile_runs=0, flags=0):
         """hi_kernels: list of Kernel (one request).  be_items: list of (Kernel, (kind, param,
         chunk)).  be_clients: optional list of item counts, one per best-effort client (the
         items are the concatenation of the clients' steps).  Returns a dict of numpy arrays
@@ -461,6 +528,9 @@ class Context:
         run.n_be_items = len(be_items)
         run.policy = policy
         run.tail_us = float(tail_us)
+        run.threshold_ms = float(threshold_ms)
+        run.profile_runs = int(profile_runs)
+        run.sched_flags = int(flags)
         run.latency_us = lat.ctypes.data_as(C.POINTER(C.c_double))
         run.preempt_latency_us = pre.ctypes.data_as(C.POINTER(C.c_double))
         run.preempt_cap = cap
@@ -483,7 +553,64 @@ class Context:
             "be_steps_done": run.be_steps_done,
             "window_us": run.window_us,
             "be_client_kernels_done": per_client,
+            "profile_samples": run.profile_samples,
+            "configs_fixed": run.configs_fixed,
         }
+
+
+class Scheduler:
+    """The priority scheduler as a running service (tally_sched_*)."""
+
+    def __init__(self, ctx, policy, be_clients, threshold_ms, profile_runs, flags):
+        self.ctx = ctx
+        self._keep = []
+        opts = SchedOpts(policy, be_clients, float(threshold_ms), int(profile_runs), int(flags))
+        h = C.c_void_p()
+        _check(_lib.tally_sched_create(ctx.h, C.byref(opts), C.byref(h)), "tally_sched_create")
+        self.h = h
+
+    def submit_be(self, kernel, config=None, client=0, loop=False, end_of_step=False):
+        self._keep.append(kernel)
+        cfg = None
+        if config is not None:
+            cfg = C.byref(Config(config[0], config[1], config[2] if len(config) > 2 else 1, 0.0, 0.0))
+        flags = (SUBMIT_LOOP if loop else 0) | (SUBMIT_END_OF_STEP if end_of_step else 0)
+        _check(_lib.tally_sched_submit_be(self.h, client, C.byref(kernel.desc), cfg, flags),
+               "tally_sched_submit_be")
+
+    def submit_hi(self, kernels):
+        arr = (KernelDesc * len(kernels))(*[k.desc for k in kernels])
+        _check(_lib.tally_sched_submit_hi(self.h, arr, len(kernels)), "tally_sched_submit_hi")
+
+    def poll(self, more_pending=False):
+        """True while the high-priority request is still in flight."""
+        f = C.c_int()
+        _check(_lib.tally_sched_poll(self.h, 1 if more_pending else 0, C.byref(f)), "tally_sched_poll")
+        return bool(f.value)
+
+    def enable_be(self, on=True):
+        _check(_lib.tally_sched_enable_be(self.h, 1 if on else 0), "tally_sched_enable_be")
+
+    def stats(self):
+        st = SchedStats()
+        _check(_lib.tally_sched_stats(self.h, C.byref(st)), "tally_sched_stats")
+        return {"hi_requests_done": st.hi_requests_done, "be_kernels_done": st.be_kernels_done,
+                "be_steps_done": st.be_steps_done,
+                "be_client_kernels_done": list(st.be_client_kernels_done),
+                "n_preempts": st.n_preempts, "profile_samples": st.profile_samples,
+                "configs_fixed": st.configs_fixed}
+
+    def take_preempt_latencies(self, cap=4096):
+        buf = (C.c_double * cap)()
+        n = C.c_uint32()
+        _check(_lib.tally_sched_take_preempt_latencies(self.h, buf, cap, C.byref(n)),
+               "tally_sched_take_preempt_latencies")
+        return np.array(buf[: n.value], dtype=np.float64)
+
+    def close(self):
+        if self.h is not None:
+            h, self.h = self.h, None
+            _check(_lib.tally_sched_destroy(h), "tally_sched_destroy")
 
 
 def device_info():

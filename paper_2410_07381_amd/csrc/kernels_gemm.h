@@ -255,12 +255,13 @@ struct GemmBodyT {
     // barrier needs anyway; all other waits sit inside a basic block and name exactly the
     // reads they need.
     uint32_t kt = 0;
+    uint32_t pause_left = ctl.ticks;   // what is left of this block's pause budget
     // steady state: stages kt+1 and kt+2 are in flight, stage kt+3 is issued here (its
     // slot in the ring held stage kt-1, whose last reads were issued a whole step ago)
     for (; kt + 3 < nk; ++kt) {
       // one wave polls; the others meet it at the barrier below
       if (ctl.ticks != 0 && wave == 0 && (kt & (YIELD_EVERY - 1)) == YIELD_EVERY - 1)
-        yield_while_preempted(ctl);
+        yield_while_preempted(ctl, pause_left);
       // stage kt+1 complete, kt+2 in flight
       asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LOADS) : "memory");
       __syncthreads();  // stage kt+1 is in LDS for everyone; everyone is done with kt-1

@@ -22,18 +22,26 @@
 
 namespace tally {
 
-constexpr uint32_t kStop = 0xFFFFFFFFu;
+// A preemption request is folded into the task counter by adding this to it: every later
+// fetch then returns an index beyond any grid (grids have fewer than 2^30 blocks).
+constexpr uint32_t kPreemptStep = 0x80000000u;
+// Bit of the host's request word that says "do not pause inside blocks".
+constexpr uint32_t kNoPauseBit = 0x80000000u;
 
 // Device-side control block of one persistent-worker launch segment.
 struct PtbCtl {
-  uint32_t *counter;        // device: global task counter (next task index)
-  uint32_t *dev_flag;       // device, 8-byte aligned: [0] epoch of the last preemption relayed,
-                            // [1] epoch of the last segment whose grid was exhausted
+  uint32_t *counter;        // device: THE shared word.  Next task index (+ counter_base), plus
+                            // kPreemptStep once a preemption request has been folded in.  It is
+                            // never reset and wraps; indices are differences modulo 2^32.
   uint32_t *exited;         // device: workers that have exited, summed over all segments
-  const uint32_t *host_flag;  // pinned host memory: epoch the host wants preempted
+  unsigned long long *pre;  // device: (epoch << 32 | progress) written by the relay right after
+                            // it folded a request in: what its fetch-and-add returned
+  const uint32_t *host_flag;  // pinned host memory: epoch the host wants preempted (| kNoPauseBit)
   unsigned long long *host_status;  // pinned: (epoch << 32 | progress) once drained
   uint32_t *host_live;      // pinned: progress mirrored while running
   uint32_t *host_raw;       // pinned: raw counter value at the drain (written before status)
+  unsigned long long *host_relay;   // pinned: (epoch << 32 | raw counter) when the relay has ended
+  uint32_t *host_relay_flags;       // pinned: bit 0 the relay gave up early, bit 1 it folded a request in
   tally_cover_rec *cover;   // device, may be null
   uint32_t total;           // logical blocks in the grid
   uint32_t limit;           // workers treat this as the end of the grid (== total normally)
@@ -42,11 +50,13 @@ struct PtbCtl {
   uint32_t counter_base;    // raw counter value that stands for task index 0 of this job
   uint32_t workers;
   uint32_t chunk;           // task indices per fetch
+  uint32_t single_pass;     // the workers' first fetches cover every index left: none fetches twice
   uint32_t segment;         // 0-based segment number, for the coverage records
   uint32_t gx, gy;          // logical grid extents (x fastest)
-  uint32_t yield_ticks;     // longest pause inside a block, in 10 ns wall-clock ticks (0: never)
-  uint32_t *flag_copies;    // device: kFlagCopies copies of dev_flag[0], 128 B apart, for the
-                            // mid-block polls (one address serves only ~80 M coherent scalar
+  uint32_t yield_ticks;     // longest pause inside ONE block, in 10 ns wall-clock ticks (0: never)
+  uint32_t *flag_copies;    // device: kFlagCopies copies of the pause request (the epoch while
+                            // workers are to pause inside their blocks, else 0), 128 B apart, for
+                            // the mid-block polls (one address serves only ~80 M coherent scalar
                             // loads per second, whoever asks)
 };
 constexpr uint32_t kFlagCopies = 64;
@@ -105,13 +115,22 @@ __global__ __launch_bounds__(Body::THREADS, Body::MIN_WAVES) void sliced_kernel(
 }
 
 // ---- persistent-worker form (Section 4.1, preemption) --------------------------------
-// The host raises the flag with one store to pinned host memory (cheap to write, but a
-// load from it crosses PCIe, far too slow for hundreds of workers to poll every
-// iteration).  A one-wave relay kernel, launched just before the workers on a stream of
-// its own, polls that word, copies every change of it into a device-memory flag the
-// workers can poll cheaply, and mirrors the progress back to the host.  It leaves when
-// every worker of the segment has exited, so its lifetime is bounded by the workers',
-// which depend on nothing.
+// The paper's worker reads a flag, then fetches and increments the task counter: two
+// dependent round trips to memory per iteration.  Here the flag lives in the counter: a
+// request is raised by adding 2^31 to it, a worker does ONE fetch-and-add per iteration
+// and leaves when the index it got is beyond the grid, whether the grid is exhausted or a
+// request was folded in.  A fetched index is always run (check and fetch are one
+// operation, so the order question does not arise).
+//
+// The host raises a request with one store to pinned host memory (cheap to write, but a
+// load from it crosses PCIe, far too slow for hundreds of workers to poll).  A one-wave
+// relay kernel, launched just before the workers on a stream of its own, polls that word;
+// when it names this segment the relay folds the request into the counter (its
+// fetch-and-add returns the exact progress, which it leaves in `pre` for the last worker
+// to publish) and, unless the request says otherwise, raises the pause word that workers
+// inside long blocks poll.  It mirrors the progress to the host and leaves when every
+// worker of the segment has exited, so its lifetime is bounded by the workers', which
+// depend on nothing.
 //
 // The relay polls with scalar loads that bypass the scalar cache: a vector load that
 // waits a microsecond on PCIe sits in the compute unit's vector-memory return queue in
@@ -126,41 +145,74 @@ __device__ __forceinline__ uint32_t scalar_load_coherent(const uint32_t *p) {
 constexpr unsigned long long kRelayGiveUpTicks = 2000000ull;  // 20 ms of the 100 MHz clock
 
 __global__ __launch_bounds__(64) void relay_kernel(PtbCtl c) {
-  uint32_t last = 0xFFFFFFFFu;
+  uint32_t last = 0u;        // the host's word is 0 while nothing is asked
+  bool added = false, gave_up = false;
   // The relay is launched before its workers.  Where the two cannot run side by side
   // (kernels executed strictly one after another) the workers cannot start until the
   // relay has ended: it leaves when neither the task counter nor the exit counter has
-  // moved for 20 ms, and that launch segment then runs without the means to preempt it.
+  // moved (by anyone but itself) for 20 ms; a request it folded in before that stands,
+  // and the workers then find it when they start.
   const unsigned long long born = wall_clock64();
-  const uint32_t ctr0 = scalar_load_coherent(c.counter), gone0 = scalar_load_coherent(c.exited);
+  uint32_t ctr0 = scalar_load_coherent(c.counter);
+  const uint32_t gone0 = scalar_load_coherent(c.exited);
   bool alive = false;
   for (uint32_t n = 0;; ++n) {
-    // forward every change of the host's word: a request (the segment's epoch) and, later,
-    // its withdrawal, which lets workers that paused inside a long block carry on
-    uint32_t want = scalar_load_coherent(c.host_flag);
-    if (want != last) {
-      if (threadIdx.x == 0)
-        __hip_atomic_store(c.dev_flag, want, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      if (c.flag_copies != nullptr && threadIdx.x < kFlagCopies)
-        __hip_atomic_store(c.flag_copies + threadIdx.x * kFlagCopyStride, want, __ATOMIC_RELAXED,
-                           __HIP_MEMORY_SCOPE_AGENT);
-      last = want;
+    // once the request is in the counter only its withdrawal (the end of a pause) is news
+    // from the host, and the exit counter is what matters: look at the host less often
+    if (!added || (n & 3u) == 0u) {
+      const uint32_t want = scalar_load_coherent(c.host_flag);
+      if (want != last) {
+        const bool mine = (want & ~kNoPauseBit) == c.epoch;
+        if (mine && !added) {
+          uint32_t p = 0;
+          if (threadIdx.x == 0) {
+            const uint32_t old = __hip_atomic_fetch_add(c.counter, kPreemptStep, __ATOMIC_RELAXED,
+                                                        __HIP_MEMORY_SCOPE_AGENT);
+            p = old - c.counter_base;
+            p = p < c.limit ? p : c.limit;
+            __hip_atomic_store(c.pre, ((unsigned long long)c.epoch << 32) | p, __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(c.host_live, p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+          }
+          added = true;
+          ctr0 += kPreemptStep;
+        }
+        // pause word: this segment's epoch while its workers are to pause inside blocks
+        const uint32_t pause = (mine && !(want & kNoPauseBit)) ? c.epoch : 0u;
+        if (c.flag_copies != nullptr && threadIdx.x < kFlagCopies)
+          __hip_atomic_store(c.flag_copies + threadIdx.x * kFlagCopyStride, pause, __ATOMIC_RELAXED,
+                             __HIP_MEMORY_SCOPE_AGENT);
+        last = want;
+      }
     }
     // the counters of a slot only ever grow (they are never reset), so a relay that
     // starts late, even after its workers are long gone, still sees the target passed
     uint32_t gone = scalar_load_coherent(c.exited);
     if ((n & 255u) == 255u)  // and, now and then, through the path the workers' atomics use
       gone = __hip_atomic_load(c.exited, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if ((int32_t)(gone - c.exit_target) >= 0) return;
+    if ((int32_t)(gone - c.exit_target) >= 0) break;
     if ((n & 15u) == 0u) {
       const uint32_t raw = scalar_load_coherent(c.counter);
       if (raw != ctr0 || gone != gone0) alive = true;
-      if (!alive && wall_clock64() - born > kRelayGiveUpTicks) return;
-      uint32_t ctr = raw - c.counter_base;
-      if (threadIdx.x == 0)
-        __hip_atomic_store(c.host_live, ctr < c.limit ? ctr : c.limit, __ATOMIC_RELAXED,
-                           __HIP_MEMORY_SCOPE_SYSTEM);
+      if (!alive && wall_clock64() - born > kRelayGiveUpTicks) { gave_up = true; break; }
+      if (!added) {
+        const uint32_t ctr = raw - c.counter_base;
+        if (threadIdx.x == 0)
+          __hip_atomic_store(c.host_live, ctr < c.limit ? ctr : c.limit, __ATOMIC_RELAXED,
+                             __HIP_MEMORY_SCOPE_SYSTEM);
+      }
     }
+  }
+  // Last act: tell the host that this relay will not touch the counter any more, and what
+  // the counter holds now (every worker has exited unless the relay gave up, in which case
+  // the last worker's own report is the final one).
+  if (threadIdx.x == 0) {
+    const uint32_t raw = __hip_atomic_load(c.counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(c.host_relay_flags, (gave_up ? 1u : 0u) | (added ? 2u : 0u), __ATOMIC_RELAXED,
+                       __HIP_MEMORY_SCOPE_SYSTEM);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __hip_atomic_store(c.host_relay, ((unsigned long long)c.epoch << 32) | raw, __ATOMIC_RELAXED,
+                       __HIP_MEMORY_SCOPE_SYSTEM);
   }
 }
 
@@ -169,47 +221,38 @@ __global__ __launch_bounds__(64) void relay_kernel(PtbCtl c) {
 // microseconds (a 256x256 GEMM tile over a long K) would keep competing with the
 // high-priority kernel for memory bandwidth and issue slots all that time.  Such a body
 // calls this every few steps: the wave sleeps, holding its registers and LDS (the
-// high-priority kernel runs beside it), until the request is withdrawn or `yield_ticks`
-// have passed, so a high-priority kernel that does NOT fit beside it cannot deadlock.
+// high-priority kernel runs beside it), until the request is withdrawn or the block's
+// pause budget is spent, so a high-priority kernel that does NOT fit beside it cannot
+// deadlock.  The budget is per block: `left` carries what remains of it across the polls.
 struct YieldCtl {          // passed by value: taking the address of the kernel's control
   const uint32_t *flag;    // block would force it out of scalar registers into memory
   uint32_t epoch, ticks;
 };
-__device__ __forceinline__ void yield_while_preempted(const YieldCtl &y) {
-  if (scalar_load_coherent(y.flag) != y.epoch) return;
+__device__ __forceinline__ void yield_while_preempted(const YieldCtl &y, uint32_t &left) {
+  if (left == 0u || scalar_load_coherent(y.flag) != y.epoch) return;
   const unsigned long long t0 = wall_clock64();
+  unsigned long long spent;
   do {
     __builtin_amdgcn_s_sleep(64);
-  } while (scalar_load_coherent(y.flag) == y.epoch &&
-           wall_clock64() - t0 < (unsigned long long)y.ticks);
+    spent = wall_clock64() - t0;
+  } while (scalar_load_coherent(y.flag) == y.epoch && spent < (unsigned long long)left);
+  left = spent < (unsigned long long)left ? left - (uint32_t)spent : 0u;
 }
+
+constexpr uint32_t kPreSpinCap = 1u << 22;   // polls of `pre` before the last worker reports failure
+constexpr uint32_t kProgressLost = 0xFFFFFFFFu;
 
 template <class Body>
 __device__ __forceinline__ void ptb_body(const typename Body::Args &args, const PtbCtl &c) {
   __shared__ uint32_t s_idx[2];
   const uint32_t worker = blockIdx.x;
-  // One lane reads flag and counter and broadcasts through LDS, so the exit decision is
-  // uniform over the workgroup.  Order as in the paper: check the flag, then fetch; a
-  // fetched index is always run.
-  //
-  // The word next to the flag says "grid exhausted": the worker whose fetch reaches the
-  // end of the grid sets it, and the others then leave without one more fetch-add.  The
-  // counter is one address that serves only ~88 M operations per second (loads included),
-  // so W failing fetches at the very end would add W x 11 ns to every kernel.
+  // One lane fetches and broadcasts through LDS, so the exit decision is uniform over the
+  // workgroup.  An index at or beyond `limit` means: grid exhausted, or a request folded
+  // into the counter; either way the worker leaves, and what it fetched before is done.
   for (uint32_t it = 0;; ++it) {
-    if (threadIdx.x == 0) {
-      const unsigned long long f = __hip_atomic_load(
-          reinterpret_cast<const unsigned long long *>(c.dev_flag), __ATOMIC_RELAXED,
-          __HIP_MEMORY_SCOPE_AGENT);
-      uint32_t first0 = kStop;
-      if ((uint32_t)f != c.epoch && (uint32_t)(f >> 32) != c.epoch) {
-        first0 = __hip_atomic_fetch_add(c.counter, c.chunk, __ATOMIC_RELAXED,
-                                        __HIP_MEMORY_SCOPE_AGENT) - c.counter_base;
-        if (first0 < c.limit && c.limit - first0 <= c.chunk)
-          __hip_atomic_store(c.dev_flag + 1, c.epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      }
-      s_idx[it & 1] = first0;
-    }
+    if (threadIdx.x == 0)
+      s_idx[it & 1] = __hip_atomic_fetch_add(c.counter, c.chunk, __ATOMIC_RELAXED,
+                                             __HIP_MEMORY_SCOPE_AGENT) - c.counter_base;
     __syncthreads();
     const uint32_t first = s_idx[it & 1];
     if (first >= c.limit) break;  // uniform across the workgroup
@@ -228,6 +271,8 @@ __device__ __forceinline__ void ptb_body(const typename Body::Args &args, const 
       // at a time; a body whose waves share no state across blocks does not need it
       if (Body::END_BARRIER) __syncthreads();
     }
+    // the first fetches of all workers cover what is left: a second one could only fail
+    if (c.single_pass) break;
   }
   // leave: the last worker of the segment publishes the progress to the host.
   // All of this is relaxed on purpose: an agent- or system-scope release here would make
@@ -240,11 +285,25 @@ __device__ __forceinline__ void ptb_body(const typename Body::Args &args, const 
   if (threadIdx.x == 0) {
     uint32_t old = __hip_atomic_fetch_add(c.exited, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (old + 1 == c.exit_target) {
-      uint32_t raw = __hip_atomic_load(c.counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      uint32_t ctr = raw - c.counter_base;
+      const uint32_t raw = __hip_atomic_load(c.counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      const uint32_t ctr = raw - c.counter_base;
       uint32_t progress = ctr < c.limit ? ctr : c.limit;
+      if (ctr & kPreemptStep) {
+        // a request was folded in: the progress is what the relay's fetch-and-add returned.
+        // The relay stores it right after that fetch-and-add, which has been performed
+        // (its effect is in the counter), so this wait is short and ends whatever the
+        // relay does next; the cap is a backstop that reports failure instead of hanging.
+        progress = kProgressLost;
+        for (uint32_t spin = 0; spin < kPreSpinCap; ++spin) {
+          const unsigned long long pre =
+              __hip_atomic_load(c.pre, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          if ((uint32_t)(pre >> 32) == c.epoch) { progress = (uint32_t)pre; break; }
+          __builtin_amdgcn_s_sleep(2);
+        }
+      }
       __hip_atomic_store(c.host_raw, raw, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
-      __hip_atomic_store(c.host_live, progress, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+      if (progress != kProgressLost)
+        __hip_atomic_store(c.host_live, progress, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
       asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // both acknowledged before the status
       __hip_atomic_store(c.host_status, ((unsigned long long)c.epoch << 32) | progress,
                          __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);

@@ -9,6 +9,8 @@
 
 #include <atomic>
 #include <chrono>
+#include <condition_variable>
+#include <deque>
 #include <map>
 #include <mutex>
 #include <new>
@@ -281,11 +283,23 @@ const KernelOps kOps[TALLY_K_COUNT] = {
 constexpr size_t kMaxArgs = 96;
 constexpr int kSlots = 64;
 constexpr int kMaxBeClients = 8;
-constexpr size_t kDevSlotBytes = 512;   // counter | dev_flag | exited, 128 B apart
-constexpr size_t kHostSlotBytes = 256;  // host_flag | status,live | slice_done
+constexpr size_t kDevSlotBytes = 512;   // counter | pre | exited, 128 B apart
+constexpr size_t kHostSlotBytes = 256;  // host_flag | status,live,raw,relay,relay_flags | slice_done
 constexpr size_t kCopySlotBytes = kFlagCopies * kFlagCopyStride * sizeof(uint32_t);
 
 enum JobKind { KIND_PTB = 0, KIND_SLICED = 1, KIND_NATIVE = 2 };
+
+// One kernel's profiling record.  Measurements are sums over real executions of the kernel
+// (each invocation measures one candidate once); the configuration is fixed when every
+// candidate has `runs` samples.
+typedef std::tuple<uint32_t, uint32_t, uint32_t, uint32_t, uint32_t> ProfileKey;
+struct ProfileEntry {
+  std::vector<tally_config> cands;
+  std::vector<double> sum_ms;
+  std::vector<uint32_t> samples;
+  int chosen = -1;
+  double threshold_ms = 0.0;   // the threshold `chosen` was selected under
+};
 
 constexpr uint32_t kStaticAttnMaxHeads = TALLY_ATTN_STATIC_MAX_HEADS;
 constexpr size_t kStaticAttnBytes =
@@ -315,6 +329,7 @@ struct tally_ctx {
   bool slot_used[kSlots];
   int next_slot;
   // device words of a slot are never reset: the host tracks their current values instead
+  // (slot_counter: the raw task counter as the slot's last job left it)
   uint32_t slot_counter[kSlots], slot_exited[kSlots], slot_epoch[kSlots];
   uint32_t *marker_host;     // pinned: [0] hi, [32] be (separate lines)
   uint32_t *marker_dev;
@@ -328,7 +343,10 @@ struct tally_ctx {
   void *static_attn_scratch; // this device's address of static_scratch
   int device;
   int live_jobs;
-  std::map<std::tuple<uint32_t, uint32_t, uint32_t, uint32_t, uint32_t>, tally_config> chosen;
+  // profile-guided configuration (Section 4.2): per (kernel, grid, block) the candidate
+  // table with its measurements, and the choice once every candidate has been measured
+  std::mutex profile_mu;
+  std::map<ProfileKey, ProfileEntry> profiles;
 };
 
 struct tally_job {
@@ -348,7 +366,9 @@ struct tally_job {
   uint32_t yield_ticks;      // the context's pause bound when the job was made
   uint32_t counter_base;     // raw counter value standing for task index 0
   uint32_t segments;         // launch segments so far
-  bool counter_dirty;        // counter overshot a stop_at limit and must be rewound
+  bool relay_pending;        // a relay of this job may still be running (its report is not in)
+  bool failed;               // the device could not report the progress of a preempted segment
+  std::atomic<uint32_t> request_word;  // what was last stored in the host's request word
   // sliced
   uint32_t slice_blocks, max_in_flight, next_off, issued, retired, segment;
   std::atomic<bool> stop_issuing;
@@ -357,7 +377,7 @@ struct tally_job {
   double preempt_latency_us;
 
   uint32_t *d_counter() { return (uint32_t *)(ctx->dev_pool + slot * kDevSlotBytes); }
-  uint32_t *d_flag() { return (uint32_t *)(ctx->dev_pool + slot * kDevSlotBytes + 128); }
+  unsigned long long *d_pre() { return (unsigned long long *)(ctx->dev_pool + slot * kDevSlotBytes + 128); }
   uint32_t *d_exited() { return (uint32_t *)(ctx->dev_pool + slot * kDevSlotBytes + 256); }
   unsigned char *h_base() { return ctx->host_pool + slot * kHostSlotBytes; }
   unsigned char *h_base_dev() { return ctx->host_pool_dev + slot * kHostSlotBytes; }
@@ -365,6 +385,8 @@ struct tally_job {
   unsigned long long *h_status() { return (unsigned long long *)(h_base() + 64); }
   uint32_t *h_live() { return (uint32_t *)(h_base() + 72); }
   uint32_t *h_raw() { return (uint32_t *)(h_base() + 76); }
+  unsigned long long *h_relay() { return (unsigned long long *)(h_base() + 80); }
+  uint32_t *h_relay_flags() { return (uint32_t *)(h_base() + 88); }
   uint32_t *h_slice_done() { return (uint32_t *)(h_base() + 128); }
 };
 
@@ -380,7 +402,8 @@ int check_desc(const tally_kernel_desc *d, const KernelOps **ops_out, tally_dim3
   if (d->grid.x != g.x || d->grid.y != g.y || d->grid.z != g.z || d->block.x != b.x ||
       d->block.y != b.y || d->block.z != b.z)
     return TALLY_ERR_INVALID_ARG;
-  if ((uint64_t)g.x * g.y * g.z > 0x7FFFFFFFull) return TALLY_ERR_INVALID_ARG;
+  // (task indices and a folded-in preemption request share one 32-bit word)
+  if ((uint64_t)g.x * g.y * g.z > 0x40000000ull) return TALLY_ERR_INVALID_ARG;
   *ops_out = ops;
   *grid = g;
   return TALLY_OK;
@@ -418,7 +441,9 @@ int new_job(tally_ctx *ctx, const tally_kernel_desc *desc, int kind, int coverag
   j->counter_base = ctx->slot_counter[slot];
   j->yield_ticks = ctx->yield_ticks;
   j->limit = j->total;
-  j->counter_dirty = false;
+  j->relay_pending = false;
+  j->failed = false;
+  j->request_word = 0;
   j->slice_blocks = j->max_in_flight = j->next_off = j->issued = j->retired = j->segment = 0;
   j->stop_issuing = false;
   j->t_preempt = 0.0;
@@ -442,29 +467,55 @@ int new_job(tally_ctx *ctx, const tally_kernel_desc *desc, int kind, int coverag
   return TALLY_OK;
 }
 
+// The relay of the job's last segment reports when it has ended and what the counter then
+// held.  Until that report is in, the relay may still fold a late request into the counter,
+// so neither a new segment nor a new job may use the slot's counter.  The relay ends within
+// microseconds of its workers (or after its 20 ms give-up bound when it ran before them).
+int settle_relay(tally_job *j) {
+  if (!j->relay_pending) return TALLY_OK;
+  for (uint64_t spins = 1;; ++spins) {
+    const unsigned long long r = __atomic_load_n(j->h_relay(), __ATOMIC_ACQUIRE);
+    if ((uint32_t)(r >> 32) == j->epoch) {
+      const uint32_t flags = __atomic_load_n(j->h_relay_flags(), __ATOMIC_RELAXED);
+      // a relay that gave up ended before its workers: their own report has the final value
+      const uint32_t raw = (flags & 1u) ? __atomic_load_n(j->h_raw(), __ATOMIC_RELAXED) : (uint32_t)r;
+      j->ctx->slot_counter[j->slot] = raw;
+      j->relay_pending = false;
+      return TALLY_OK;
+    }
+    if ((spins & 0xFFFFFu) == 0) {
+      hipError_t q = hipStreamQuery(j->ctl);
+      if (q != hipSuccess && q != hipErrorNotReady) { g_last_hip = (int)q; return TALLY_ERR_HIP; }
+    }
+  }
+}
+
+// Launch the workers (and their relay) for task indices [progress, limit).  Requires the
+// job's previous segment, if any, to have drained.
 int ptb_launch_segment(tally_job *j, uint32_t limit) {
   tally_ctx *ctx = j->ctx;
   const int slot = j->slot;
-  if (j->counter_dirty) {
-    uint32_t raw = j->counter_base + j->progress.load();
-    hipLaunchKernelGGL(set_word_kernel, dim3(1), dim3(64), 0, j->be, j->d_counter(), raw);
-    HIPCHK(hipGetLastError());
-    // the relay below runs on another stream and mirrors the counter to the host: it must
-    // not see the value from before the rewind (the job is drained, the stream is idle)
-    HIPCHK(hipStreamSynchronize(j->be));
-    ctx->slot_counter[slot] = raw;
-    j->counter_dirty = false;
-  }
+  int rc = settle_relay(j);
+  if (rc) return rc;
+  const uint32_t start = j->progress.load();
+  // The counter is never rewound: failed fetches of the last segment (after a request, or
+  // beyond a stop_at limit) have advanced it, so the value that stands for task index 0
+  // moves instead, such that the next index handed out is `start` again.
+  j->counter_base = ctx->slot_counter[slot] - start;
   j->epoch = ctx->slot_epoch[slot] + 1;
   j->limit = limit < j->total ? limit : j->total;
+  __atomic_store_n(j->h_flag(), 0u, __ATOMIC_RELEASE);   // no request stands against the new segment
+  j->request_word = 0;
   PtbCtl c;
   c.counter = j->d_counter();
-  c.dev_flag = j->d_flag();
   c.exited = j->d_exited();
+  c.pre = j->d_pre();
   c.host_flag = (const uint32_t *)j->h_base_dev();
   c.host_status = (unsigned long long *)(j->h_base_dev() + 64);
   c.host_live = (uint32_t *)(j->h_base_dev() + 72);
   c.host_raw = (uint32_t *)(j->h_base_dev() + 76);
+  c.host_relay = (unsigned long long *)(j->h_base_dev() + 80);
+  c.host_relay_flags = (uint32_t *)(j->h_base_dev() + 88);
   c.cover = j->cover;
   c.total = j->total;
   c.limit = j->limit;
@@ -473,6 +524,8 @@ int ptb_launch_segment(tally_job *j, uint32_t limit) {
   c.counter_base = j->counter_base;
   c.workers = j->workers;
   c.chunk = j->chunk;
+  c.single_pass = (j->limit > start ? (uint64_t)(j->limit - start) : 0ull) <=
+                          (uint64_t)j->chunk * j->workers ? 1u : 0u;
   c.segment = j->segments;
   c.gx = j->grid.x;
   c.gy = j->grid.y;
@@ -484,13 +537,14 @@ int ptb_launch_segment(tally_job *j, uint32_t limit) {
   // first), and without the relay a request is never seen.  Its exit depends only on the
   // slot's exit counter reaching the target, so it may start early; where kernels are run
   // strictly one at a time (counter collection under a profiler) it gives up when no
-  // worker has shown up for a while, and that one launch cannot be preempted.
+  // worker has shown up for a while, and a request raised after that goes unseen.
   hipLaunchKernelGGL(relay_kernel, dim3(1), dim3(64), 0, j->ctl, c);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) {  // nothing was enqueued: the slot's bookkeeping is unchanged
     g_last_hip = (int)e;
     return TALLY_ERR_HIP;
   }
+  j->relay_pending = true;
   e = j->ops->ptb(j->be, j->args, c);
   ctx->slot_epoch[slot] = j->epoch;
   ctx->slot_exited[slot] = c.exit_target;
@@ -535,11 +589,13 @@ void refresh(tally_job *j) {
     unsigned long long st = __atomic_load_n(j->h_status(), __ATOMIC_ACQUIRE);
     if ((uint32_t)(st >> 32) == j->epoch) {
       uint32_t p = (uint32_t)st;
+      if (p == kProgressLost) {   // the device could not tell: keep the last known progress
+        j->failed = true;
+        p = j->progress.load();
+      }
       j->progress = p;
-      j->ctx->slot_counter[j->slot] = __atomic_load_n(j->h_raw(), __ATOMIC_RELAXED);
       double tp = j->t_preempt.load();
       j->preempt_latency_us = (tp > 0.0 && p < j->total) ? now_us() - tp : -1.0;
-      if (j->limit < j->total) j->counter_dirty = true;
       j->state = (p >= j->total) ? TALLY_JOB_COMPLETE : TALLY_JOB_STOPPED;
     } else {
       uint32_t live = __atomic_load_n(j->h_live(), __ATOMIC_RELAXED);
@@ -816,29 +872,30 @@ int tally_max_workers(tally_ctx *ctx, const tally_kernel_desc *desc, uint32_t *m
   return TALLY_OK;
 }
 
-int tally_preempt(tally_job *job) {
+namespace {
+int preempt_impl(tally_job *job, bool pause) {
   if (!job) return TALLY_ERR_INVALID_ARG;
   if (job->state.load() != TALLY_JOB_RUNNING) return TALLY_OK;
   if (job->t_preempt.load() == 0.0) job->t_preempt = now_us();
-  if (job->kind == KIND_PTB)
-    __atomic_store_n(job->h_flag(), job->epoch, __ATOMIC_RELEASE);
-  else if (job->kind == KIND_SLICED)
+  if (job->kind == KIND_PTB) {
+    const uint32_t word = pause ? job->epoch : (job->epoch | kNoPauseBit);
+    job->request_word = word;
+    __atomic_store_n(job->h_flag(), word, __ATOMIC_RELEASE);
+  } else if (job->kind == KIND_SLICED) {
     job->stop_issuing = true;
+  }
   return TALLY_OK;
 }
+}  // namespace
+
+int tally_preempt(tally_job *job) { return preempt_impl(job, false); }
+int tally_preempt_pausing(tally_job *job) { return preempt_impl(job, true); }
 
 int tally_resume_until(tally_job *job, uint64_t stop_at) {
   if (!job) return TALLY_ERR_INVALID_ARG;
   refresh(job);
   int st = job->state.load();
   if (st == TALLY_JOB_COMPLETE) return TALLY_OK;
-  if (st == TALLY_JOB_RUNNING && job->kind == KIND_PTB && job->t_preempt.load() != 0.0) {
-    // requested but not drained yet: withdraw the request; workers pausing inside a
-    // block go on, those that already left stay away until the next launch segment
-    __atomic_store_n(job->h_flag(), 0u, __ATOMIC_RELEASE);
-    job->t_preempt = 0.0;
-    return TALLY_OK;
-  }
   if (st != TALLY_JOB_STOPPED) return TALLY_ERR_BAD_STATE;
   if (job->kind == KIND_PTB) {
     if (stop_at < job->progress.load()) return TALLY_ERR_INVALID_ARG;
@@ -852,6 +909,20 @@ int tally_resume_until(tally_job *job, uint64_t stop_at) {
 }
 
 int tally_resume(tally_job *job) { return tally_resume_until(job, ~0ull); }
+
+int tally_end_pause(tally_job *job) {
+  if (!job) return TALLY_ERR_INVALID_ARG;
+  // Workers pausing inside a block go on and finish it.  The request itself is in the task
+  // counter and cannot be taken back: every worker still leaves at its next block boundary
+  // and the job then needs a resume like any preempted one.  The time of the request is
+  // kept: the drain that follows is the preemption's.
+  const uint32_t w = job->request_word.load();
+  if (job->kind == KIND_PTB && w != 0 && !(w & kNoPauseBit) && job->state.load() == TALLY_JOB_RUNNING) {
+    job->request_word = w | kNoPauseBit;
+    __atomic_store_n(job->h_flag(), w | kNoPauseBit, __ATOMIC_RELEASE);
+  }
+  return TALLY_OK;
+}
 
 int tally_progress(tally_job *job, uint64_t *done_blocks, uint64_t *total_blocks, int *state) {
   if (!job) return TALLY_ERR_INVALID_ARG;
@@ -881,6 +952,7 @@ int tally_wait(tally_job *job, int *state) {
     int rc = tally_pump(job);
     if (rc) return rc;
     int st = job->state.load();
+    if (job->failed) return TALLY_ERR_BAD_STATE;
     if (st == TALLY_JOB_STOPPED || st == TALLY_JOB_COMPLETE) break;
     // a kernel that failed after enqueue would leave the status word unwritten for ever
     if ((spins & 0xFFFFu) == 0) {
@@ -904,7 +976,12 @@ int tally_job_free(tally_job *job) {
     (void)hipStreamSynchronize(job->be);
     (void)hipFree(job->cover);
   }
-  if (job->kind == KIND_PTB) refresh(job);  // learn the counter's final value for the slot
+  if (job->kind == KIND_PTB) {
+    // the slot's counter may not be handed to another job before this job's last relay has
+    // ended (it could still fold a late request in) and has reported the counter's value
+    refresh(job);
+    (void)settle_relay(job);
+  }
   ctx->slot_used[job->slot] = false;
   ctx->live_jobs--;
   delete job;
@@ -1004,6 +1081,92 @@ int tally_select_config(const tally_config *c, uint32_t n, double threshold_ms) 
   return best;
 }
 
+}  // extern "C"
+
+namespace {
+
+ProfileKey profile_key(const tally_kernel_desc *d) {
+  return std::make_tuple(d->kernel_id, d->grid.x, d->grid.y, d->grid.z, d->block.x);
+}
+
+// Turnaround estimate of one measured candidate (Section 4.2).
+void fill_turnaround(tally_ctx *ctx, const KernelOps *ops, const void *args, uint64_t total,
+                     tally_config *c) {
+  if (c->kind == 0) {
+    c->turnaround_ms = (float)tally_ptb_turnaround_ms(c->latency_ms, c->param, c->chunk ? c->chunk : 1, total);
+    // a body that pauses inside its blocks hands the execution units over after a share
+    // of ONE block, whatever the chunk: Eq. 1 with chunk 1, times that share
+    const double share = ctx->yield_ticks ? ops->pause_fraction(args) : 1.0;
+    if (share < 1.0)
+      c->turnaround_ms = (float)(tally_ptb_turnaround_ms(c->latency_ms, c->param, 1, total) * share);
+  } else {
+    // one slice's time, times the number of slices that may be enqueued at once
+    uint64_t slices = (total + c->param - 1) / c->param;
+    uint64_t inflight = c->chunk ? c->chunk : 1;
+    if (inflight > slices) inflight = slices;
+    c->turnaround_ms = (float)(c->latency_ms / (double)slices * (double)inflight);
+  }
+}
+
+// The candidate set of Section 4.2: persistent-worker counts that are multiples of the
+// compute-unit count and fit (every worker resident), each with 1, 4 and 16 task indices per
+// fetch where the grid has that many blocks per worker; slices of 1/2 ... 1/256 of the grid.
+uint32_t candidate_configs(tally_ctx *ctx, uint32_t kernel_id, uint64_t total, tally_config *out,
+                           uint32_t cap) {
+  uint32_t n = 0;
+  auto push = [&](uint32_t kind, uint32_t param, uint32_t chunk) {
+    for (uint32_t i = 0; i < n; ++i)
+      if (out[i].kind == kind && out[i].param == param && out[i].chunk == chunk) return;
+    if (n < cap) out[n++] = tally_config{kind, param, chunk, 0.f, 0.f};
+  };
+  const uint32_t maxw = ctx->max_workers[kernel_id];
+  for (uint32_t w = ctx->num_cus; w <= maxw; w += ctx->num_cus) {
+    const uint32_t workers = (uint64_t)w < total ? w : (uint32_t)total;
+    static const uint32_t chunks[3] = {1, 4, 16};
+    for (uint32_t ch : chunks)
+      if (ch == 1 || (uint64_t)workers * ch <= total) push(0, workers, ch);
+    if ((uint64_t)w >= total) break;
+  }
+  for (uint32_t sh = 1; sh <= 8; ++sh) {
+    const uint64_t blocks = total >> sh;
+    push(1, (uint32_t)(blocks ? blocks : 1), 1);
+  }
+  return n;
+}
+
+// Record one measurement; when the table is complete, choose.  Returns true when the
+// configuration became fixed by this call.
+bool profile_record(tally_ctx *ctx, ProfileEntry &e, uint32_t idx, double ms, uint32_t runs,
+                    double threshold_ms, const KernelOps *ops, const void *args, uint64_t total) {
+  e.sum_ms[idx] += ms;
+  e.samples[idx] += 1;
+  for (uint32_t i = 0; i < e.cands.size(); ++i)
+    if (e.samples[i] < runs) return false;
+  for (uint32_t i = 0; i < e.cands.size(); ++i) {
+    e.cands[i].latency_ms = (float)(e.sum_ms[i] / e.samples[i]);
+    fill_turnaround(ctx, ops, args, total, &e.cands[i]);
+  }
+  e.chosen = tally_select_config(e.cands.data(), (uint32_t)e.cands.size(), threshold_ms);
+  e.threshold_ms = threshold_ms;
+  return true;
+}
+
+}  // namespace
+
+extern "C" {
+
+int tally_candidate_configs(tally_ctx *ctx, const tally_kernel_desc *desc, tally_config *out,
+                            uint32_t cap, uint32_t *n) {
+  if (!ctx || !desc || !out || !n || cap == 0) return TALLY_ERR_INVALID_ARG;
+  const KernelOps *ops;
+  tally_dim3 g;
+  int rc = check_desc(desc, &ops, &g);
+  if (rc) return rc;
+  if (!ops->transformable) return TALLY_ERR_UNSUPPORTED;
+  *n = candidate_configs(ctx, desc->kernel_id, (uint64_t)g.x * g.y * g.z, out, cap);
+  return TALLY_OK;
+}
+
 int tally_profile(tally_ctx *ctx, const tally_kernel_desc *desc, tally_config *cands, uint32_t n,
                   uint32_t runs, double threshold_ms, uint32_t *chosen) {
   if (!ctx || !desc || !cands || n == 0 || runs == 0) return TALLY_ERR_INVALID_ARG;
@@ -1012,9 +1175,12 @@ int tally_profile(tally_ctx *ctx, const tally_kernel_desc *desc, tally_config *c
   int rc = check_desc(desc, &ops, &g);
   if (rc) return rc;
   const uint64_t total = (uint64_t)g.x * g.y * g.z;
+  ProfileEntry e;
+  e.cands.assign(cands, cands + n);
+  e.sum_ms.assign(n, 0.0);
+  e.samples.assign(n, 0);
   for (uint32_t i = 0; i < n; ++i) {
     if (cands[i].kind > 1 || cands[i].param == 0) return TALLY_ERR_INVALID_ARG;
-    double sum = 0.0;
     for (uint32_t r = 0; r <= runs; ++r) {  // run 0 is the warm-up
       tally_be_item it = {desc, cands[i]};
       tally_job *j;
@@ -1027,39 +1193,49 @@ int tally_profile(tally_ctx *ctx, const tally_kernel_desc *desc, tally_config *c
       double t1 = now_us();
       tally_job_free(j);
       if (rc) return rc;
-      if (r > 0) sum += t1 - t0;
-    }
-    cands[i].latency_ms = (float)(sum / runs / 1000.0);
-    if (cands[i].kind == 0) {
-      cands[i].turnaround_ms = (float)tally_ptb_turnaround_ms(
-          cands[i].latency_ms, cands[i].param, cands[i].chunk ? cands[i].chunk : 1, total);
-      // a body that pauses inside its blocks hands the execution units over after a share
-      // of ONE block, whatever the chunk: Eq. 1 with chunk 1, times that share
-      const double share = ctx->yield_ticks ? ops->pause_fraction(desc->args) : 1.0;
-      if (share < 1.0)
-        cands[i].turnaround_ms = (float)(tally_ptb_turnaround_ms(cands[i].latency_ms, cands[i].param,
-                                                                 1, total) * share);
-    } else {
-      // one slice's time, times the number of slices that may be enqueued at once
-      uint64_t slices = (total + cands[i].param - 1) / cands[i].param;
-      uint64_t inflight = cands[i].chunk ? cands[i].chunk : 1;
-      if (inflight > slices) inflight = slices;
-      cands[i].turnaround_ms = (float)(cands[i].latency_ms / (double)slices * (double)inflight);
+      if (r > 0) profile_record(ctx, e, i, (t1 - t0) / 1000.0, runs, threshold_ms, ops, desc->args, total);
     }
   }
-  int pick = tally_select_config(cands, n, threshold_ms);
-  if (pick < 0) return pick;
-  ctx->chosen[std::make_tuple(desc->kernel_id, g.x, g.y, g.z, desc->block.x)] = cands[pick];
-  if (chosen) *chosen = (uint32_t)pick;
+  if (e.chosen < 0) return e.chosen;
+  for (uint32_t i = 0; i < n; ++i) cands[i] = e.cands[i];
+  if (chosen) *chosen = (uint32_t)e.chosen;
+  std::lock_guard<std::mutex> lk(ctx->profile_mu);
+  ctx->profiles[profile_key(desc)] = e;
   return TALLY_OK;
 }
 
 int tally_lookup_config(tally_ctx *ctx, const tally_kernel_desc *desc, tally_config *out) {
   if (!ctx || !desc || !out) return TALLY_ERR_INVALID_ARG;
-  auto it = ctx->chosen.find(
-      std::make_tuple(desc->kernel_id, desc->grid.x, desc->grid.y, desc->grid.z, desc->block.x));
-  if (it == ctx->chosen.end()) return TALLY_ERR_BAD_STATE;
-  *out = it->second;
+  std::lock_guard<std::mutex> lk(ctx->profile_mu);
+  auto it = ctx->profiles.find(profile_key(desc));
+  if (it == ctx->profiles.end() || it->second.chosen < 0) return TALLY_ERR_BAD_STATE;
+  *out = it->second.cands[it->second.chosen];
+  return TALLY_OK;
+}
+
+int tally_profile_table(tally_ctx *ctx, const tally_kernel_desc *desc, tally_config *out, uint32_t cap,
+                        uint32_t *n, uint32_t *samples, int *chosen) {
+  if (!ctx || !desc || !n) return TALLY_ERR_INVALID_ARG;
+  std::lock_guard<std::mutex> lk(ctx->profile_mu);
+  auto it = ctx->profiles.find(profile_key(desc));
+  if (it == ctx->profiles.end()) { *n = 0; if (chosen) *chosen = -1; return TALLY_OK; }
+  const ProfileEntry &e = it->second;
+  *n = (uint32_t)e.cands.size();
+  for (uint32_t i = 0; i < *n && i < cap; ++i) {
+    if (out) {
+      out[i] = e.cands[i];
+      if (e.samples[i]) out[i].latency_ms = (float)(e.sum_ms[i] / e.samples[i]);
+    }
+    if (samples) samples[i] = e.samples[i];
+  }
+  if (chosen) *chosen = e.chosen;
+  return TALLY_OK;
+}
+
+int tally_profile_reset(tally_ctx *ctx) {
+  if (!ctx) return TALLY_ERR_INVALID_ARG;
+  std::lock_guard<std::mutex> lk(ctx->profile_mu);
+  ctx->profiles.clear();
   return TALLY_OK;
 }
 
@@ -1094,55 +1270,98 @@ int launch_be_item(tally_ctx *ctx, const tally_be_item *it, tally_job **out) {
 }  // namespace
 
 // --------------------------------------------------------------- priority scheduling loop
-// The loop of Figure 4 split over two host threads, one per client class, because a
-// launch call cannot be interrupted: a single thread that is inside the best-effort
-// client's launch when a high-priority kernel arrives delays it by that call.
-//   high-priority thread (the caller): on arrival, raise the preemption flag of the
-//     running best-effort segment, launch the kernels in their original form, then watch
-//     for the completion marker.  While a request is in flight `hi_active` is set.
-//   best-effort thread: launch / resume / issue the next slice only while `hi_active`
-//     is clear; account for completed kernels and preemption latencies.
+// The loop of Figure 4, built on the public calls above (launch, preempt, resume, pump,
+// progress), split over two host threads, one per client class, because a launch call cannot
+// be interrupted: a single thread that is inside the best-effort client's launch when a
+// high-priority kernel arrives delays it by that call.
+//   high-priority client (the caller's thread, tally_sched_submit_hi / tally_sched_poll):
+//     on arrival, preempt the running best-effort kernels, launch the request's kernels in
+//     their original form, then watch for the completion marker.  While a request is in
+//     flight `hi_active` is set.
+//   best-effort clients (the scheduler's own thread): fetch the next kernel of each client,
+//     look its configuration up or profile the next unmeasured candidate with this very
+//     invocation, launch / resume / issue the next slice only while `hi_active` is clear;
+//     account for completed kernels and preemption latencies.  The thread sleeps while no
+//     client has work.
 namespace {
 
-struct SchedShared {
-  std::atomic<bool> hi_active{false};
-  std::atomic<bool> stop{false};
-  // per best-effort client, slot and epoch of its persistent-worker segment now running:
-  // what the high-priority thread needs in order to raise the flag without touching the job
-  std::atomic<uint64_t> ptb_token[kMaxBeClients];
-  std::atomic<double> t_preempt{0.0};
-  std::atomic<int> rc{TALLY_OK};
-  SchedShared() { for (auto &t : ptb_token) t = 0; }
+constexpr uint32_t kCfgAuto = 3;   // tally_config.kind: let the profiler choose
+constexpr uint32_t kPreemptRing = 4096;
+
+struct BeWork {
+  tally_kernel_desc desc;
+  alignas(16) unsigned char args[kMaxArgs];
+  tally_config config;     // kind kCfgAuto: profile-guided
+  bool loop;               // goes to the back of its client's queue when it completes
+  bool last_of_step;       // completing it ends one step of a looping client
 };
 
-constexpr uint64_t kNoToken = 0;
-
-// One best-effort client: its own step of kernels, its own stream pair, one kernel in
+// One best-effort client: its own queue of kernels, its own stream pair, one kernel in
 // flight at a time (Figure 4 visits every best-effort client on every pass).
 struct BeClient {
-  uint32_t first = 0, count = 0, idx = 0;  // its items in run->be_items
+  std::deque<BeWork> queue;      // guarded by tally_sched::mu
   hipStream_t be = nullptr, ctl = nullptr;
+  // `job` and the fields below it are written by the best-effort thread under `lock` and
+  // read by the high-priority client under `lock`
+  std::atomic_flag lock = ATOMIC_FLAG_INIT;
   tally_job *job = nullptr;
-  bool preempt_seen = false;  // a preemption request was raised against the current segment
-  uint64_t kernels_done = 0, steps_done = 0;
-  // admission among best-effort clients: what the client's resident workgroups occupy on
-  // one compute unit (zero while it has none), and its place in the queue of clients
-  // that want to put workgroups on the GPU (0 = not asking)
-  uint32_t lds = 0, waves = 0, regs = 0;
-  uint64_t ticket = 0;
+  BeWork cur;                    // the kernel in flight (or stopped)
+  bool has_cur = false;
+  int profiling = -1;            // candidate index this invocation measures, or -1
+  double t_launch = 0.0;
+  bool preempt_seen = false;     // a preemption request was raised against the current segment
+  uint32_t dl = 0, dw = 0, dr = 0;   // per-compute-unit demand of its resident workgroups
+  uint64_t ticket = 0;           // place in the queue of clients waiting for room (0: not waiting)
+  std::atomic<uint64_t> kernels_done{0}, steps_done{0};
 };
 
-// Per-compute-unit demand of the workgroups a best-effort item puts on the GPU at once
+struct SpinGuard {
+  std::atomic_flag &f;
+  explicit SpinGuard(std::atomic_flag &fl) : f(fl) { while (f.test_and_set(std::memory_order_acquire)) {} }
+  ~SpinGuard() { f.clear(std::memory_order_release); }
+};
+
+}  // namespace
+
+struct tally_sched {
+  tally_ctx *ctx;
+  tally_sched_opts opts;
+  double threshold_ms;
+  uint32_t profile_runs;
+  uint32_t n_clients;
+  BeClient clients[kMaxBeClients];
+  std::mutex mu;                      // queues, wake-ups
+  std::condition_variable cv;
+  std::thread be_thread;
+  std::atomic<bool> hi_active{false}, stop{false}, be_enabled{true};
+  std::atomic<double> t_preempt{0.0};
+  std::atomic<int> rc{TALLY_OK};
+  // the high-priority request in flight: largest demand of one of its workgroups
+  uint32_t hl = 0, hw = 0, hr = 0;
+  bool hi_inflight = false;
+  uint32_t hi_seq = 0;
+  uint64_t hi_done = 0;
+  // statistics
+  std::atomic<uint64_t> n_preempts{0}, profile_samples{0}, configs_fixed{0};
+  std::mutex pre_mu;
+  std::vector<double> pre_ring;
+  uint64_t next_ticket = 0;
+};
+
+namespace {
+
+// Per-compute-unit demand of the workgroups a best-effort kernel puts on the GPU at once
 // (all its workers; one slice; the whole grid for a native launch), spread evenly.
-int item_demand(tally_ctx *ctx, const tally_be_item *it, uint32_t *lds, uint32_t *waves, uint32_t *regs) {
+int item_demand(tally_ctx *ctx, const tally_kernel_desc *desc, const tally_config &cfg, uint32_t *lds,
+                uint32_t *waves, uint32_t *regs) {
   const KernelOps *ops;
   tally_dim3 g;
-  int rc = check_desc(it->kernel, &ops, &g);
+  int rc = check_desc(desc, &ops, &g);
   if (rc) return rc;
-  const uint32_t *ft = ctx->foot[it->kernel->kernel_id][it->config.kind == 0 ? 0 : 1];
+  const uint32_t *ft = ctx->foot[desc->kernel_id][cfg.kind == 0 ? 0 : 1];
   const uint32_t l = ft[0], w = ft[1], r = ft[2];
   const uint64_t total = (uint64_t)g.x * g.y * g.z;
-  uint64_t groups = it->config.kind == 2 ? total : it->config.param;
+  uint64_t groups = cfg.kind == 2 ? total : cfg.param;
   if (groups > total) groups = total;
   const uint64_t per_cu = (groups + ctx->num_cus - 1) / ctx->num_cus;
   const uint64_t cap = 64;  // beyond any compute unit's capacity: keeps the products small
@@ -1153,146 +1372,418 @@ int item_demand(tally_ctx *ctx, const tally_be_item *it, uint32_t *lds, uint32_t
   return TALLY_OK;
 }
 
+// lookup_launch_config() / launch_and_profile() of Figure 4 for one fetched kernel: the
+// configuration to launch this invocation with, and which candidate (if any) the
+// invocation measures.  One unmeasured candidate is profiled per real invocation; once
+// every candidate has its samples the choice is made and kept (Section 4.2).
+int choose_config(tally_sched *s, const BeWork &w, tally_config *cfg, int *profiling) {
+  *profiling = -1;
+  if (w.config.kind != kCfgAuto) { *cfg = w.config; return TALLY_OK; }
+  tally_ctx *ctx = s->ctx;
+  std::lock_guard<std::mutex> lk(ctx->profile_mu);
+  ProfileEntry &e = ctx->profiles[profile_key(&w.desc)];
+  if (e.cands.empty()) {
+    tally_config tmp[64];
+    const uint64_t total = (uint64_t)w.desc.grid.x * w.desc.grid.y * w.desc.grid.z;
+    uint32_t n = candidate_configs(ctx, w.desc.kernel_id, total, tmp, 64);
+    if (n == 0) return TALLY_ERR_UNSUPPORTED;
+    e.cands.assign(tmp, tmp + n);
+    e.sum_ms.assign(n, 0.0);
+    e.samples.assign(n, 0);
+  }
+  if (e.chosen >= 0) {
+    if (e.threshold_ms != s->threshold_ms) {   // the threshold moved: choose again from the table
+      e.chosen = tally_select_config(e.cands.data(), (uint32_t)e.cands.size(), s->threshold_ms);
+      e.threshold_ms = s->threshold_ms;
+    }
+    *cfg = e.cands[e.chosen];
+    return TALLY_OK;
+  }
+  for (uint32_t i = 0; i < e.cands.size(); ++i)
+    if (e.samples[i] < s->profile_runs) {
+      *cfg = e.cands[i];
+      *profiling = (int)i;
+      return TALLY_OK;
+    }
+  return TALLY_ERR_BAD_STATE;  // unreachable: a full table has a choice
+}
 
-void be_thread_main(tally_ctx *ctx, tally_sched_run_t *run, SchedShared *sh, BeClient *clients,
-                    uint32_t n_clients, const std::vector<uint8_t> *pause_ok, double t0, double t_end) {
+void be_thread_main(tally_sched *s) {
+  tally_ctx *ctx = s->ctx;
   int rc = TALLY_OK;
+  if (hipSetDevice(ctx->device) != hipSuccess) { s->rc = TALLY_ERR_HIP; return; }
   // A kernel is put on the GPU only if all the workgroups it brings fit beside the
   // best-effort workgroups already resident: a dispatch that waits for resources blocks
   // its hardware pipe for every queue mapped to that pipe, the high-priority queue
   // possibly among them (two 128 KB-LDS GEMMs launched together held high-priority
   // kernels back for milliseconds).  Clients that have to wait are served first come,
   // first served.  A client with the GPU to itself is always admitted.
-  uint64_t next_ticket = 0;
-  auto admit = [&](uint32_t c, const tally_be_item *it) -> bool {
-    BeClient &cl = clients[c];
-    if (cl.ticket == 0) cl.ticket = ++next_ticket;
+  auto admit = [&](uint32_t c, uint32_t l, uint32_t w, uint32_t r) -> bool {
+    BeClient &cl = s->clients[c];
+    if (cl.ticket == 0) cl.ticket = ++s->next_ticket;
     uint32_t lds = 0, waves = 0, regs = 0, others = 0;
-    for (uint32_t o = 0; o < n_clients; ++o) {
+    for (uint32_t o = 0; o < s->n_clients; ++o) {
       if (o == c) continue;
-      if (clients[o].ticket != 0 && clients[o].ticket < cl.ticket) return false;
-      if (clients[o].waves) others++;
-      lds += clients[o].lds;
-      waves += clients[o].waves;
-      regs += clients[o].regs;
+      const BeClient &oc = s->clients[o];
+      if (oc.ticket != 0 && oc.ticket < cl.ticket) return false;
+      if (oc.dw) others++;
+      lds += oc.dl;
+      waves += oc.dw;
+      regs += oc.dr;
     }
-    uint32_t l, w, r;
-    if (item_demand(ctx, it, &l, &w, &r) != TALLY_OK) return true;  // the launch reports it
     // (one wave slot and 32 registers are kept back for the newcomer's relay)
     if (others && (lds + l > ctx->lds_per_cu || waves + w > 31u || regs + r > 480u)) return false;
-    cl.lds = l;
-    cl.waves = w;
-    cl.regs = r;
+    SpinGuard g(cl.lock);
+    cl.dl = l; cl.dw = w; cl.dr = r;
     cl.ticket = 0;
     return true;
   };
-  auto vacate = [&](BeClient &cl) { cl.lds = cl.waves = cl.regs = 0; };
-  if (hipSetDevice(ctx->device) != hipSuccess) {
-    sh->rc = TALLY_ERR_HIP;
-    return;
-  }
-  auto publish = [&](uint32_t c, tally_job *j) {
-    if (j && j->kind == KIND_PTB && j->state.load() == TALLY_JOB_RUNNING)
-      sh->ptb_token[c] = ((uint64_t)(j->slot + 1) << 32) | j->epoch;
-    else
-      sh->ptb_token[c] = kNoToken;
+  auto vacate = [&](BeClient &cl) { SpinGuard g(cl.lock); cl.dl = cl.dw = cl.dr = 0; };
+  auto set_job = [&](BeClient &cl, tally_job *j) { SpinGuard g(cl.lock); cl.job = j; };
+  auto note_preempt = [&](double us) {
+    s->n_preempts++;
+    std::lock_guard<std::mutex> lk(s->pre_mu);
+    if (s->pre_ring.size() < kPreemptRing) s->pre_ring.push_back(us);
   };
-  bool done = false;
-  while (!done && rc == TALLY_OK) {
-    uint32_t idle = 0;
-    for (uint32_t c = 0; c < n_clients && rc == TALLY_OK; ++c) {
-      BeClient &cl = clients[c];
-      tally_job *&be = cl.job;
-      const double now = now_us() - t0;
-      const bool closing = sh->stop.load() || (run->n_arrivals == 0 && now >= t_end);
-      const bool hold = run->policy != 2 && sh->hi_active.load();
-      if (be) {
+  auto finish = [&](BeClient &cl, bool completed) {
+    tally_job *j = cl.job;
+    if (completed && cl.profiling >= 0 && j->segments <= 1 && j->segment == 0 && !cl.preempt_seen) {
+      // this invocation was the measurement of one candidate (and was not disturbed)
+      const KernelOps *ops = j->ops;
+      std::lock_guard<std::mutex> lk(ctx->profile_mu);
+      ProfileEntry &e = ctx->profiles[profile_key(&cl.cur.desc)];
+      if (e.chosen < 0 && (size_t)cl.profiling < e.cands.size()) {
+        s->profile_samples++;
+        if (profile_record(ctx, e, (uint32_t)cl.profiling, (now_us() - cl.t_launch) / 1000.0,
+                           s->profile_runs, s->threshold_ms, ops, cl.cur.args, j->total))
+          s->configs_fixed++;
+      }
+    }
+    set_job(cl, nullptr);
+    tally_job_free(j);
+    vacate(cl);
+    cl.preempt_seen = false;
+    cl.profiling = -1;
+    if (completed) {
+      cl.kernels_done++;
+      if (cl.cur.last_of_step) cl.steps_done++;
+      if (cl.cur.loop) {
+        std::lock_guard<std::mutex> lk(s->mu);
+        cl.queue.push_back(cl.cur);
+      }
+    }
+    cl.has_cur = false;
+  };
+
+  while (rc == TALLY_OK) {
+    const bool stopping = s->stop.load();
+    uint32_t busy = 0;
+    for (uint32_t c = 0; c < s->n_clients && rc == TALLY_OK; ++c) {
+      BeClient &cl = s->clients[c];
+      const bool closing = stopping || !s->be_enabled.load();
+      const bool hold = s->opts.policy != 2 && s->hi_active.load();
+      if (cl.job) {
+        tally_job *be = cl.job;
+        busy++;
         if (hold && !cl.preempt_seen && be->state.load() == TALLY_JOB_RUNNING) {
-          // the other thread raised the flag (persistent workers); for the other kinds
-          // "preempt" means that nothing further is issued until the request is done
+          // the high-priority client raised the request (persistent workers); for the other
+          // kinds "preempt" means that nothing further is issued until the request is done
           cl.preempt_seen = true;
-          if (be->t_preempt.load() == 0.0) be->t_preempt = sh->t_preempt.load();
+          if (be->t_preempt.load() == 0.0) be->t_preempt = s->t_preempt.load();
           if (be->kind == KIND_SLICED) be->stop_issuing = true;
         }
-        refresh(be);
-        int st = be->state.load();
-        if (st != TALLY_JOB_RUNNING) publish(c, nullptr);
-        if (st == TALLY_JOB_RUNNING && !hold && cl.preempt_seen && be->kind == KIND_PTB) {
-          // the request is over and the job has not drained (its workers sit inside long
-          // blocks, pausing): withdraw the flag instead of waiting for a drain and relaunch
-          (void)tally_resume(be);
-          cl.preempt_seen = false;
-        }
-        if (st != TALLY_JOB_RUNNING) vacate(cl);
+        rc = tally_pump(be);   // refresh; a sliced job also issues its next slice unless stopped
+        if (rc) break;
+        if (be->failed) { rc = TALLY_ERR_BAD_STATE; break; }
+        const int st = be->state.load();
         if (st == TALLY_JOB_COMPLETE) {
-          tally_job_free(be);
-          be = nullptr;
-          cl.preempt_seen = false;
-          cl.kernels_done++;
-          if (++cl.idx == cl.count) { cl.idx = 0; cl.steps_done++; }
+          finish(cl, true);
         } else if (st == TALLY_JOB_STOPPED) {
-          if (cl.preempt_seen && be->preempt_latency_us >= 0.0) {
-            if (run->preempt_latency_us && run->n_preempts < run->preempt_cap)
-              run->preempt_latency_us[run->n_preempts] = be->preempt_latency_us;
-            run->n_preempts++;
-          }
+          vacate(cl);
+          if (cl.preempt_seen && be->preempt_latency_us >= 0.0) note_preempt(be->preempt_latency_us);
           cl.preempt_seen = false;
-          if (closing) {
-            tally_job_free(be);
-            be = nullptr;
-          } else if (!hold && admit(c, &run->be_items[cl.first + cl.idx])) {
-            rc = tally_resume(be);
-            if (rc) break;
-            publish(c, be);
-            if (run->policy != 2 && sh->hi_active.load()) (void)tally_preempt(be);
+          if (stopping) {
+            finish(cl, false);
+          } else if (closing) {
+            // best-effort work is switched off: the kernel stays stopped where it is
+          } else if (!hold) {
+            uint32_t l = 0, w = 0, r = 0;
+            tally_config cfg{};
+            cfg.kind = (uint32_t)be->kind;
+            cfg.param = be->kind == KIND_PTB ? be->workers : be->slice_blocks;
+            (void)item_demand(ctx, &cl.cur.desc, cfg, &l, &w, &r);
+            if (admit(c, l, w, r)) {
+              rc = tally_resume(be);   // kernel.resume()
+              if (rc) break;
+              // a request that arrived while the resume was being made saw a stopped job
+              if (s->opts.policy == 0 && s->hi_active.load() && be->kind == KIND_PTB) {
+                be->t_preempt = s->t_preempt.load();
+                (void)tally_preempt(be);
+                cl.preempt_seen = true;
+              }
+            }
           }
-        } else if (be->kind == KIND_SLICED) {
-          if (closing) be->stop_issuing = true;
-          if (!hold && !closing) {
-            rc = sliced_issue(be);
-            if (rc) break;
-          }
-        } else if (closing && be->kind == KIND_PTB) {
-          (void)tally_preempt(be);
+        } else if (closing) {
+          // shutting down: drain at block boundaries, without pausing
+          if (be->kind == KIND_SLICED) be->stop_issuing = true;
+          else if (be->kind == KIND_PTB) (void)tally_preempt(be);
         }
       }
-      if (!be) {
-        if (closing) { idle++; continue; }
-        if (!hold && admit(c, &run->be_items[cl.first + cl.idx])) {
-          ctx->cur_be = cl.be;
-          ctx->cur_ctl = cl.ctl;
-          // workers may pause inside their blocks only if every high-priority kernel fits
-          // beside the paused blocks; otherwise they stop at block boundaries and drain
-          const uint32_t bound = ctx->yield_ticks;
-          if (!(*pause_ok)[cl.first + cl.idx]) ctx->yield_ticks = 0;
-          rc = launch_be_item(ctx, &run->be_items[cl.first + cl.idx], &be);
-          ctx->yield_ticks = bound;
-          ctx->cur_be = ctx->be;
-          ctx->cur_ctl = ctx->ctl;
+      if (!cl.job && !stopping && s->be_enabled.load()) {
+        if (!cl.has_cur) {
+          std::lock_guard<std::mutex> lk(s->mu);
+          if (!cl.queue.empty()) {             // client.fetch_next_kernel()
+            cl.cur = cl.queue.front();
+            cl.queue.pop_front();
+            cl.cur.desc.args = cl.cur.args;
+            cl.has_cur = true;
+          }
+        }
+        if (cl.has_cur) busy++;
+        if (cl.has_cur && !hold) {
+          tally_config cfg;
+          int prof = -1;
+          rc = choose_config(s, cl.cur, &cfg, &prof);
           if (rc) break;
-          publish(c, be);
-          // a request that arrived while this launch was being made has used the old
-          // token: raise the flag of the new segment here
-          if (run->policy == 0 && sh->hi_active.load() && be->kind == KIND_PTB) {
-            be->t_preempt = sh->t_preempt.load();
-            (void)tally_preempt(be);
-            cl.preempt_seen = true;
+          uint32_t l = 0, w = 0, r = 0;
+          (void)item_demand(ctx, &cl.cur.desc, cfg, &l, &w, &r);
+          if (admit(c, l, w, r)) {
+            ctx->cur_be = cl.be;
+            ctx->cur_ctl = cl.ctl;
+            tally_be_item it = {&cl.cur.desc, cfg};
+            tally_job *j = nullptr;
+            cl.t_launch = now_us();
+            rc = launch_be_item(ctx, &it, &j);
+            ctx->cur_be = ctx->be;
+            ctx->cur_ctl = ctx->ctl;
+            if (rc) break;
+            cl.profiling = prof;
+            set_job(cl, j);
+            // a request that arrived while this launch was being made found no job to
+            // preempt: raise it against the new segment here
+            if (s->opts.policy == 0 && s->hi_active.load() && j->kind == KIND_PTB) {
+              j->t_preempt = s->t_preempt.load();
+              (void)tally_preempt(j);
+              cl.preempt_seen = true;
+            }
           }
         }
       }
     }
-    done = idle == n_clients;
+    if (stopping && busy == 0) break;
+    if (busy == 0) {
+      // nothing in flight and nothing queued: sleep until a kernel is submitted
+      std::unique_lock<std::mutex> lk(s->mu);
+      bool any = false;
+      for (uint32_t c = 0; c < s->n_clients; ++c) any = any || !s->clients[c].queue.empty();
+      if (!any && !s->stop.load())
+        s->cv.wait_for(lk, std::chrono::milliseconds(50));
+    }
   }
-  for (uint32_t c = 0; c < n_clients; ++c) {
-    publish(c, nullptr);
-    if (clients[c].job) { tally_job_free(clients[c].job); clients[c].job = nullptr; }
+  for (uint32_t c = 0; c < s->n_clients; ++c) {
+    BeClient &cl = s->clients[c];
+    if (cl.job) {
+      tally_job *j = cl.job;
+      set_job(cl, nullptr);
+      tally_job_free(j);
+    }
   }
-  if (rc) sh->rc = rc;
+  if (rc) s->rc = rc;
 }
 
 }  // namespace
 
-extern "C" int tally_sched_run(tally_ctx *ctx, tally_sched_run_t *run) {
+extern "C" {
+
+int tally_sched_create(tally_ctx *ctx, const tally_sched_opts *opts, tally_sched **out) {
+  if (!ctx || !opts || !out) return TALLY_ERR_INVALID_ARG;
+  if (opts->policy > 2 || opts->n_be_clients > (uint32_t)kMaxBeClients) return TALLY_ERR_INVALID_ARG;
+  if (opts->threshold_ms < 0.0) return TALLY_ERR_INVALID_ARG;
+  const uint32_t n_clients = opts->n_be_clients;
+  // Every client needs two hardware queues (kernels, relays) beside the null stream's and
+  // the high-priority stream's.  HIP folds streams onto GPU_MAX_HW_QUEUES hardware queues
+  // (4 unless the environment says otherwise), and streams that share one run in order:
+  // a high-priority kernel behind a relay would wait for a whole best-effort kernel.
+  if (n_clients >= 1) {
+    const char *env = getenv("GPU_MAX_HW_QUEUES");
+    const long have = env ? strtol(env, nullptr, 10) : 4;
+    if (have < (long)(2 + 2 * n_clients)) return TALLY_ERR_UNSUPPORTED;
+  }
+  tally_sched *s = new (std::nothrow) tally_sched();
+  if (!s) return TALLY_ERR_NOMEM;
+  s->ctx = ctx;
+  s->opts = *opts;
+  s->threshold_ms = opts->threshold_ms > 0.0 ? opts->threshold_ms : 0.0316;
+  s->profile_runs = opts->profile_runs ? opts->profile_runs : 10;
+  s->n_clients = n_clients;
+  for (uint32_t c = 0; c < n_clients; ++c) {
+    if (c == 0) {
+      s->clients[c].be = ctx->be;
+      s->clients[c].ctl = ctx->ctl;
+    } else {  // further clients get a stream pair of their own, made once per context
+      hipError_t e = hipSuccess;
+      if (!ctx->client_be[c]) e = hipStreamCreateWithFlags(&ctx->client_be[c], hipStreamNonBlocking);
+      if (e == hipSuccess && !ctx->client_ctl[c])
+        e = hipStreamCreateWithFlags(&ctx->client_ctl[c], hipStreamNonBlocking);
+      if (e != hipSuccess) { g_last_hip = (int)e; delete s; return TALLY_ERR_HIP; }
+      s->clients[c].be = ctx->client_be[c];
+      s->clients[c].ctl = ctx->client_ctl[c];
+    }
+  }
+  hipError_t e = hipStreamSynchronize(ctx->hi);
+  if (e == hipSuccess) e = hipStreamSynchronize(ctx->be);
+  if (e != hipSuccess) { g_last_hip = (int)e; delete s; return TALLY_ERR_HIP; }
+  (void)tally_marker_read(ctx, 1, &s->hi_seq);
+  if (n_clients) s->be_thread = std::thread(be_thread_main, s);
+  *out = s;
+  return TALLY_OK;
+}
+
+int tally_sched_destroy(tally_sched *s) {
+  if (!s) return TALLY_ERR_INVALID_ARG;
+  s->stop = true;
+  s->hi_active = false;
+  s->cv.notify_all();
+  if (s->be_thread.joinable()) s->be_thread.join();
+  for (uint32_t c = 0; c < s->n_clients; ++c) (void)hipStreamSynchronize(s->clients[c].be);
+  (void)hipStreamSynchronize(s->ctx->hi);
+  (void)hipStreamSynchronize(s->ctx->be);
+  int rc = s->rc.load();
+  delete s;
+  return rc;
+}
+
+int tally_sched_submit_be(tally_sched *s, uint32_t client, const tally_kernel_desc *kernel,
+                          const tally_config *config, uint32_t flags) {
+  if (!s || !kernel || client >= s->n_clients) return TALLY_ERR_INVALID_ARG;
+  const KernelOps *ops;
+  tally_dim3 g;
+  int rc = check_desc(kernel, &ops, &g);
+  if (rc) return rc;
+  BeWork w;
+  w.desc = *kernel;
+  memcpy(w.args, kernel->args, ops->args_size);
+  w.loop = (flags & TALLY_SUBMIT_LOOP) != 0;
+  w.last_of_step = (flags & TALLY_SUBMIT_END_OF_STEP) != 0;
+  if (config) {
+    if (config->kind > 2 || (config->kind != 2 && config->param == 0)) return TALLY_ERR_INVALID_ARG;
+    if (config->kind != 2 && !ops->transformable) return TALLY_ERR_UNSUPPORTED;
+    if (config->kind == 0 && config->param > s->ctx->max_workers[kernel->kernel_id]) return TALLY_ERR_INVALID_ARG;
+    w.config = *config;
+  } else {
+    if (!ops->transformable) return TALLY_ERR_UNSUPPORTED;
+    w.config = tally_config{kCfgAuto, 0, 0, 0.f, 0.f};
+  }
+  {
+    std::lock_guard<std::mutex> lk(s->mu);
+    s->clients[client].queue.push_back(w);
+  }
+  s->cv.notify_all();
+  return TALLY_OK;
+}
+
+int tally_sched_submit_hi(tally_sched *s, const tally_kernel_desc *kernels, uint32_t n) {
+  if (!s || !kernels || n == 0) return TALLY_ERR_INVALID_ARG;
+  if (s->hi_inflight) return TALLY_ERR_BAD_STATE;
+  tally_ctx *ctx = s->ctx;
+  uint32_t hl = 0, hw = 0, hr = 0;  // largest demand of one high-priority workgroup
+  for (uint32_t i = 0; i < n; ++i) {
+    const KernelOps *ops;
+    tally_dim3 g;
+    int rc = check_desc(&kernels[i], &ops, &g);
+    if (rc) return rc;
+    const uint32_t *ft = ctx->foot[kernels[i].kernel_id][1];
+    hl = ft[0] > hl ? ft[0] : hl;
+    hw = ft[1] > hw ? ft[1] : hw;
+    const uint32_t per_simd = ((ft[1] + 3) / 4) * ft[2];
+    hr = per_simd > hr ? per_simd : hr;
+  }
+  // the request time is published before the flag that makes the other thread read it
+  s->t_preempt = now_us();
+  s->hi_active = true;
+  if (s->opts.policy == 0) {   // preempt_best_effort_kernel()
+    for (uint32_t c = 0; c < s->n_clients; ++c) {
+      BeClient &cl = s->clients[c];
+      SpinGuard g(cl.lock);
+      if (!cl.job || cl.job->kind != KIND_PTB) continue;
+      // Workers may pause inside their blocks only if every kernel of the request fits
+      // beside the paused workgroups on a compute unit; otherwise the request would wait
+      // for them while they wait for it: then they give way at block boundaries only.
+      const bool fits = cl.dl + hl <= ctx->lds_per_cu && cl.dw + hw <= 32u && cl.dr + hr <= 512u;
+      if (fits && !(s->opts.flags & TALLY_SCHED_NO_PAUSE)) (void)tally_preempt_pausing(cl.job);
+      else (void)tally_preempt(cl.job);
+    }
+  }
+  int rc = TALLY_OK;
+  for (uint32_t i = 0; i < n && rc == TALLY_OK; ++i) rc = tally_launch_native(ctx, &kernels[i], 1);
+  if (rc == TALLY_OK) rc = tally_marker(ctx, 1, ++s->hi_seq);
+  if (rc != TALLY_OK) { s->hi_active = false; return rc; }
+  s->hi_inflight = true;
+  return TALLY_OK;
+}
+
+int tally_sched_poll(tally_sched *s, int more_pending, int *hi_in_flight) {
+  if (!s) return TALLY_ERR_INVALID_ARG;
+  int rc = s->rc.load();
+  if (rc) return rc;
+  if (s->hi_inflight) {
+    uint32_t seen;
+    (void)tally_marker_read(s->ctx, 1, &seen);
+    if (seen == s->hi_seq) {
+      s->hi_inflight = false;
+      s->hi_done++;
+      // a queued request keeps the best-effort clients held; otherwise release them and
+      // end the pause, so that workers pausing inside a block carry on at once
+      if (!more_pending) {
+        for (uint32_t c = 0; c < s->n_clients; ++c) {
+          BeClient &cl = s->clients[c];
+          SpinGuard g(cl.lock);
+          if (cl.job) (void)tally_end_pause(cl.job);
+        }
+        s->hi_active = false;
+      }
+    }
+  }
+  if (hi_in_flight) *hi_in_flight = s->hi_inflight ? 1 : 0;
+  return TALLY_OK;
+}
+
+int tally_sched_enable_be(tally_sched *s, int enable) {
+  if (!s) return TALLY_ERR_INVALID_ARG;
+  s->be_enabled = enable != 0;
+  s->cv.notify_all();
+  return TALLY_OK;
+}
+
+int tally_sched_stats(tally_sched *s, tally_sched_stats_t *out) {
+  if (!s || !out) return TALLY_ERR_INVALID_ARG;
+  memset(out, 0, sizeof(*out));
+  out->hi_requests_done = s->hi_done;
+  for (uint32_t c = 0; c < s->n_clients; ++c) {
+    out->be_client_kernels_done[c] = s->clients[c].kernels_done.load();
+    out->be_kernels_done += out->be_client_kernels_done[c];
+  }
+  out->be_steps_done = s->n_clients ? s->clients[0].steps_done.load() : 0;
+  out->n_preempts = s->n_preempts.load();
+  out->profile_samples = s->profile_samples.load();
+  out->configs_fixed = s->configs_fixed.load();
+  return TALLY_OK;
+}
+
+int tally_sched_take_preempt_latencies(tally_sched *s, double *out, uint32_t cap, uint32_t *n) {
+  if (!s || !n || (cap && !out)) return TALLY_ERR_INVALID_ARG;
+  std::lock_guard<std::mutex> lk(s->pre_mu);
+  uint32_t k = (uint32_t)s->pre_ring.size();
+  if (k > cap) k = cap;
+  for (uint32_t i = 0; i < k; ++i) out[i] = s->pre_ring[i];
+  s->pre_ring.erase(s->pre_ring.begin(), s->pre_ring.begin() + k);
+  *n = k;
+  return TALLY_OK;
+}
+
+// Replay driver: one fixed request at given arrival times against looping best-effort
+// steps, on top of the scheduler above.
+int tally_sched_run(tally_ctx *ctx, tally_sched_run_t *run) {
   if (!ctx || !run) return TALLY_ERR_INVALID_ARG;
   if (run->n_arrivals && (!run->arrivals_us || !run->latency_us || !run->hi_kernels ||
                           !run->n_hi_kernels))
@@ -1307,20 +1798,13 @@ extern "C" int tally_sched_run(tally_ctx *ctx, tally_sched_run_t *run) {
     if (rc) return rc;
   }
   for (uint32_t i = 0; i < run->n_be_items; ++i) {
+    if (!run->be_items[i].kernel || run->be_items[i].config.kind > kCfgAuto) return TALLY_ERR_INVALID_ARG;
     const KernelOps *ops;
     tally_dim3 g;
-    if (!run->be_items[i].kernel || run->be_items[i].config.kind > 2 ||
-        (run->be_items[i].config.kind != 2 && run->be_items[i].config.param == 0))
-      return TALLY_ERR_INVALID_ARG;
     int rc = check_desc(run->be_items[i].kernel, &ops, &g);
     if (rc) return rc;
-    if (run->be_items[i].config.kind != 2 && !ops->transformable) return TALLY_ERR_UNSUPPORTED;
-    if (run->be_items[i].config.kind == 0 &&
-        run->be_items[i].config.param > ctx->max_workers[run->be_items[i].kernel->kernel_id])
-      return TALLY_ERR_INVALID_ARG;
   }
   // best-effort clients: one owning every item unless the caller splits them up
-  BeClient clients[kMaxBeClients];
   uint32_t n_clients = run->n_be_items ? 1 : 0;
   if (run->n_be_items && run->n_be_clients) {
     if (!run->be_client_items || run->n_be_clients > (uint32_t)kMaxBeClients) return TALLY_ERR_INVALID_ARG;
@@ -1332,132 +1816,77 @@ extern "C" int tally_sched_run(tally_ctx *ctx, tally_sched_run_t *run) {
     if (sum != run->n_be_items) return TALLY_ERR_INVALID_ARG;
     n_clients = run->n_be_clients;
   }
-  // Every client needs two hardware queues (kernels, relays) beside the null stream's and
-  // the high-priority stream's.  HIP folds streams onto GPU_MAX_HW_QUEUES hardware queues
-  // (4 unless the environment says otherwise), and streams that share one run in order:
-  // a high-priority kernel behind a relay would wait for a whole best-effort kernel.
-  if (n_clients >= 1) {
-    const char *env = getenv("GPU_MAX_HW_QUEUES");
-    const long have = env ? strtol(env, nullptr, 10) : 4;
-    if (have < (long)(2 + 2 * n_clients)) return TALLY_ERR_UNSUPPORTED;
-  }
-  for (uint32_t c = 0, first = 0; c < n_clients; ++c) {
-    clients[c].first = first;
-    clients[c].count = run->n_be_clients ? run->be_client_items[c] : run->n_be_items;
-    first += clients[c].count;
-    if (c == 0) {
-      clients[c].be = ctx->be;
-      clients[c].ctl = ctx->ctl;
-    } else {  // further clients get a stream pair of their own, made once per context
-      if (!ctx->client_be[c]) HIPCHK(hipStreamCreateWithFlags(&ctx->client_be[c], hipStreamNonBlocking));
-      if (!ctx->client_ctl[c]) HIPCHK(hipStreamCreateWithFlags(&ctx->client_ctl[c], hipStreamNonBlocking));
-      clients[c].be = ctx->client_be[c];
-      clients[c].ctl = ctx->client_ctl[c];
+  tally_sched_opts opts;
+  memset(&opts, 0, sizeof(opts));
+  opts.policy = run->policy;
+  opts.n_be_clients = n_clients;
+  opts.threshold_ms = run->threshold_ms;
+  opts.profile_runs = run->profile_runs;
+  opts.flags = run->sched_flags;
+  tally_sched *s = nullptr;
+  int rc = tally_sched_create(ctx, &opts, &s);
+  if (rc) return rc;
+  (void)tally_sched_enable_be(s, 0);   // nothing starts before the clock does
+  for (uint32_t c = 0, first = 0; c < n_clients && rc == TALLY_OK; ++c) {
+    const uint32_t count = run->n_be_clients ? run->be_client_items[c] : run->n_be_items;
+    for (uint32_t i = 0; i < count && rc == TALLY_OK; ++i) {
+      const tally_be_item &it = run->be_items[first + i];
+      rc = tally_sched_submit_be(s, c, it.kernel, it.config.kind == kCfgAuto ? nullptr : &it.config,
+                                 TALLY_SUBMIT_LOOP | (i + 1 == count ? TALLY_SUBMIT_END_OF_STEP : 0u));
     }
+    first += count;
   }
-  // A best-effort worker that pauses inside a block keeps its registers and LDS.  A
-  // high-priority kernel that does not fit beside such workers would wait for them while
-  // they wait for the request to end (until the pause bound): those items run without the
-  // pause and give way at block boundaries only.
-  std::vector<uint8_t> pause_ok(run->n_be_items, 1);
-  if (run->n_arrivals) {
-    uint32_t hl = 0, hw = 0, hr = 0;  // largest demand of one high-priority workgroup
-    for (uint32_t i = 0; i < run->n_hi_kernels; ++i) {
-      const uint32_t *ft = ctx->foot[run->hi_kernels[i].kernel_id][1];
-      const uint32_t l = ft[0], w = ft[1], r = ft[2];
-      hl = l > hl ? l : hl;
-      hw = w > hw ? w : hw;
-      const uint32_t per_simd = ((w + 3) / 4) * r;
-      hr = per_simd > hr ? per_simd : hr;
-    }
-    for (uint32_t i = 0; i < run->n_be_items; ++i) {
-      uint32_t l, w, r;
-      if (run->be_items[i].config.kind != 0) continue;
-      int rc2 = item_demand(ctx, &run->be_items[i], &l, &w, &r);
-      if (rc2) return rc2;
-      if (l + hl > ctx->lds_per_cu || w + hw > 32u || r + hr > 512u) pause_ok[i] = 0;
-    }
-  }
-  HIPCHK(hipStreamSynchronize(ctx->hi));
-  HIPCHK(hipStreamSynchronize(ctx->be));
+  if (rc) { (void)tally_sched_destroy(s); return rc; }
 
-  uint32_t hi_seq = 0;
-  (void)tally_marker_read(ctx, 1, &hi_seq);
   run->n_preempts = 0;
   run->be_kernels_done = 0;
   run->be_steps_done = 0;
   const double last_arrival = run->n_arrivals ? run->arrivals_us[run->n_arrivals - 1] : 0.0;
   const double t_end = last_arrival + run->tail_us;
-  SchedShared sh;
-  int rc = TALLY_OK;
   const double t0 = now_us();
-  std::thread be_thread;
-  if (n_clients) be_thread = std::thread(be_thread_main, ctx, run, &sh, clients, n_clients, &pause_ok, t0, t_end);
-
-  // ---- high-priority client (this thread) ----------------------------------------------
+  (void)tally_sched_enable_be(s, 1);
   uint32_t next_arrival = 0, cur = 0, completed = 0;
-  bool inflight = false;
-  uint64_t raised_tok[kMaxBeClients] = {};
-  while (rc == TALLY_OK && sh.rc.load() == TALLY_OK) {
+  int inflight = 0;
+  while (rc == TALLY_OK) {
     const double now = now_us() - t0;
     if (inflight) {
-      uint32_t seen;
-      (void)tally_marker_read(ctx, 1, &seen);
-      if (seen == hi_seq) {
+      const bool more = next_arrival < run->n_arrivals && run->arrivals_us[next_arrival] <= now;
+      rc = tally_sched_poll(s, more ? 1 : 0, &inflight);
+      if (rc) break;
+      if (!inflight) {
         run->latency_us[cur] = (now_us() - t0) - run->arrivals_us[cur];
-        inflight = false;
         completed++;
-        // a queued request keeps the best-effort client held; otherwise release it and
-        // withdraw the request, so that workers pausing inside a block carry on at once
-        if (!(next_arrival < run->n_arrivals && run->arrivals_us[next_arrival] <= now)) {
-          for (uint32_t c = 0; c < n_clients; ++c) {
-            if (raised_tok[c] == kNoToken) continue;
-            uint32_t slot = (uint32_t)(raised_tok[c] >> 32) - 1;
-            __atomic_store_n((uint32_t *)(ctx->host_pool + slot * kHostSlotBytes), 0u,
-                             __ATOMIC_RELEASE);
-            raised_tok[c] = kNoToken;
-          }
-          sh.hi_active = false;
-        }
       }
     }
     if (!inflight && next_arrival < run->n_arrivals && run->arrivals_us[next_arrival] <= now) {
       cur = next_arrival++;
-      // the request time is published before the flag that makes the other thread read it
-      sh.t_preempt = now_us();
-      sh.hi_active = true;
-      if (run->policy == 0) {  // preempt_best_effort_kernel(): one store to pinned memory each
-        for (uint32_t c = 0; c < n_clients; ++c) {
-          uint64_t tok = sh.ptb_token[c].load();
-          if (tok == kNoToken) continue;
-          uint32_t slot = (uint32_t)(tok >> 32) - 1;
-          __atomic_store_n((uint32_t *)(ctx->host_pool + slot * kHostSlotBytes), (uint32_t)tok,
-                           __ATOMIC_RELEASE);
-          raised_tok[c] = tok;
-        }
-      }
-      for (uint32_t i = 0; i < run->n_hi_kernels && rc == TALLY_OK; ++i)
-        rc = tally_launch_native(ctx, &run->hi_kernels[i], 1);
-      if (rc == TALLY_OK) rc = tally_marker(ctx, 1, ++hi_seq);
+      rc = tally_sched_submit_hi(s, run->hi_kernels, run->n_hi_kernels);
+      if (rc) break;
       if (run->issue_us) run->issue_us[cur] = (now_us() - t0) - run->arrivals_us[cur];
-      inflight = true;
+      inflight = 1;
     }
-    if (!inflight && completed == run->n_arrivals && (run->n_arrivals > 0 || now >= t_end) &&
-        now >= (run->n_arrivals ? last_arrival + run->tail_us : t_end))
-      break;
+    if (!inflight && completed == run->n_arrivals && now >= t_end) break;
+    if (!inflight && run->n_arrivals == 0) {
+      int dummy;
+      rc = tally_sched_poll(s, 0, &dummy);   // surfaces an error of the best-effort thread
+    }
   }
-  sh.stop = true;
-  sh.hi_active = false;
-  if (be_thread.joinable()) be_thread.join();
   run->window_us = now_us() - t0;
-  for (uint32_t c = 0; c < n_clients; ++c) {
-    run->be_kernels_done += clients[c].kernels_done;
-    if (run->be_client_kernels_done) run->be_client_kernels_done[c] = clients[c].kernels_done;
-    (void)hipStreamSynchronize(clients[c].be);
+  tally_sched_stats_t st;
+  (void)tally_sched_stats(s, &st);
+  run->be_kernels_done = st.be_kernels_done;
+  run->be_steps_done = st.be_steps_done;
+  run->n_preempts = (uint32_t)st.n_preempts;
+  run->profile_samples = st.profile_samples;
+  run->configs_fixed = st.configs_fixed;
+  if (run->be_client_kernels_done)
+    for (uint32_t c = 0; c < n_clients; ++c) run->be_client_kernels_done[c] = st.be_client_kernels_done[c];
+  if (run->preempt_latency_us && run->preempt_cap) {
+    uint32_t got = 0;
+    (void)tally_sched_take_preempt_latencies(s, run->preempt_latency_us, run->preempt_cap, &got);
   }
-  run->be_steps_done = n_clients ? clients[0].steps_done : 0;
-  (void)hipStreamSynchronize(ctx->hi);
-  (void)hipStreamSynchronize(ctx->be);
-  if (rc == TALLY_OK) rc = sh.rc.load();
-  return rc;
+  int rc2 = tally_sched_destroy(s);   // drains and frees what is in flight; not part of the window
+  return rc ? rc : rc2;
 }
+
+}  // extern "C"

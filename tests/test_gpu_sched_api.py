@@ -1,0 +1,258 @@
+"""GPU tests of the scheduler as a service (Section 4.2, Figure 4): kernels handed over while
+the loop runs, the profile-guided configuration filled one candidate per real invocation, the
+candidate set, draining without a pause, and the two sensitivity knobs (turnaround threshold,
+high-priority load) through the public API."""
+import time
+
+import numpy as np
+import pytest
+
+import tally_inputs as TI
+from oracle import profiler as OP
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def env():
+    import torch
+    import paper_2410_07381_amd.binding as B
+    assert torch.cuda.is_available()
+    hi, be = torch.cuda.Stream(), torch.cuda.Stream()
+    ctx = B.Context(hi, be)
+    yield B, ctx, torch
+    ctx.close()
+
+
+def _wait_for(cond, seconds=20.0):
+    t0 = time.perf_counter()
+    while time.perf_counter() - t0 < seconds:
+        if cond():
+            return True
+        time.sleep(0.0005)
+    return False
+
+
+def test_candidate_set_follows_section_4_2(env):
+    B, ctx, torch = env
+    x = torch.rand(1 << 26, device="cuda")
+    partial = torch.zeros(1 << 14, device="cuda")
+    k = B.reduce_sum(x, partial)                         # 16384 logical blocks
+    cands = ctx.candidate_configs(k)
+    cus = B.device_info()["num_cus"]
+    occ = ctx.max_workers(k) // cus
+    ptb1 = [p for kind, p, c in cands if kind == B.CFG_PTB and c == 1]
+    assert ptb1 == OP.ptb_candidates(k.total_blocks, cus, occ)        # k x CUs, k = 1 .. occupancy
+    sliced = [p for kind, p, c in cands if kind == B.CFG_SLICED]
+    assert sliced == OP.slice_candidates(k.total_blocks)              # 1/2 ... 1/256 of the grid
+    for kind, p, c in cands:
+        if kind == B.CFG_PTB:
+            assert c in (1, 4, 16) and (c == 1 or p * c <= k.total_blocks)
+    # a grid smaller than the GPU: worker counts are capped at the grid, no duplicates
+    small = B.reduce_sum(x[: 4096 * 100], partial[:100])
+    cs = ctx.candidate_configs(small)
+    assert [p for kind, p, c in cs if kind == B.CFG_PTB] == [100]
+    assert len(set(cs)) == len(cs)
+
+
+def test_kernels_submitted_while_the_loop_runs(env):
+    """Best-effort kernels the scheduler has never seen are handed over while it is already
+    serving others and high-priority requests; each runs exactly once with the right result."""
+    B, ctx, torch = env
+    from gpu_util import host, oracle_block_sums, oracle_softmax_rows, assert_close_rel
+    sx = torch.ones(1 << 16, device="cuda")
+    sy = torch.zeros(1 << 16, device="cuda")
+    hi_k = B.saxpy(sx, sy, 1.0)
+    x0 = torch.rand(1 << 24, device="cuda")
+    p0 = torch.zeros(1 << 12, device="cuda")
+    fresh = []
+    for i in (5, 15, 25, 35):                            # buffers of the kernels submitted later
+        ya = torch.full((256,), float(i), device="cuda")
+        yb = torch.ones(256, device="cuda")
+        r = torch.randn((512, 1024), device="cuda")
+        fresh.append((i, ya, yb, r, torch.zeros_like(r)))
+    torch.cuda.synchronize()
+    s = ctx.scheduler(policy=B.POLICY_TALLY, be_clients=1)
+    try:
+        s.submit_be(B.reduce_sum(x0, p0), (B.CFG_PTB, 512, 4), loop=True, end_of_step=True)
+        late = []
+        for i in range(40):
+            s.submit_hi([hi_k])
+            if i % 10 == 5:                              # kernels unknown when the loop started
+                _, ya, yb, r, ro = fresh[i // 10]
+                s.submit_be(B.saxpy(ya, yb, 2.0), (B.CFG_SLICED, 1, 1))   # yb <- 2 i + 1, once
+                s.submit_be(B.softmax_f32(r, ro), None)  # configuration left to the profiler
+                late.append((i, yb, r, ro))
+            assert _wait_for(lambda: not s.poll(), 5.0)
+            time.sleep(0.001)
+        assert _wait_for(lambda: s.stats()["be_kernels_done"] >= 50 and
+                         s.stats()["hi_requests_done"] == 40)
+        st = s.stats()
+        assert st["be_steps_done"] >= 10
+    finally:
+        s.close()
+    torch.cuda.synchronize()
+    assert (host(sy) == 40.0).all()
+    for i, yb, r, ro in late:
+        assert (host(yb) == 2.0 * i + 1.0).all(), i      # ran exactly once
+        assert_close_rel(host(ro), oracle_softmax_rows(host(r)), 1e-5, 1e-7)
+    _, want = oracle_block_sums(host(x0))
+    assert_close_rel(host(p0), want, 2e-6)
+
+
+def test_profile_fills_one_candidate_per_invocation(env):
+    """launch_and_profile(): every real invocation of a kernel without a fixed configuration
+    measures the next unmeasured candidate; when all are measured the choice is the oracle's
+    selection on the same measurements, and later invocations reuse it."""
+    B, ctx, torch = env
+    ctx.profile_reset()
+    x = torch.rand(1 << 25, device="cuda")
+    partial = torch.zeros(1 << 13, device="cuda")
+    torch.cuda.synchronize()
+    k = B.reduce_sum(x, partial)
+    cands = ctx.candidate_configs(k)
+    s = ctx.scheduler(policy=B.POLICY_TALLY, be_clients=1, profile_runs=1, threshold_ms=0.0316)
+    seen_patterns = set()
+    try:
+        s.submit_be(k, None, loop=True)
+        t0 = time.perf_counter()
+        while s.stats()["configs_fixed"] < 1 and time.perf_counter() - t0 < 30.0:
+            rows, chosen = ctx.profile_table(k)
+            seen_patterns.add(tuple(r["samples"] for r in rows))
+        st = s.stats()
+        assert st["configs_fixed"] == 1 and st["profile_samples"] == len(cands)
+        done_at_fix = st["be_kernels_done"]
+        assert _wait_for(lambda: s.stats()["be_kernels_done"] >= done_at_fix + 5)
+        assert s.stats()["profile_samples"] == len(cands)      # no further measuring
+    finally:
+        s.close()
+    rows, chosen = ctx.profile_table(k)
+    assert [(r["kind"], r["param"], r["chunk"]) for r in rows] == cands
+    assert all(r["samples"] == 1 for r in rows) and chosen >= 0
+    # at every moment observed the measured candidates were a prefix of the list: one at a time
+    for pat in seen_patterns:
+        n = sum(pat)
+        assert pat == (1,) * n + (0,) * (len(pat) - n), pat
+    assert len(seen_patterns) >= 3
+    cache = OP.ProfileCache(0.0316)
+    key = ("reduce_sum", k.grid, (256, 1, 1))
+    ocands = [("ptb" if kd == B.CFG_PTB else "sliced", p, c) for kd, p, c in cands]
+    for oc, r in zip(ocands, rows):
+        assert cache.next_unmeasured(key, ocands) == oc
+        assert cache.finalize(key, ocands) is None
+        cache.record(key, oc, r["latency_ms"], k.total_blocks)
+    want = cache.finalize(key, ocands)
+    got = rows[chosen]
+    assert (want["kind"], want["param"]) == ("ptb" if got["kind"] == B.CFG_PTB else "sliced", got["param"])
+    for oc, r in zip(ocands, rows):
+        assert r["turnaround_ms"] == pytest.approx(cache.meas[key][oc]["turnaround_ms"], rel=1e-4)
+    assert ctx.lookup_config(k)["param"] == got["param"]
+
+
+def test_preempt_and_wait_on_a_long_block_drains_within_one_block(env):
+    """A plain preemption request never pauses: workers finish the tile they hold and leave,
+    so the drain takes at most about one tile.  A pausing request that is never withdrawn
+    costs at most the pause budget on top, once per block, however many polls a block has."""
+    B, ctx, torch = env
+    m = n = 1024
+    k = 16384                                            # 512 k-steps, 32 pause points per tile
+    g = TI.gemm_inputs(m, n, k, scale=1.0 / 128.0, config_index=1)
+    A = torch.from_numpy(g["A"].view(np.int16)).cuda()
+    Bt = torch.from_numpy(g["Bt"].view(np.int16)).cuda()
+    Cd = torch.zeros((1, m, n), dtype=torch.int16, device="cuda")
+    torch.cuda.synchronize()
+    kern = B.gemm_bf16(A, Bt, Cd)                        # 16 tiles
+
+    def drain(pause, bound_us, workers=8):
+        ctx.set_yield_bound_us(bound_us)
+        job = ctx.launch_ptb(kern, workers)              # two tiles per worker
+        time.sleep(0.0001)
+        t0 = time.perf_counter()
+        job.preempt(pause=pause)
+        st = job.wait()
+        dt = time.perf_counter() - t0
+        done = job.progress()[0]
+        if st == B.JOB_STOPPED:
+            job.resume()
+            assert job.wait() == B.JOB_COMPLETE
+        job.free()
+        return dt, st, done
+
+    job = ctx.launch_ptb(kern, 16)                       # warm-up and the time of one tile
+    t0 = time.perf_counter()
+    assert job.wait() == B.JOB_COMPLETE
+    tile = time.perf_counter() - t0
+    job.free()
+    assert tile < 0.003
+    dt, st, done = drain(False, 1000)
+    assert st == B.JOB_STOPPED and done == 8 and dt < 1.5 * tile + 0.0005, (dt, tile)
+    dt, st, done = drain(True, 2000)                     # never withdrawn: one budget per block
+    assert st == B.JOB_STOPPED and done == 8
+    assert 0.0015 < dt < 1.5 * tile + 0.002 + 0.001, (dt, tile)
+    ctx.set_yield_bound_us(1000)
+
+
+def _hi_and_be(B, torch):
+    sx = torch.randn(1 << 20, device="cuda")
+    sy = torch.randn(1 << 20, device="cuda")
+    x = torch.rand(1 << 27, device="cuda")
+    partial = torch.zeros(1 << 15, device="cuda")
+    torch.cuda.synchronize()
+    return B.saxpy(sx, sy, 0.0), B.reduce_sum(x, partial), x, partial
+
+
+def test_threshold_sweep_two_points(env):
+    """Section 5.6 through the public API: a tighter turnaround threshold makes the profiler
+    choose a configuration whose estimate is no larger than the looser threshold's choice,
+    and the best-effort results stay right under both."""
+    B, ctx, torch = env
+    from gpu_util import host, oracle_block_sums, assert_close_rel
+    ctx.profile_reset()
+    hi_k, be_k, x, partial = _hi_and_be(B, torch)
+    arrivals = TI.poisson_arrivals_us(2000.0, 300, config_index=2)
+    picks = {}
+    for thr in (0.005, 1.0):
+        warm = ctx.sched_run([], [], [(be_k, (B.CFG_AUTO, 0, 0))], tail_us=3e6, threshold_ms=thr,
+                             profile_runs=1)
+        if warm["configs_fixed"] == 0:                   # the table was complete already
+            assert ctx.profile_table(be_k)[1] >= 0
+        partial.zero_()
+        out = ctx.sched_run([hi_k], arrivals, [(be_k, (B.CFG_AUTO, 0, 0))], threshold_ms=thr,
+                            profile_runs=1)
+        assert out["be_kernels_done"] > 5 and (out["latency_us"] > 0).all()
+        rows, chosen = ctx.profile_table(be_k)
+        picks[thr] = rows[chosen]
+        torch.cuda.synchronize()
+        idx, want = oracle_block_sums(host(x), range(0, 1 << 15, 97))
+        assert_close_rel(host(partial)[idx], want, 2e-6)
+    assert picks[0.005]["turnaround_ms"] <= picks[1.0]["turnaround_ms"]
+    assert picks[1.0]["latency_ms"] <= picks[0.005]["latency_ms"]      # looser: at least as fast
+    ok = [r for r in ctx.profile_table(be_k)[0] if r["turnaround_ms"] <= 0.005]
+    if ok:
+        assert picks[0.005]["turnaround_ms"] <= 0.005
+
+
+def test_load_sweep_two_points(env):
+    """Section 5.3 through the public API: at a higher high-priority duty the best-effort job
+    retains less of its throughput; every request completes and the results stay right."""
+    B, ctx, torch = env
+    from gpu_util import host, oracle_block_sums, assert_close_rel
+    hi_k, be_k, x, partial = _hi_and_be(B, torch)
+    item = [(be_k, (B.CFG_PTB, 512, 8))]
+    ctx.sched_run([hi_k], TI.periodic_arrivals_us(500.0, 20), item)          # warm-up
+    solo = ctx.sched_run([], [], item, tail_us=2e5)
+    tput_solo = solo["be_kernels_done"] / solo["window_us"]
+    probe = ctx.sched_run([hi_k], TI.periodic_arrivals_us(500.0, 200), [])
+    svc_us = float(np.median(probe["latency_us"][20:]))
+    kept = {}
+    for duty in (0.1, 0.7):
+        arr = TI.poisson_arrivals_us(duty / (svc_us * 1e-6), 1500, config_index=1)
+        partial.zero_()
+        out = ctx.sched_run([hi_k], arr, item)
+        assert (out["latency_us"] > 0).all()
+        kept[duty] = out["be_kernels_done"] / out["window_us"] / tput_solo
+        torch.cuda.synchronize()
+        idx, want = oracle_block_sums(host(x), range(0, 1 << 15, 97))
+        assert_close_rel(host(partial)[idx], want, 2e-6)
+    assert kept[0.7] < kept[0.1], kept
+    assert kept[0.1] > 0.5, kept

@@ -186,9 +186,9 @@ def test_profile_picks_a_config_under_the_threshold(env):
 
 
 def test_workers_pause_inside_long_blocks_while_preempted(env):
-    """A 256x256 tile over K = 32768 lasts about a millisecond.  With the pause enabled a
-    preemption request raised mid-tile suspends the workers until it is withdrawn; the
-    kernel then finishes, every block exactly once, with the right numbers."""
+    """A 256x256 tile over K = 32768 lasts about a millisecond.  A pausing preemption request
+    raised mid-tile suspends the workers until the pause is ended; the kernel then finishes,
+    every block exactly once, with the right numbers."""
     import time
     B, ctx, torch = env
     from gpu_util import host, assert_bf16_close
@@ -209,12 +209,15 @@ def test_workers_pause_inside_long_blocks_while_preempted(env):
         job = ctx.launch_ptb(kern, 16, coverage=True)
         time.sleep(0.0002)
         if pause_s:
-            job.preempt()
+            job.preempt(pause=True)
             time.sleep(pause_s)
-            job.resume()                         # still running: withdraws the request
+            job.end_pause()                      # paused workers go on and finish their tile
         st = job.wait()
         dt = time.perf_counter() - t0
-        if st == B.JOB_STOPPED:                  # a worker was between blocks: relaunch
+        if pause_s:
+            # the preemption itself stood: one tile per worker ran, then every worker left
+            assert st == B.JOB_STOPPED or job.progress()[0] == 16
+        if st == B.JOB_STOPPED:
             job.resume()
             assert job.wait() == B.JOB_COMPLETE
         rec = job.coverage()
