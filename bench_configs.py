@@ -37,7 +37,7 @@ def pct(a, q):
 
 def p99(a):
     """The 99th percentile, or None where the sample is too small for one."""
-    return p99(a) if len(a) >= MIN_P99_SAMPLES else None
+    return pct(a, 99) if len(a) >= MIN_P99_SAMPLES else None
 
 
 def ovh(x, base):

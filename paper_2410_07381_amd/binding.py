@@ -54,7 +54,7 @@ EXPORTS = [
     "tally_candidate_configs", "tally_profile_table", "tally_profile_reset",
     "tally_sched_create", "tally_sched_destroy", "tally_sched_submit_be", "tally_sched_submit_hi",
     "tally_sched_poll", "tally_sched_enable_be", "tally_sched_stats",
-    "tally_sched_take_preempt_latencies",
+    "tally_sched_take_preempt_latencies", "tally_set_yield_every",
 ]
 
 
@@ -202,6 +202,7 @@ def _load():
         "tally_max_workers": ([vp, P(KernelDesc), P(u32)], i32),
         "tally_kernel_footprint": ([vp, u32, i32, P(u32), P(u32), P(u32)], i32),
         "tally_mfma_ceiling_tflops": ([vp, u32, P(dbl)], i32),
+        "tally_set_yield_every": ([vp, u32], i32),
         "tally_preempt_pausing": ([vp], i32),
         "tally_end_pause": ([vp], i32),
         "tally_candidate_configs": ([vp, P(KernelDesc), P(Config), u32, P(u32)], i32),
@@ -429,6 +430,9 @@ class Context:
 
     def set_yield_bound_us(self, us):
         _check(_lib.tally_set_yield_bound_us(self.h, int(us)), "tally_set_yield_bound_us")
+
+    def set_yield_every(self, steps):
+        _check(_lib.tally_set_yield_every(self.h, int(steps)), "tally_set_yield_every")
 
     def marker(self, value, hi=True):
         _check(_lib.tally_marker(self.h, 1 if hi else 0, value), "tally_marker")

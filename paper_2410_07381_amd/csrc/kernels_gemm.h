@@ -59,19 +59,30 @@ struct GemmBodyT {
   // the next tile's first loads cannot overtake a reader of this tile
   static constexpr bool END_BARRIER = false;
   static constexpr bool YIELDS = true;
-  static constexpr uint32_t YIELD_EVERY = 16;             // k-steps between flag checks (~8 us)
-  // share of a tile between two flag checks (host side, for turnaround estimates)
-  static double pause_fraction(const Args &a) {
+  static constexpr bool RANGE = false;
+  // share of a tile between two looks at the pause word, `every` k-steps apart (host side,
+  // for turnaround estimates)
+  static double pause_fraction(const Args &a, uint32_t every) {
     const uint32_t nk = a.k / BK;
-    return nk > YIELD_EVERY ? (double)YIELD_EVERY / nk : 1.0;
+    return nk > every ? (double)every / nk : 1.0;
   }
 
   static __device__ __forceinline__ void run(const Args &a, uint32_t bx, uint32_t by, uint32_t bz) {
-    run_yielding(a, bx, by, bz, YieldCtl{nullptr, 0, 0});
+    run_impl<false>(a, bx, by, bz, YieldCtl{nullptr, 0, 0, 15});
   }
-
+  // best-effort forms: the output tile is written with non-temporal stores (it is not read
+  // again by this kernel and would only push other data out of the caches)
+  static __device__ __forceinline__ void run_be(const Args &a, uint32_t bx, uint32_t by, uint32_t bz) {
+    run_impl<true>(a, bx, by, bz, YieldCtl{nullptr, 0, 0, 15});
+  }
   static __device__ __forceinline__ void run_yielding(const Args &a, uint32_t bx, uint32_t by,
                                                       uint32_t bz, const YieldCtl ctl) {
+    run_impl<true>(a, bx, by, bz, ctl);
+  }
+
+  template <bool NT>
+  static __device__ __forceinline__ void run_impl(const Args &a, uint32_t bx, uint32_t by,
+                                                  uint32_t bz, const YieldCtl ctl) {
     extern __shared__ __align__(1024) unsigned char tally_dyn_lds[];
     unsigned char *sA = tally_dyn_lds;                    // STAGES x 16 KB
     unsigned char *sB = tally_dyn_lds + STAGES * OPA;
@@ -260,7 +271,7 @@ struct GemmBodyT {
     // slot in the ring held stage kt-1, whose last reads were issued a whole step ago)
     for (; kt + 3 < nk; ++kt) {
       // one wave polls; the others meet it at the barrier below
-      if (ctl.ticks != 0 && wave == 0 && (kt & (YIELD_EVERY - 1)) == YIELD_EVERY - 1)
+      if (ctl.ticks != 0 && wave == 0 && (kt & ctl.mask) == ctl.mask)
         yield_while_preempted(ctl, pause_left);
       // stage kt+1 complete, kt+2 in flight
       asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LOADS) : "memory");
@@ -345,7 +356,12 @@ struct GemmBodyT {
         const uint4 v = *reinterpret_cast<const uint4 *>(stage + row * PITCH + r_chunk * 16);
         const uint32_t grow = by * TILE + wm * 128 + h * 64 + row;
         const uint32_t gcol = bx * TILE_N + wn * 32 * NB + r_chunk * 8;
-        *reinterpret_cast<uint4 *>(gC + (uint64_t)grow * a.n + gcol) = v;
+        if constexpr (NT) {
+          const u32x4_nt w = {v.x, v.y, v.z, v.w};
+          __builtin_nontemporal_store(w, reinterpret_cast<u32x4_nt *>(gC + (uint64_t)grow * a.n + gcol));
+        } else {
+          *reinterpret_cast<uint4 *>(gC + (uint64_t)grow * a.n + gcol) = v;
+        }
       }
     }
   }
@@ -370,10 +386,12 @@ struct GemmSmallBody {
   static constexpr int TILE = 32;
   static constexpr unsigned DYN_LDS = 0;
   static constexpr bool YIELDS = false;
+  static constexpr bool RANGE = false;
   // the partial sums of consecutive blocks of one workgroup share LDS
   static constexpr bool END_BARRIER = true;
   static constexpr int BATCH = 6;                         // k-chunks requested together per wave
 
+  static __device__ __forceinline__ void run_be(const Args &a, uint32_t x, uint32_t y, uint32_t z) { run(a, x, y, z); }
   static __device__ __forceinline__ void run(const Args &a, uint32_t bx, uint32_t by, uint32_t bz) {
     __shared__ float s_part[4][16][64];                   // [wave][register][lane]
     const uint32_t tid = threadIdx.x, lane = tid & 63;

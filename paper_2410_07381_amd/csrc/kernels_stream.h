@@ -24,6 +24,43 @@ __device__ __forceinline__ float wave_max(float v) {
   for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, kWave));
   return v;
 }
+// Best-effort forms stream their data with non-temporal accesses (NT): what a best-effort
+// kernel reads once and writes once would otherwise push the high-priority job's weights
+// and caches out of the L2s and the 256 MB Infinity Cache between two of its requests
+// (measured: a decode step beside a streaming softmax took 65 us instead of 41 on the
+// device with ordinary accesses, 36 us with non-temporal ones).  The original form of a
+// kernel keeps ordinary accesses.
+typedef float f32x4_nt __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4_nt __attribute__((ext_vector_type(4)));
+template <bool NT>
+__device__ __forceinline__ float4 ld4(const float *p) {
+  if constexpr (NT) {
+    const f32x4_nt v = __builtin_nontemporal_load(reinterpret_cast<const f32x4_nt *>(p));
+    return make_float4(v.x, v.y, v.z, v.w);
+  } else {
+    return *reinterpret_cast<const float4 *>(p);
+  }
+}
+template <bool NT>
+__device__ __forceinline__ void st4(float *p, float4 v) {
+  if constexpr (NT) {
+    const f32x4_nt w = {v.x, v.y, v.z, v.w};
+    __builtin_nontemporal_store(w, reinterpret_cast<f32x4_nt *>(p));
+  } else {
+    *reinterpret_cast<float4 *>(p) = v;
+  }
+}
+template <bool NT>
+__device__ __forceinline__ float ld1(const float *p) {
+  if constexpr (NT) return __builtin_nontemporal_load(p);
+  else return *p;
+}
+template <bool NT>
+__device__ __forceinline__ void st1(float *p, float v) {
+  if constexpr (NT) __builtin_nontemporal_store(v, p);
+  else *p = v;
+}
+
 __device__ __forceinline__ float bf16_lo(uint32_t u) { return __uint_as_float(u << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t u) { return __uint_as_float(u & 0xFFFF0000u); }
 __device__ __forceinline__ uint16_t f32_to_bf16(float f) {
@@ -40,9 +77,31 @@ struct SaxpyBody {
   static constexpr unsigned DYN_LDS = 0;
   static constexpr bool YIELDS = false;
   static constexpr bool END_BARRIER = false;
-  static __device__ __forceinline__ void run(const Args &a, uint32_t bx, uint32_t, uint32_t) {
+  static constexpr bool RANGE = true;
+  template <bool NT>
+  static __device__ __forceinline__ void run_t(const Args &a, uint32_t bx) {
     uint32_t i = bx * kThreads + threadIdx.x;
-    if (i < a.n) a.y[i] = __builtin_fmaf(a.a, a.x[i], a.y[i]);
+    if (i < a.n) st1<NT>(a.y + i, __builtin_fmaf(a.a, ld1<NT>(a.x + i), ld1<NT>(a.y + i)));
+  }
+  static __device__ __forceinline__ void run(const Args &a, uint32_t bx, uint32_t, uint32_t) { run_t<false>(a, bx); }
+  static __device__ __forceinline__ void run_be(const Args &a, uint32_t bx, uint32_t, uint32_t) { run_t<true>(a, bx); }
+  // Logical blocks [first, last) of the (one-dimensional) grid in one go, for a worker that
+  // fetched several consecutive task indices: the same elements get the same arithmetic as
+  // block by block, but the loads of eight blocks are in flight together instead of one
+  // block's loads waiting for the previous block's store.
+  static __device__ __forceinline__ void run_range(const Args &a, uint32_t first, uint32_t last) {
+    const float *__restrict__ x = a.x;
+    float *__restrict__ y = a.y;
+    const uint32_t end = last * kThreads < a.n ? last * kThreads : a.n;
+    uint32_t i = first * kThreads + threadIdx.x;
+    for (; i + 7 * kThreads < end; i += 8 * kThreads) {
+      float xv[8], yv[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) { xv[u] = ld1<true>(x + i + u * kThreads); yv[u] = ld1<true>(y + i + u * kThreads); }
+#pragma unroll
+      for (int u = 0; u < 8; ++u) st1<true>(y + i + u * kThreads, __builtin_fmaf(a.a, xv[u], yv[u]));
+    }
+    for (; i < end; i += kThreads) st1<true>(y + i, __builtin_fmaf(a.a, ld1<true>(x + i), ld1<true>(y + i)));
   }
 };
 
@@ -53,9 +112,13 @@ struct ReduceSumBody {
   static constexpr int MIN_WAVES = 4;
   static constexpr unsigned DYN_LDS = 0;
   static constexpr bool YIELDS = false;
+  static constexpr bool RANGE = true;
   static constexpr bool END_BARRIER = false;
   static constexpr uint32_t PER_BLOCK = 4096;
-  static __device__ __forceinline__ void run(const Args &a, uint32_t bx, uint32_t, uint32_t) {
+  static __device__ __forceinline__ void run(const Args &a, uint32_t bx, uint32_t, uint32_t) { run_t<false>(a, bx); }
+  static __device__ __forceinline__ void run_be(const Args &a, uint32_t bx, uint32_t, uint32_t) { run_t<true>(a, bx); }
+  template <bool NT>
+  static __device__ __forceinline__ void run_t(const Args &a, uint32_t bx) {
     // two sets of wave partials, alternating with the block index: a worker that runs
     // consecutive blocks back to back then needs no barrier between them (the barrier
     // below already keeps any wave at most one block ahead of the reader)
@@ -64,9 +127,8 @@ struct ReduceSumBody {
     const uint64_t base = (uint64_t)bx * PER_BLOCK;
     float s = 0.f;
     if (base + PER_BLOCK <= a.n) {
-      const float4 *p = reinterpret_cast<const float4 *>(a.x + base);
-      float4 v0 = p[threadIdx.x], v1 = p[threadIdx.x + 256], v2 = p[threadIdx.x + 512],
-             v3 = p[threadIdx.x + 768];
+      const float *p = a.x + base + 4 * threadIdx.x;
+      float4 v0 = ld4<NT>(p), v1 = ld4<NT>(p + 1024), v2 = ld4<NT>(p + 2048), v3 = ld4<NT>(p + 3072);
       s = ((v0.x + v0.y) + (v0.z + v0.w)) + ((v1.x + v1.y) + (v1.z + v1.w)) +
           (((v2.x + v2.y) + (v2.z + v2.w)) + ((v3.x + v3.y) + (v3.z + v3.w)));
     } else {
@@ -77,6 +139,38 @@ struct ReduceSumBody {
     __syncthreads();
     if (threadIdx.x == 0) a.partial[bx] = (s_part[0] + s_part[1]) + (s_part[2] + s_part[3]);
   }
+  // Consecutive blocks [first, last) for a worker that fetched several task indices: four
+  // blocks at a time, their 64 KB requested together before any of them is reduced, and one
+  // barrier for the four (a persistent worker has far fewer blocks in flight per compute unit
+  // than the hardware keeps when it dispatches the original grid, so it has to ask for more
+  // per block-time to keep the memory system as busy).  Per block the same sums in the same
+  // order as run().
+  static __device__ __forceinline__ void run_range(const Args &a, uint32_t first, uint32_t last) {
+    __shared__ float s_quad[2][4][kThreads / kWave];
+    const uint32_t t = threadIdx.x;
+    uint32_t b = first;
+    for (uint32_t it = 0; b + 4 <= last && ((uint64_t)b + 4) * PER_BLOCK <= a.n; b += 4, ++it) {
+      float4 v[4][4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const float *p = a.x + (uint64_t)(b + q) * PER_BLOCK + 4 * t;
+        v[q][0] = ld4<true>(p); v[q][1] = ld4<true>(p + 1024); v[q][2] = ld4<true>(p + 2048); v[q][3] = ld4<true>(p + 3072);
+      }
+      float (*part)[kThreads / kWave] = s_quad[it & 1];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        float s = ((v[q][0].x + v[q][0].y) + (v[q][0].z + v[q][0].w)) +
+                  ((v[q][1].x + v[q][1].y) + (v[q][1].z + v[q][1].w)) +
+                  (((v[q][2].x + v[q][2].y) + (v[q][2].z + v[q][2].w)) +
+                   ((v[q][3].x + v[q][3].y) + (v[q][3].z + v[q][3].w)));
+        s = wave_sum(s);
+        if ((t & (kWave - 1)) == 0) part[q][t / kWave] = s;
+      }
+      __syncthreads();   // (the other buffer is free again: its reader is past this barrier)
+      if (t < 4) a.partial[b + t] = (part[t][0] + part[t][1]) + (part[t][2] + part[t][3]);
+    }
+    for (; b < last; ++b) run_t<true>(a, b);
+  }
 };
 
 struct ReduceFinalBody {
@@ -85,7 +179,9 @@ struct ReduceFinalBody {
   static constexpr int MIN_WAVES = 4;
   static constexpr unsigned DYN_LDS = 0;
   static constexpr bool YIELDS = false;
+  static constexpr bool RANGE = false;
   static constexpr bool END_BARRIER = true;   // s_d is reused by the next block
+  static __device__ __forceinline__ void run_be(const Args &a, uint32_t x, uint32_t y, uint32_t z) { run(a, x, y, z); }
   static __device__ __forceinline__ void run(const Args &a, uint32_t, uint32_t, uint32_t) {
     __shared__ double s_d[kThreads];
     double s = 0.0;
@@ -107,6 +203,7 @@ struct GemvBody {
   static constexpr int MIN_WAVES = 8;   // <= 64 registers: two waves fit beside a GEMM tile
   static constexpr unsigned DYN_LDS = 0;
   static constexpr bool YIELDS = false;
+  static constexpr bool RANGE = false;
   static constexpr bool END_BARRIER = false;
   // 8 bf16 products per 16-byte pair with four packed dot-product instructions (fp32
   // accumulate): a sixth of the vector-ALU work of unpack + fma, which matters because
@@ -122,6 +219,7 @@ struct GemvBody {
                                         __builtin_bit_cast(bf16x2_t, x.w), s, false);
     return s;
   }
+  static __device__ __forceinline__ void run_be(const Args &a, uint32_t x, uint32_t y, uint32_t z) { run(a, x, y, z); }
   static __device__ __forceinline__ void run(const Args &a, uint32_t bx, uint32_t, uint32_t) {
     const uint32_t lane = threadIdx.x & (kWave - 1);
     const uint32_t row = bx * 4 + threadIdx.x / kWave;
@@ -145,21 +243,20 @@ struct GemvBody {
 };
 
 // ---- row-wise kernels: a wave keeps its row in registers as NV float4 per lane --------
-template <int NV>
+template <int NV, bool NT>
 __device__ __forceinline__ void load_row(const float *row, uint32_t cols, uint32_t lane,
                                          float4 (&v)[NV], float fill) {
 #pragma unroll
   for (int i = 0; i < NV; ++i) {
     uint32_t c = (i * kWave + lane) * 4;
-    v[i] = (c < cols) ? *reinterpret_cast<const float4 *>(row + c)
-                      : make_float4(fill, fill, fill, fill);
+    v[i] = (c < cols) ? ld4<NT>(row + c) : make_float4(fill, fill, fill, fill);
   }
 }
 
-template <int NV>
+template <int NV, bool NT>
 __device__ __forceinline__ void softmax_row(const float *x, float *y, uint32_t cols, uint32_t lane) {
   float4 v[NV];
-  load_row<NV>(x, cols, lane, v, -INFINITY);
+  load_row<NV, NT>(x, cols, lane, v, -INFINITY);
   float m = -INFINITY;
 #pragma unroll
   for (int i = 0; i < NV; ++i) m = fmaxf(m, fmaxf(fmaxf(v[i].x, v[i].y), fmaxf(v[i].z, v[i].w)));
@@ -176,9 +273,7 @@ __device__ __forceinline__ void softmax_row(const float *x, float *y, uint32_t c
 #pragma unroll
   for (int i = 0; i < NV; ++i) {
     uint32_t c = (i * kWave + lane) * 4;
-    if (c < cols)
-      *reinterpret_cast<float4 *>(y + c) =
-          make_float4(v[i].x * inv, v[i].y * inv, v[i].z * inv, v[i].w * inv);
+    if (c < cols) st4<NT>(y + c, make_float4(v[i].x * inv, v[i].y * inv, v[i].z * inv, v[i].w * inv));
   }
 }
 
@@ -207,33 +302,47 @@ __device__ __forceinline__ void softmax_row_streamed(const float *x, float *y, u
   }
 }
 
-struct SoftmaxBody {
+// MAXNV bounds the widest row instantiated (in float4 per lane): the widest instantiation
+// sets the register allocation of the whole kernel, so rows of up to 1024 columns get a
+// kernel of their own that needs a quarter of the registers.  A high-priority kernel over
+// narrow rows then fits several waves per SIMD beside paused best-effort workgroups.
+template <int MAXNV>
+struct SoftmaxBodyT {
   using Args = tally_softmax_f32_args;
   static constexpr int THREADS = kThreads;
-  static constexpr int MIN_WAVES = 4;
+  static constexpr int MIN_WAVES = MAXNV <= 4 ? 8 : 4;
   static constexpr unsigned DYN_LDS = 0;
   static constexpr bool YIELDS = false;
+  static constexpr bool RANGE = false;
   static constexpr bool END_BARRIER = false;
-  static __device__ __forceinline__ void run(const Args &a, uint32_t bx, uint32_t, uint32_t) {
+  static constexpr uint32_t MAX_COLS = MAXNV * kWave * 4;   // widest row held in registers
+  static __device__ __forceinline__ void run(const Args &a, uint32_t bx, uint32_t, uint32_t) { run_t<false>(a, bx); }
+  static __device__ __forceinline__ void run_be(const Args &a, uint32_t bx, uint32_t, uint32_t) { run_t<true>(a, bx); }
+  template <bool NT>
+  static __device__ __forceinline__ void run_t(const Args &a, uint32_t bx) {
     const uint32_t lane = threadIdx.x & (kWave - 1);
     const uint32_t row = bx * 4 + threadIdx.x / kWave;
     if (row >= a.rows) return;
     const float *x = a.x + (uint64_t)row * a.cols;
     float *y = a.y + (uint64_t)row * a.cols;
-    if (a.cols <= 256) softmax_row<1>(x, y, a.cols, lane);
-    else if (a.cols <= 512) softmax_row<2>(x, y, a.cols, lane);
-    else if (a.cols <= 1024) softmax_row<4>(x, y, a.cols, lane);
-    else if (a.cols <= 2048) softmax_row<8>(x, y, a.cols, lane);
-    else if (a.cols <= 4096) softmax_row<16>(x, y, a.cols, lane);
-    else softmax_row_streamed(x, y, a.cols, lane);
+    if (a.cols <= 256) softmax_row<1, NT>(x, y, a.cols, lane);
+    else if (a.cols <= 512) softmax_row<2, NT>(x, y, a.cols, lane);
+    else if (a.cols <= 1024) softmax_row<4, NT>(x, y, a.cols, lane);
+    else if constexpr (MAXNV >= 16) {
+      if (a.cols <= 2048) softmax_row<8, NT>(x, y, a.cols, lane);
+      else if (a.cols <= 4096) softmax_row<16, NT>(x, y, a.cols, lane);
+      else softmax_row_streamed(x, y, a.cols, lane);   // (re-read twice: ordinary accesses)
+    }
   }
 };
+using SoftmaxBody = SoftmaxBodyT<16>;
+using SoftmaxNarrowBody = SoftmaxBodyT<4>;
 
-template <int NV>
+template <int NV, bool NT>
 __device__ __forceinline__ void layernorm_row(const float *x, const float *g, const float *b,
                                               float *y, uint32_t cols, float eps, uint32_t lane) {
   float4 v[NV];
-  load_row<NV>(x, cols, lane, v, 0.f);
+  load_row<NV, NT>(x, cols, lane, v, 0.f);
   float s = 0.f;
 #pragma unroll
   for (int i = 0; i < NV; ++i) s += (v[i].x + v[i].y) + (v[i].z + v[i].w);
@@ -254,11 +363,11 @@ __device__ __forceinline__ void layernorm_row(const float *x, const float *g, co
     if (c < cols) {
       float4 gg = *reinterpret_cast<const float4 *>(g + c);
       float4 bb = *reinterpret_cast<const float4 *>(b + c);
-      *reinterpret_cast<float4 *>(y + c) = make_float4(
+      st4<NT>(y + c, make_float4(
           __builtin_fmaf((v[i].x - mu) * rstd, gg.x, bb.x),
           __builtin_fmaf((v[i].y - mu) * rstd, gg.y, bb.y),
           __builtin_fmaf((v[i].z - mu) * rstd, gg.z, bb.z),
-          __builtin_fmaf((v[i].w - mu) * rstd, gg.w, bb.w));
+          __builtin_fmaf((v[i].w - mu) * rstd, gg.w, bb.w)));
     }
   }
 }
@@ -291,26 +400,36 @@ __device__ __forceinline__ void layernorm_row_streamed(const float *x, const flo
   }
 }
 
-struct LayerNormBody {
+template <int MAXNV>
+struct LayerNormBodyT {
   using Args = tally_layernorm_f32_args;
   static constexpr int THREADS = kThreads;
-  static constexpr int MIN_WAVES = 2;
+  static constexpr int MIN_WAVES = MAXNV <= 4 ? 8 : 2;
   static constexpr unsigned DYN_LDS = 0;
   static constexpr bool YIELDS = false;
+  static constexpr bool RANGE = false;
   static constexpr bool END_BARRIER = false;
-  static __device__ __forceinline__ void run(const Args &a, uint32_t bx, uint32_t, uint32_t) {
+  static constexpr uint32_t MAX_COLS = MAXNV * kWave * 4;
+  static __device__ __forceinline__ void run(const Args &a, uint32_t bx, uint32_t, uint32_t) { run_t<false>(a, bx); }
+  static __device__ __forceinline__ void run_be(const Args &a, uint32_t bx, uint32_t, uint32_t) { run_t<true>(a, bx); }
+  template <bool NT>
+  static __device__ __forceinline__ void run_t(const Args &a, uint32_t bx) {
     const uint32_t lane = threadIdx.x & (kWave - 1);
     const uint32_t row = bx * 4 + threadIdx.x / kWave;
     if (row >= a.rows) return;
     const float *x = a.x + (uint64_t)row * a.cols;
     float *y = a.y + (uint64_t)row * a.cols;
-    if (a.cols <= 256) layernorm_row<1>(x, a.gamma, a.beta, y, a.cols, a.eps, lane);
-    else if (a.cols <= 512) layernorm_row<2>(x, a.gamma, a.beta, y, a.cols, a.eps, lane);
-    else if (a.cols <= 1024) layernorm_row<4>(x, a.gamma, a.beta, y, a.cols, a.eps, lane);
-    else if (a.cols <= 2048) layernorm_row<8>(x, a.gamma, a.beta, y, a.cols, a.eps, lane);
-    else if (a.cols <= 4096) layernorm_row<16>(x, a.gamma, a.beta, y, a.cols, a.eps, lane);
-    else layernorm_row_streamed(x, a.gamma, a.beta, y, a.cols, a.eps, lane);
+    if (a.cols <= 256) layernorm_row<1, NT>(x, a.gamma, a.beta, y, a.cols, a.eps, lane);
+    else if (a.cols <= 512) layernorm_row<2, NT>(x, a.gamma, a.beta, y, a.cols, a.eps, lane);
+    else if (a.cols <= 1024) layernorm_row<4, NT>(x, a.gamma, a.beta, y, a.cols, a.eps, lane);
+    else if constexpr (MAXNV >= 16) {
+      if (a.cols <= 2048) layernorm_row<8, NT>(x, a.gamma, a.beta, y, a.cols, a.eps, lane);
+      else if (a.cols <= 4096) layernorm_row<16, NT>(x, a.gamma, a.beta, y, a.cols, a.eps, lane);
+      else layernorm_row_streamed(x, a.gamma, a.beta, y, a.cols, a.eps, lane);
+    }
   }
 };
+using LayerNormBody = LayerNormBodyT<16>;
+using LayerNormNarrowBody = LayerNormBodyT<4>;
 
 }  // namespace tally

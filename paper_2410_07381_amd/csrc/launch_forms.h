@@ -9,8 +9,14 @@
 //                                            would race on workgroup-shared state
 //   static constexpr bool YIELDS;            true if the body offers run_yielding(), which
 //                                            pauses inside the block while preempted
+//   static constexpr bool RANGE;             true if the body offers run_range(args, first,
+//                                            last) for consecutive blocks of a 1-D grid
 //   static __device__ void run(const Args&, uint32_t bx, uint32_t by, uint32_t bz);
-// run() performs the work of original block (bx,by,bz); every thread of the workgroup
+//   static __device__ void run_be(const Args&, uint32_t bx, uint32_t by, uint32_t bz);
+// run() performs the work of original block (bx,by,bz); run_be() is the same work as the
+// best-effort forms (sliced, persistent workers) do it: identical arithmetic, but data that
+// is touched once goes through non-temporal accesses so that it does not evict the
+// high-priority job's data from the caches; every thread of the workgroup
 // calls it and returns from it (no early exit), so the workgroup-wide barriers of the
 // persistent-worker loop are reached by all threads (Section 4.1: divergent barriers
 // stall a kernel for ever; hand-written bodies handle ragged tails by predication).
@@ -54,6 +60,7 @@ struct PtbCtl {
   uint32_t segment;         // 0-based segment number, for the coverage records
   uint32_t gx, gy;          // logical grid extents (x fastest)
   uint32_t yield_ticks;     // longest pause inside ONE block, in 10 ns wall-clock ticks (0: never)
+  uint32_t yield_mask;      // a pausing body looks at the pause word every (yield_mask + 1) steps
   uint32_t *flag_copies;    // device: kFlagCopies copies of the pause request (the epoch while
                             // workers are to pause inside their blocks, else 0), 128 B apart, for
                             // the mid-block polls (one address serves only ~80 M coherent scalar
@@ -105,7 +112,7 @@ template <class Body>
 __device__ __forceinline__ void sliced_body(const typename Body::Args &args, const SliceCtl &ctl) {
   uint32_t idx = ctl.offset + blockIdx.x, bx, by, bz;
   delinearize(idx, ctl.gx, ctl.gy, bx, by, bz);
-  Body::run(args, bx, by, bz);
+  Body::run_be(args, bx, by, bz);
   record(ctl.cover, idx, bx, by, bz, ctl.segment, blockIdx.x);
 }
 template <class Body>
@@ -227,6 +234,7 @@ __global__ __launch_bounds__(64) void relay_kernel(PtbCtl c) {
 struct YieldCtl {          // passed by value: taking the address of the kernel's control
   const uint32_t *flag;    // block would force it out of scalar registers into memory
   uint32_t epoch, ticks;
+  uint32_t mask;           // poll when (step & mask) == mask
 };
 __device__ __forceinline__ void yield_while_preempted(const YieldCtl &y, uint32_t &left) {
   if (left == 0u || scalar_load_coherent(y.flag) != y.epoch) return;
@@ -257,15 +265,24 @@ __device__ __forceinline__ void ptb_body(const typename Body::Args &args, const 
     const uint32_t first = s_idx[it & 1];
     if (first >= c.limit) break;  // uniform across the workgroup
     const uint32_t last = (c.limit - first < c.chunk) ? c.limit : first + c.chunk;
+    if constexpr (Body::RANGE) {
+      // the blocks a fetch brought, handed to the body together (one-dimensional grids)
+      if (last - first > 1) {
+        Body::run_range(args, first, last);
+        for (uint32_t idx = first; idx < last; ++idx) record(c.cover, idx, idx, 0, 0, c.segment, worker);
+        if (c.single_pass) break;
+        continue;
+      }
+    }
     for (uint32_t idx = first; idx < last; ++idx) {
       uint32_t bx, by, bz;
       delinearize(idx, c.gx, c.gy, bx, by, bz);
       if constexpr (Body::YIELDS)
         Body::run_yielding(args, bx, by, bz,
                            YieldCtl{c.flag_copies + (worker % kFlagCopies) * kFlagCopyStride, c.epoch,
-                                    c.flag_copies != nullptr ? c.yield_ticks : 0u});
+                                    c.flag_copies != nullptr ? c.yield_ticks : 0u, c.yield_mask});
       else
-        Body::run(args, bx, by, bz);
+        Body::run_be(args, bx, by, bz);
       record(c.cover, idx, bx, by, bz, c.segment, worker);
       // the paper ends every iteration with a barrier so that a worker handles one block
       // at a time; a body whose waves share no state across blocks does not need it

@@ -60,7 +60,7 @@ struct KernelOps {
   int (*occupancy)(int *blocks_per_cu);
   // share of one logical block between two points at which a preempted worker pauses
   // (1 for bodies that only stop at block boundaries)
-  double (*pause_fraction)(const void *args);
+  double (*pause_fraction)(const void *args, uint32_t every);
   // what one workgroup of the persistent-worker kernel occupies on a compute unit
   hipError_t (*footprint)(uint32_t *lds_bytes, uint32_t *waves, uint32_t *regs_per_lane);
   // the same for one workgroup of the kernel in its original form
@@ -143,6 +143,16 @@ hipError_t footprint_attn(uint32_t *lds_bytes, uint32_t *waves, uint32_t *regs_p
   *waves = 4;
   *regs_per_lane = ((uint32_t)attr.numRegs + 7u) & ~7u;
   return hipSuccess;
+}
+
+// Row kernels in their original form: rows that fit the narrow instantiation get the kernel
+// that needs a quarter of the registers.
+template <class Wide, class Narrow>
+hipError_t launch_native_rows_t(hipStream_t s, const void *args, tally_dim3 g, uint32_t urgent) {
+  typename Wide::Args a;
+  memcpy(&a, args, sizeof(a));
+  if (a.cols <= Narrow::MAX_COLS) return launch_native_t<Narrow>(s, args, g, urgent);
+  return launch_native_t<Wide>(s, args, g, urgent);
 }
 
 const tally_dim3 kBlock256 = {256, 1, 1};
@@ -251,11 +261,11 @@ int grid_attn(const void *p, tally_dim3 *g, tally_dim3 *b) {
 }
 
 template <class Body>
-double pause_fraction_t(const void *args) {
+double pause_fraction_t(const void *args, uint32_t every) {
   if constexpr (Body::YIELDS) {
     typename Body::Args a;
     memcpy(&a, args, sizeof(a));
-    return Body::pause_fraction(a);
+    return Body::pause_fraction(a, every);
   } else {
     return 1.0;
   }
@@ -272,8 +282,14 @@ const KernelOps kOps[TALLY_K_COUNT] = {
     OPS(ReduceFinalBody, "reduce_final", grid_reduce_final),
     OPS(GemmBody, "gemm_bf16", grid_gemm),
     OPS(GemvBody, "gemv_bf16", grid_gemv),
-    OPS(SoftmaxBody, "softmax_f32", grid_softmax),
-    OPS(LayerNormBody, "layernorm_f32", grid_layernorm),
+    {"softmax_f32", sizeof(SoftmaxBody::Args), true, grid_softmax,
+     launch_native_rows_t<SoftmaxBody, SoftmaxNarrowBody>, launch_sliced_t<SoftmaxBody>,
+     launch_ptb_t<SoftmaxBody>, init_t<SoftmaxBody>, occupancy_t<SoftmaxBody>,
+     pause_fraction_t<SoftmaxBody>, footprint_t<SoftmaxBody>, footprint_native_t<SoftmaxBody>},
+    {"layernorm_f32", sizeof(LayerNormBody::Args), true, grid_layernorm,
+     launch_native_rows_t<LayerNormBody, LayerNormNarrowBody>, launch_sliced_t<LayerNormBody>,
+     launch_ptb_t<LayerNormBody>, init_t<LayerNormBody>, occupancy_t<LayerNormBody>,
+     pause_fraction_t<LayerNormBody>, footprint_t<LayerNormBody>, footprint_native_t<LayerNormBody>},
     {"attn_decode_bf16", sizeof(tally_attn_decode_args), false, grid_attn, launch_attn_decode,
      nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, footprint_attn},
     OPS(GemmSmallBody, "gemm_bf16_small", grid_gemm_small),
@@ -340,6 +356,7 @@ struct tally_ctx {
   // [0] persistent-worker form, [1] original form; asked of the runtime once, at creation
   uint32_t foot[TALLY_K_COUNT][2][3];
   uint32_t yield_ticks;      // bound of a mid-block pause, 10 ns ticks
+  uint32_t yield_every;      // steps between two looks at the pause word (a power of two)
   void *static_attn_scratch; // this device's address of static_scratch
   int device;
   int live_jobs;
@@ -364,6 +381,7 @@ struct tally_job {
   // persistent workers
   uint32_t workers, chunk, epoch, limit;
   uint32_t yield_ticks;      // the context's pause bound when the job was made
+  uint32_t yield_every;
   uint32_t counter_base;     // raw counter value standing for task index 0
   uint32_t segments;         // launch segments so far
   bool relay_pending;        // a relay of this job may still be running (its report is not in)
@@ -440,6 +458,7 @@ int new_job(tally_ctx *ctx, const tally_kernel_desc *desc, int kind, int coverag
   j->workers = j->chunk = j->epoch = j->segments = 0;
   j->counter_base = ctx->slot_counter[slot];
   j->yield_ticks = ctx->yield_ticks;
+  j->yield_every = ctx->yield_every;
   j->limit = j->total;
   j->relay_pending = false;
   j->failed = false;
@@ -530,6 +549,7 @@ int ptb_launch_segment(tally_job *j, uint32_t limit) {
   c.gx = j->grid.x;
   c.gy = j->grid.y;
   c.yield_ticks = j->yield_ticks;
+  c.yield_mask = j->yield_every - 1;
   c.flag_copies = ctx->copy_pool + (size_t)slot * (kCopySlotBytes / sizeof(uint32_t));
   // The relay goes first, on its own stream: once the workers are on the GPU there may be
   // no wave slot or register left anywhere for it (four 128-register softmax workgroups
@@ -678,6 +698,7 @@ int tally_create(tally_ctx **out, void *hip_stream_hi, void *hip_stream_be) {
   c->num_cus = (uint32_t)prop.multiProcessorCount;
   c->lds_per_cu = (uint32_t)prop.maxSharedMemoryPerMultiProcessor;
   c->yield_ticks = 100000;  // 1 ms
+  c->yield_every = 4;
   c->device = dev;
   for (int k = 0; k < TALLY_K_COUNT; ++k) {
     if (kOps[k].init && (e = kOps[k].init()) != hipSuccess) {
@@ -1024,6 +1045,12 @@ int tally_set_yield_bound_us(tally_ctx *ctx, uint32_t us) {
   return TALLY_OK;
 }
 
+int tally_set_yield_every(tally_ctx *ctx, uint32_t steps) {
+  if (!ctx || steps == 0 || steps > 1024 || (steps & (steps - 1))) return TALLY_ERR_INVALID_ARG;
+  ctx->yield_every = steps;
+  return TALLY_OK;
+}
+
 int tally_last_hip_error(void) { return g_last_hip; }
 
 const char *tally_strerror(int status) {
@@ -1096,7 +1123,7 @@ void fill_turnaround(tally_ctx *ctx, const KernelOps *ops, const void *args, uin
     c->turnaround_ms = (float)tally_ptb_turnaround_ms(c->latency_ms, c->param, c->chunk ? c->chunk : 1, total);
     // a body that pauses inside its blocks hands the execution units over after a share
     // of ONE block, whatever the chunk: Eq. 1 with chunk 1, times that share
-    const double share = ctx->yield_ticks ? ops->pause_fraction(args) : 1.0;
+    const double share = ctx->yield_ticks ? ops->pause_fraction(args, ctx->yield_every) : 1.0;
     if (share < 1.0)
       c->turnaround_ms = (float)(tally_ptb_turnaround_ms(c->latency_ms, c->param, 1, total) * share);
   } else {
