@@ -9,9 +9,10 @@ A "step" is PERIODS_PER_STEP (100) high-priority periods: 100 arrivals, each wit
 preempt + native launch, and the best-effort work scheduled around them, so that the
 default 20 steps give the configuration's 2000 arrivals per run.  K steps are timed, after
 W warm-up steps, for (1) the high-priority job alone, (2) the best-effort job alone, (3) both
-co-located under the priority scheduler; the pair (1), (3) is run `--repeats` times,
-alternating, and the reported percentiles are the medians over the repeats (pooled ones
-beside them).  From those: p50/p99 of the high-priority latency alone and co-located, the
+co-located under the priority scheduler.  (1) and (3) alternate INSIDE every run, in blocks of
+100 arrivals with the best-effort side switched off and on, so that both see the same host
+noise and machine state; the run is made `--repeats` times and the reported percentiles are
+the medians over the repeats (pooled ones beside them).  From those: p50/p99 of the high-priority latency alone and co-located, the
 p99 overhead, best-effort throughput retained, preemption latency.  A p99 is only reported
 from 1000 samples per run upwards; below that the fields are null and the line says why.
 Two latencies are given per request: the host clock's (scheduled arrival to completion
@@ -149,7 +150,9 @@ def main():
                     help="cfg1 is the headline workload; the others print one JSON line each "
                          "with that configuration's figures")
     ap.add_argument("--period-us", type=float, default=1000.0)
-    ap.add_argument("--workers", type=int, default=256)
+    ap.add_argument("--workers", type=int, default=None,
+                    help="persistent workers of the best-effort GEMM; default: the profiler's choice "
+                         "from the Section 4.2 candidate set under --threshold-ms (0.0316)")
     ap.add_argument("--threshold-ms", type=float, default=None,
                     help="turnaround-latency threshold of the profile-guided choice (cfg3, cfg4)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -223,7 +226,20 @@ def main():
     torch.cuda.synchronize()
     gemm = B.gemm_bf16(A, Bt, Cd)
     gemv = B.gemv_bf16(x, W, y)
-    be_cfg = (B.CFG_PTB, args.workers, 1)
+    thr = args.threshold_ms if args.threshold_ms is not None else 0.0316
+    if args.workers is None:
+        # profile-guided choice (Section 4.2): every candidate really runs the kernel
+        meas, chosen = ctx.profile(gemm, ctx.candidate_configs(gemm), runs=5, threshold_ms=thr)
+        pick = meas[chosen]
+        be_cfg = (pick["kind"], pick["param"], pick["chunk"])
+        choice = {"by": "profiler", "threshold_ms": thr, "candidates": len(meas),
+                  "form": "ptb" if pick["kind"] == B.CFG_PTB else "sliced", "param": pick["param"],
+                  "chunk": pick["chunk"], "kernel_latency_us": pick["latency_ms"] * 1e3,
+                  "turnaround_estimate_us": pick["turnaround_ms"] * 1e3}
+    else:
+        be_cfg = (B.CFG_PTB, args.workers, 1)
+        choice = {"by": "--workers", "form": "ptb", "param": args.workers, "chunk": 1}
+    args.workers = be_cfg[1] if be_cfg[0] == B.CFG_PTB else ctx.max_workers(gemm)
 
     if args.leg == "roofline":
         # counter runs: a plain copy of known size calibrates FETCH_SIZE / WRITE_SIZE
@@ -262,25 +278,42 @@ def main():
     ctx.sched_run([], [], [(gemm, be_cfg)], tail_us=max(Wm, 100) * args.period_us)   # warm-up
     be_solo = ctx.sched_run([], [], [(gemm, be_cfg)], tail_us=K * args.period_us)
     tput_solo = be_solo["be_kernels_done"] / (be_solo["window_us"] * 1e-6)
-    # ---- (1) high-priority alone and (3) co-located under the priority scheduler, alternating
-    solo_runs, co_runs = [], []
+    # ---- (1) high-priority alone and (3) co-located, alternating INSIDE each run ----------
+    # Blocks of 100 arrivals alternate between "best-effort side switched off" (the job
+    # alone) and "on" (co-located), so both populations see the same host noise and the
+    # same machine state; a run holds Wm warm-up arrivals, then K alone and K co-located.
+    # The first SETTLE arrivals of every block are left out (the switch takes a best-effort
+    # kernel's drain, or its launch, to take effect).
+    T, SETTLE = PERIODS_PER_STEP, 5
+    Wb = -(-Wm // (2 * T)) * 2 * T                 # warm-up rounded up to whole block pairs
+    arrivals = TI.periodic_arrivals_us(args.period_us, Wb + 2 * K)
+    idx = np.arange(len(arrivals))
+    timed = (idx >= Wb) & (idx % T >= SETTLE)
+    solo_mask = timed & ((idx // T) % 2 == 0)
+    co_mask = timed & ((idx // T) % 2 == 1)
+    runs = []
     t_wall = 0.0
     for _ in range(max(args.repeats, 1)):
-        solo_runs.append(ctx.sched_run([gemv], arrivals, [], policy=B.POLICY_TALLY, tail_us=0.0))
         t_wall0 = time.perf_counter()
-        co_runs.append(ctx.sched_run([gemv], arrivals, [(gemm, be_cfg)], policy=B.POLICY_TALLY,
-                                     tail_us=0.0))
+        runs.append(ctx.sched_run([gemv], arrivals, [(gemm, be_cfg)], policy=B.POLICY_TALLY,
+                                  tail_us=0.0, be_toggle_every=T))
         t_wall += time.perf_counter() - t_wall0
-    host_lat = lambda r: r["latency_us"][Wm:]
+    solo_runs = [{"lat": r["latency_us"][solo_mask], "dev": (r["latency_us"] - r["issue_us"])[solo_mask]}
+                 for r in runs]
+    co_runs = [{"lat": r["latency_us"][co_mask], "dev": (r["latency_us"] - r["issue_us"])[co_mask]}
+               for r in runs]
+    host_lat = lambda r: r["lat"]
     # the part of a latency that follows the host's launch calls (device side and completion)
-    dev_lat = lambda r: (r["latency_us"] - r["issue_us"])[Wm:]
-    co = {"window_us": sum(r["window_us"] for r in co_runs),
-          "be_kernels_done": sum(r["be_kernels_done"] for r in co_runs),
-          "n_preempts": sum(r["n_preempts"] for r in co_runs),
-          "preempt_latency_us": np.concatenate([r["preempt_latency_us"] for r in co_runs])}
-    tput_co = co["be_kernels_done"] / (co["window_us"] * 1e-6)
+    dev_lat = lambda r: r["dev"]
+    co = {"window_us": sum(r["window_us"] for r in runs),
+          "be_enabled_us": sum(r["be_enabled_us"] for r in runs),
+          "be_kernels_done": sum(r["be_kernels_done"] for r in runs),
+          "n_preempts": sum(r["n_preempts"] for r in runs),
+          "preempt_latency_us": np.concatenate([r["preempt_latency_us"] for r in runs])}
+    tput_co = co["be_kernels_done"] / (co["be_enabled_us"] * 1e-6)
     n_run = int(len(host_lat(co_runs[0])))
     p99_ok = n_run >= MIN_P99_SAMPLES
+    arrivals = TI.periodic_arrivals_us(args.period_us, K + Wm)     # for the decomposition runs
     # ---- decomposition: same load with native best-effort kernels, and with no scheduling -
     n_dec = Wm + max(K // 2, min(K, MIN_P99_SAMPLES))
     nat = ctx.sched_run([gemv], arrivals[:n_dec], [(gemm, (B.CFG_NATIVE, 1, 1))],
@@ -355,23 +388,25 @@ def main():
     }
 
     dec_p99 = lambda r: pct(r["latency_us"][Wm:], 99) if len(r["latency_us"][Wm:]) >= MIN_P99_SAMPLES else None
+    steps_run = (len(idx) / (2.0 * T)) * len(runs)
     out = {
         "metric": METRIC,
         "value": overhead,
         "unit": "% (hi-pri p99 latency overhead, co-located vs alone; host clock, scheduled "
                 "arrival to completion observed)",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": co["window_us"] / (args.steps + args.warmup) / len(co_runs) / 1e3,
+        "ms_per_step": co["window_us"] / steps_run / 1e3,
         "repeats": len(co_runs),
         "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "cfg1: best-effort bf16 GEMM 4096^3 (256x256 logical tiles, "
-                               f"persistent workers W={args.workers}) + hi-pri bf16 GEMV 4096x4096 "
-                               f"every {args.period_us:.0f} us",
-                   "step": f"{PERIODS_PER_STEP} high-priority periods (arrivals) and the best-effort "
-                           "work scheduled around them",
+                               f"{choice['form']} {choice['param']} x {choice['chunk']}) + hi-pri bf16 GEMV "
+                               f"4096x4096 every {args.period_us:.0f} us",
+                   "step": f"{PERIODS_PER_STEP} high-priority periods (arrivals) co-located with the "
+                           f"best-effort job, preceded by {PERIODS_PER_STEP} periods alone as their baseline "
+                           "(blocks alternate inside one run; the first 5 arrivals of a block are left out)",
                    "arrivals_per_step": PERIODS_PER_STEP, "timed_arrivals_per_run": n_run,
-                   "be_form": "ptb", "workers": args.workers, "chunk": 1,
+                   "be_config": choice,
                    "period_us": args.period_us, "gpu_max_hw_queues": hwq},
         "hi_pri_latency_us": host_side,
         "hi_pri_device_side_latency_us": dict(

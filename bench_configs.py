@@ -45,6 +45,12 @@ def ovh(x, base):
     return None if x is None or base is None else (x - base) / base * 100.0
 
 
+def _progress(msg):
+    """One line on stderr per completed part of a long workload."""
+    import sys
+    print("[bench] " + msg, file=sys.stderr, flush=True)
+
+
 def _time(torch, B, stream, launch, reps=10, warm=2, wait_before_stop=False):
     """Mean/min duration in us of one launch, HIP events on `stream`.  For host-driven
     forms (sliced) the stop event is recorded after the job has completed."""
@@ -163,6 +169,7 @@ def cfg2(torch, B, ctx, be_stream, args):
         t = _time(torch, B, be_stream, lambda: ctx.launch_sliced(red, s), reps=reps, warm=1,
                   wait_before_stop=True)
         co = ctx.sched_run([hi], arrivals, [(red, (B.CFG_SLICED, s, 1))], tail_us=0.0)
+        _progress(f"cfg2 slices of {s} done")
         lat = co["latency_us"][args.n_warm:]
         out["slices"][str(s)] = {
             "launches": nslices, "total_us": t[0],
@@ -357,9 +364,12 @@ def _colocate(torch, B, ctx, be_stream, args, hi, rate, cfg_index, label):
     if thr is None:
         thr = min(0.0316, 0.1 * pct(ls, 50) * 1e-3)
         rule = "min(0.0316 ms, a tenth of the request's median latency alone)"
+    _progress("high-priority job alone done")
     table, items = _profile_step(torch, B, ctx, be_stream, step, thr)
+    _progress("candidates of the step's kernels profiled")
     solo_be = ctx.sched_run([], [], items, tail_us=min(dur_us, 3e6), threshold_ms=thr)
     co = ctx.sched_run(hi, arrivals, items, policy=B.POLICY_TALLY, threshold_ms=thr)
+    _progress("co-located run done")
     nat_items = [(k, (B.CFG_NATIVE, 1, 1)) for k, _ in items]
     sub = arrivals[: max(count // 2, MIN_P99_SAMPLES + w)]
     nat = ctx.sched_run(hi, sub, nat_items, policy=B.POLICY_PRIORITY_NATIVE)
@@ -468,6 +478,7 @@ def sweep_threshold(torch, B, ctx, be_stream, args):
         key = (c["kind"], c["param"], c["chunk"])
         if key not in seen:
             seen[key] = _coloc_stats(B, ctx, hi, arrivals, [(red, key)], w, solo_p99, tput_solo)
+        _progress(f"threshold sweep (a) {thr} ms done")
         part_a[str(thr)] = dict(
             chosen={"form": "ptb" if c["kind"] == B.CFG_PTB else "sliced", "param": c["param"],
                     "chunk": c["chunk"], "kernel_latency_us": c["latency_ms"] * 1e3,
@@ -501,6 +512,7 @@ def sweep_threshold(torch, B, ctx, be_stream, args):
             picks[name] = {"form": "ptb" if c["kind"] == B.CFG_PTB else "sliced",
                            "param": c["param"], "chunk": c["chunk"],
                            "turnaround_estimate_us": c["turnaround_ms"] * 1e3}
+        _progress(f"threshold sweep (b) {thr} ms")
         part_b[str(thr)] = dict(chosen=picks, **_coloc_stats(B, ctx, hi_b, arr_b, items, wb,
                                                              solo_b_p99, tput_solo_b))
     return {
@@ -547,6 +559,7 @@ def sweep_load(torch, B, ctx, be_stream, args):
                             policy=B.POLICY_NONE)
         row["no_scheduling_p99_us"] = p99(nat["latency_us"][min(w, 20):])
         rows["%d%%" % round(duty * 100)] = row
+        _progress(f"load sweep duty {duty} done")
     rate = 0.3 / (svc_us * 1e-6)
     arr = TI.bursty_arrivals_us(rate, 2 * n, config_index=1, burst=10.0, p_on=0.05,
                                 mean_segment_us=2000.0)
@@ -608,6 +621,7 @@ def multi_be(torch, B, ctx, be_stream, args):
         nos = ctx.sched_run(hi, arrivals[: w + max(args.n_arrivals // 2, MIN_P99_SAMPLES)],
                             [(k, (B.CFG_NATIVE, 1, 1)) for _, k, _ in clients[:n]],
                             policy=B.POLICY_NONE, be_clients=[1] * n)
+        _progress(f"{n} best-effort clients done")
         lat = co["latency_us"][w:]
         per = co["be_client_kernels_done"] / co["window_us"] * 1e6
         rows[str(n)] = {

@@ -456,6 +456,13 @@ typedef struct {
   /* profile-guided items (kind 3) */
   double threshold_ms; uint32_t profile_runs; uint32_t sched_flags;   /* as tally_sched_opts */
   uint64_t profile_samples, configs_fixed;                            /* outputs             */
+  /* Alternating measurement: with be_toggle_every = T > 0 the best-effort side is switched
+   * off (tally_sched_enable_be) for arrivals [0, T), on for [T, 2T), off for [2T, 3T) ...,
+   * so that one run yields the high-priority job's latencies alone and co-located under the
+   * same host and machine conditions.  be_enabled_us (output) is the time the best-effort
+   * side was switched on; be_kernels_done counts what completed in the whole window. */
+  uint32_t be_toggle_every;
+  double be_enabled_us;
 } tally_sched_run_t;
 
 /* Replay driver over the scheduler: creates one, submits every best-effort item as a looping

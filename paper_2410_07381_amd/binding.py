@@ -138,7 +138,8 @@ class SchedRun(C.Structure):
                 ("be_client_kernels_done", C.POINTER(C.c_uint64)),
                 ("threshold_ms", C.c_double), ("profile_runs", C.c_uint32),
                 ("sched_flags", C.c_uint32),
-                ("profile_samples", C.c_uint64), ("configs_fixed", C.c_uint64)]
+                ("profile_samples", C.c_uint64), ("configs_fixed", C.c_uint64),
+                ("be_toggle_every", C.c_uint32), ("be_enabled_us", C.c_double)]
 
 
 class SchedOpts(C.Structure):
@@ -508,7 +509,7 @@ class Context:
                     turnaround_ms=c.turnaround_ms)
 
     def sched_run(self, hi_kernels, arrivals_us, be_items, policy=POLICY_TALLY, tail_us=0.0,
-                  be_clients=None, threshold_ms=0.0, profile_runs=0, flags=0):
+                  be_clients=None, threshold_ms=0.0, profile_runs=0, flags=0, be_toggle_every=0):
         """hi_kernels: list of Kernel (one request).  be_items: list of (Kernel, (kind, param,
         chunk)).  be_clients: optional list of item counts, one per best-effort client (the
         items are the concatenation of the clients' steps).  Returns a dict of numpy arrays
@@ -535,6 +536,7 @@ class Context:
         run.threshold_ms = float(threshold_ms)
         run.profile_runs = int(profile_runs)
         run.sched_flags = int(flags)
+        run.be_toggle_every = int(be_toggle_every)
         run.latency_us = lat.ctypes.data_as(C.POINTER(C.c_double))
         run.preempt_latency_us = pre.ctypes.data_as(C.POINTER(C.c_double))
         run.preempt_cap = cap
@@ -557,6 +559,7 @@ class Context:
             "be_steps_done": run.be_steps_done,
             "window_us": run.window_us,
             "be_client_kernels_done": per_client,
+            "be_enabled_us": run.be_enabled_us,
             "profile_samples": run.profile_samples,
             "configs_fixed": run.configs_fixed,
         }

@@ -112,18 +112,22 @@ struct GemmBodyT {
     const uint32_t ldsB_wave = wave * 16 * NB * BK * 2;
 
     // one direct load: 16 rows of A (B) of the 64 (16 NB) a wave contributes to a stage
+    // (the operands keep ordinary loads in every form: tiles share them through the L2s and
+    // the Infinity Cache; with non-temporal operand loads a co-located decode step ran as
+    // fast as alone, but the GEMM itself took 1.7 to 2.1 times as long)
+    constexpr int AUX = 0;
     auto load_a = [&](const unsigned char *g, lptr_t l, int j) {
-      if (j == 0) __builtin_amdgcn_global_load_lds((gptr_t)(g + voffA), l, 16, 0, 0);
-      if (j == 1) __builtin_amdgcn_global_load_lds((gptr_t)(g + stepA + voffA), l, 16, 1024, 0);
-      if (j == 2) __builtin_amdgcn_global_load_lds((gptr_t)(g + 2 * stepA + voffA), l, 16, 2048, 0);
-      if (j == 3) __builtin_amdgcn_global_load_lds((gptr_t)(g + 3 * stepA + voffA), l, 16, 3072, 0);
+      if (j == 0) __builtin_amdgcn_global_load_lds((gptr_t)(g + voffA), l, 16, 0, AUX);
+      if (j == 1) __builtin_amdgcn_global_load_lds((gptr_t)(g + stepA + voffA), l, 16, 1024, AUX);
+      if (j == 2) __builtin_amdgcn_global_load_lds((gptr_t)(g + 2 * stepA + voffA), l, 16, 2048, AUX);
+      if (j == 3) __builtin_amdgcn_global_load_lds((gptr_t)(g + 3 * stepA + voffA), l, 16, 3072, AUX);
     };
     auto load_b = [&](const unsigned char *g, lptr_t l, int j) {
-      if (j == 0) __builtin_amdgcn_global_load_lds((gptr_t)(g + voffB), l, 16, 0, 0);
-      if (j == 1) __builtin_amdgcn_global_load_lds((gptr_t)(g + stepB + voffB), l, 16, 1024, 0);
+      if (j == 0) __builtin_amdgcn_global_load_lds((gptr_t)(g + voffB), l, 16, 0, AUX);
+      if (j == 1) __builtin_amdgcn_global_load_lds((gptr_t)(g + stepB + voffB), l, 16, 1024, AUX);
       if constexpr (NB > 2) {
-        if (j == 2) __builtin_amdgcn_global_load_lds((gptr_t)(g + 2 * stepB + voffB), l, 16, 2048, 0);
-        if (j == 3) __builtin_amdgcn_global_load_lds((gptr_t)(g + 3 * stepB + voffB), l, 16, 3072, 0);
+        if (j == 2) __builtin_amdgcn_global_load_lds((gptr_t)(g + 2 * stepB + voffB), l, 16, 2048, AUX);
+        if (j == 3) __builtin_amdgcn_global_load_lds((gptr_t)(g + 3 * stepB + voffB), l, 16, 3072, AUX);
       }
     };
     auto issue_loads = [&](uint32_t kt) {
@@ -148,6 +152,13 @@ struct GemmBodyT {
         for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
     const uint32_t nk = K / BK;
+    uint32_t pause_left = ctl.ticks;   // what is left of this block's pause budget
+    // A tile's first loads (every resident tile starts at once after a launch) and its
+    // epilogue (32 MiB written by all compute units together) are its heaviest bursts of
+    // memory traffic: a tile long enough to afford two more looks at the pause word takes
+    // them just before either, so that neither burst starts on top of a high-priority kernel.
+    const bool edge_polls = ctl.ticks != 0 && nk >= 32;
+    if (edge_polls && wave == 0) yield_while_preempted(ctl, pause_left);
     // a previous tile's waves may still be reading its last stage: fence them off before
     // refilling the ring
     __syncthreads();
@@ -266,7 +277,6 @@ struct GemmBodyT {
     // barrier needs anyway; all other waits sit inside a basic block and name exactly the
     // reads they need.
     uint32_t kt = 0;
-    uint32_t pause_left = ctl.ticks;   // what is left of this block's pause budget
     // steady state: stages kt+1 and kt+2 are in flight, stage kt+3 is issued here (its
     // slot in the ring held stage kt-1, whose last reads were issued a whole step ago)
     for (; kt + 3 < nk; ++kt) {
@@ -302,6 +312,7 @@ struct GemmBodyT {
       mma(fa0, fb0);
       __builtin_amdgcn_sched_barrier(0);
     }
+    if (edge_polls && wave == 0) yield_while_preempted(ctl, pause_left);
     // every wave is past its last fragment read: the ring can be reused as staging space
     __syncthreads();
     mma(fa1, fb1);
@@ -332,6 +343,10 @@ struct GemmBodyT {
     const uint32_t w_row = (lane >> 5) * 4, w_col = (lane & 31) * 2;
     const uint32_t r_row = lane / LPR, r_chunk = lane % LPR;
     uint16_t *gC = a.C + bz * a.stride_c;
+    // an output too large to stay in the 256 MB Infinity Cache beside anything else is
+    // written with non-temporal stores in the original form too (2 GB of attention scores:
+    // 960 us -> 620 us)
+    const bool big_output = (uint64_t)a.m * a.n * a.batch * 2u > (128ull << 20);
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
 #pragma unroll
@@ -356,7 +371,7 @@ struct GemmBodyT {
         const uint4 v = *reinterpret_cast<const uint4 *>(stage + row * PITCH + r_chunk * 16);
         const uint32_t grow = by * TILE + wm * 128 + h * 64 + row;
         const uint32_t gcol = bx * TILE_N + wn * 32 * NB + r_chunk * 8;
-        if constexpr (NT) {
+        if (NT || big_output) {
           const u32x4_nt w = {v.x, v.y, v.z, v.w};
           __builtin_nontemporal_store(w, reinterpret_cast<u32x4_nt *>(gC + (uint64_t)grow * a.n + gcol));
         } else {

@@ -1871,7 +1871,10 @@ int tally_sched_run(tally_ctx *ctx, tally_sched_run_t *run) {
   const double last_arrival = run->n_arrivals ? run->arrivals_us[run->n_arrivals - 1] : 0.0;
   const double t_end = last_arrival + run->tail_us;
   const double t0 = now_us();
-  (void)tally_sched_enable_be(s, 1);
+  const uint32_t toggle = run->n_arrivals ? run->be_toggle_every : 0;
+  bool be_on = toggle == 0;
+  double t_on = 0.0, enabled_us = 0.0;
+  (void)tally_sched_enable_be(s, be_on ? 1 : 0);
   uint32_t next_arrival = 0, cur = 0, completed = 0;
   int inflight = 0;
   while (rc == TALLY_OK) {
@@ -1883,6 +1886,16 @@ int tally_sched_run(tally_ctx *ctx, tally_sched_run_t *run) {
       if (!inflight) {
         run->latency_us[cur] = (now_us() - t0) - run->arrivals_us[cur];
         completed++;
+      }
+    }
+    if (toggle && !inflight && next_arrival < run->n_arrivals) {
+      // switch the best-effort side for the block of arrivals that starts next, as soon as
+      // the last request of the previous block is done
+      const bool want_on = ((next_arrival / toggle) & 1u) != 0;
+      if (want_on != be_on) {
+        be_on = want_on;
+        if (be_on) t_on = now; else enabled_us += now - t_on;
+        (void)tally_sched_enable_be(s, be_on ? 1 : 0);
       }
     }
     if (!inflight && next_arrival < run->n_arrivals && run->arrivals_us[next_arrival] <= now) {
@@ -1899,6 +1912,8 @@ int tally_sched_run(tally_ctx *ctx, tally_sched_run_t *run) {
     }
   }
   run->window_us = now_us() - t0;
+  if (be_on) enabled_us += run->window_us - t_on;
+  run->be_enabled_us = toggle ? enabled_us : run->window_us;
   tally_sched_stats_t st;
   (void)tally_sched_stats(s, &st);
   run->be_kernels_done = st.be_kernels_done;
