@@ -282,11 +282,12 @@ def main():
     # Blocks of 100 arrivals alternate between "best-effort side switched off" (the job
     # alone) and "on" (co-located), so both populations see the same host noise and the
     # same machine state; a run holds Wm warm-up arrivals, then K alone and K co-located.
-    # The first SETTLE arrivals of every block are left out (the switch takes a best-effort
-    # kernel's drain, or its launch, to take effect).
-    T, SETTLE = PERIODS_PER_STEP, 5
+    # Every block starts with SETTLE extra arrivals that are left out (the switch takes a
+    # best-effort kernel's drain, or its launch, to take effect).
+    SETTLE = 5
+    T = PERIODS_PER_STEP + SETTLE                  # a block: 5 arrivals to settle, 100 that count
     Wb = -(-Wm // (2 * T)) * 2 * T                 # warm-up rounded up to whole block pairs
-    arrivals = TI.periodic_arrivals_us(args.period_us, Wb + 2 * K)
+    arrivals = TI.periodic_arrivals_us(args.period_us, Wb + 2 * args.steps * T)
     idx = np.arange(len(arrivals))
     timed = (idx >= Wb) & (idx % T >= SETTLE)
     solo_mask = timed & ((idx // T) % 2 == 0)
@@ -404,7 +405,7 @@ def main():
                                f"4096x4096 every {args.period_us:.0f} us",
                    "step": f"{PERIODS_PER_STEP} high-priority periods (arrivals) co-located with the "
                            f"best-effort job, preceded by {PERIODS_PER_STEP} periods alone as their baseline "
-                           "(blocks alternate inside one run; the first 5 arrivals of a block are left out)",
+                           "(blocks alternate inside one run; each block starts with 5 more arrivals that are left out)",
                    "arrivals_per_step": PERIODS_PER_STEP, "timed_arrivals_per_run": n_run,
                    "be_config": choice,
                    "period_us": args.period_us, "gpu_max_hw_queues": hwq},

@@ -113,14 +113,16 @@ struct GemmBodyT {
 
     // one direct load: 16 rows of A (B) of the 64 (16 NB) a wave contributes to a stage
     // (the operands keep ordinary loads in every form: tiles share them through the L2s and
-    // the Infinity Cache; with non-temporal operand loads a co-located decode step ran as
-    // fast as alone, but the GEMM itself took 1.7 to 2.1 times as long)
+    // the Infinity Cache; with non-temporal loads of both operands a co-located decode step
+    // ran as fast as alone, but the GEMM itself took 1.7 to 2.1 times as long, and with
+    // non-temporal loads of A alone 1.1 to 1.4 times for a tenth off the decode step)
     constexpr int AUX = 0;
+    constexpr int AUXA = 0;
     auto load_a = [&](const unsigned char *g, lptr_t l, int j) {
-      if (j == 0) __builtin_amdgcn_global_load_lds((gptr_t)(g + voffA), l, 16, 0, AUX);
-      if (j == 1) __builtin_amdgcn_global_load_lds((gptr_t)(g + stepA + voffA), l, 16, 1024, AUX);
-      if (j == 2) __builtin_amdgcn_global_load_lds((gptr_t)(g + 2 * stepA + voffA), l, 16, 2048, AUX);
-      if (j == 3) __builtin_amdgcn_global_load_lds((gptr_t)(g + 3 * stepA + voffA), l, 16, 3072, AUX);
+      if (j == 0) __builtin_amdgcn_global_load_lds((gptr_t)(g + voffA), l, 16, 0, AUXA);
+      if (j == 1) __builtin_amdgcn_global_load_lds((gptr_t)(g + stepA + voffA), l, 16, 1024, AUXA);
+      if (j == 2) __builtin_amdgcn_global_load_lds((gptr_t)(g + 2 * stepA + voffA), l, 16, 2048, AUXA);
+      if (j == 3) __builtin_amdgcn_global_load_lds((gptr_t)(g + 3 * stepA + voffA), l, 16, 3072, AUXA);
     };
     auto load_b = [&](const unsigned char *g, lptr_t l, int j) {
       if (j == 0) __builtin_amdgcn_global_load_lds((gptr_t)(g + voffB), l, 16, 0, AUX);

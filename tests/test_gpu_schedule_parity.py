@@ -299,6 +299,47 @@ def test_async_flag_preemption_prefix_and_exactly_once(env, workers, chunk):
     assert_close_rel(host(partial)[idx], want, 2e-6)
 
 
+def test_many_preemptions_in_a_row_keep_exactly_once(env):
+    """Sixty asynchronous preempt / drain / resume cycles on one job: the task counter is
+    never reset (the base moves after every drain, the word accumulates every failed fetch
+    and 2^31 per request, wrapping several times), yet every block runs exactly once, each
+    drain leaves a prefix, and the segments are the ones the oracle gets from the same
+    progress values."""
+    B, ctx, torch = env
+    from gpu_util import host, assert_cover_equal, oracle_block_sums, assert_close_rel
+    n = 1 << 28
+    x = torch.rand(n, device="cuda")
+    nb = n // 4096
+    partial = torch.zeros(nb, device="cuda")
+    torch.cuda.synchronize()
+    k = B.reduce_sum(x, partial)
+    workers, chunk = 256, 4                      # slow enough (about 0.3 ms alone) to be caught
+    pts = []
+    job = ctx.launch_ptb(k, workers, chunk=chunk, coverage=True)
+    for cycle in range(60):
+        job.preempt()
+        st = job.wait()
+        done = job.progress()[0]
+        if st == B.JOB_COMPLETE:
+            break
+        assert st == B.JOB_STOPPED and done % chunk == 0 and (not pts or done >= pts[-1])
+        pts.append(done)
+        job.resume()
+    assert job.wait() == B.JOB_COMPLETE
+    rec = job.coverage()
+    job.free()
+    assert len(pts) >= 10, pts
+    assert (rec["count"] == 1).all()
+    # (a request that found nothing new to stop repeats the progress value: an empty segment,
+    # on the GPU and in the oracle alike)
+    cov, log = OS.run_ptb(None, (nb, 1, 1), {}, workers, preempt_points=pts, seed=9, chunk=chunk)
+    assert log == pts + [nb]
+    assert_cover_equal(rec, cov)
+    sample = [0, nb - 1] + [int(v) for v in np.random.default_rng(5).integers(nb, size=500)]
+    idx, want = oracle_block_sums(host(x), sample)
+    assert_close_rel(host(partial)[idx], want, 2e-6)
+
+
 def test_preemption_reaches_workers_that_fill_the_gpu(env):
     """The largest worker count of the softmax kernel leaves no register free on any compute
     unit: the flag must still reach the workers (the relay is resident before them) and the
