@@ -105,6 +105,38 @@ def test_header_is_plain_c():
                                      C.sizeof(B.Config), C.sizeof(B.SchedRun)]
 
 
+def test_every_mirrored_struct_has_the_header_layout(B, tmp_path):
+    """Field by field: a C program that includes only the header prints offsetof() of every
+    field the binding's ctypes structures name (a field the header does not have fails to
+    compile) and sizeof() of every structure; both must be what ctypes computed."""
+    import ctypes as C
+    import subprocess
+    pairs = [(B.Dim3, "tally_dim3"), (B.SaxpyArgs, "tally_saxpy_args"),
+             (B.ReduceSumArgs, "tally_reduce_sum_args"), (B.ReduceFinalArgs, "tally_reduce_final_args"),
+             (B.GemmArgs, "tally_gemm_bf16_args"), (B.GemvArgs, "tally_gemv_bf16_args"),
+             (B.SoftmaxArgs, "tally_softmax_f32_args"), (B.LayerNormArgs, "tally_layernorm_f32_args"),
+             (B.AttnDecodeArgs, "tally_attn_decode_args"), (B.KernelDesc, "tally_kernel_desc"),
+             (B.CoverRec, "tally_cover_rec"), (B.Config, "tally_config"), (B.BeItem, "tally_be_item"),
+             (B.SchedRun, "tally_sched_run_t"), (B.SchedOpts, "tally_sched_opts"),
+             (B.SchedStats, "tally_sched_stats_t")]
+    lines, want = [], []
+    for cls, cname in pairs:
+        lines.append('printf("%%zu\\n", sizeof(%s));' % cname)
+        want.append(C.sizeof(cls))
+        for fname, _ in cls._fields_:
+            lines.append('printf("%%zu\\n", offsetof(%s, %s));' % (cname, fname))
+            want.append(getattr(cls, fname).offset)
+    src = tmp_path / "layout.c"
+    src.write_text('#include <stdio.h>\n#include <stddef.h>\n#include "tally.h"\nint main(void){\n'
+                   + "\n".join(lines) + "\nreturn 0;}\n")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    exe = tmp_path / "layout"
+    subprocess.run(["gcc", "-std=c99", "-I", os.path.join(root, "include"), str(src), "-o", str(exe)],
+                   check=True, timeout=60)
+    got = [int(v) for v in subprocess.run([str(exe)], capture_output=True, text=True, timeout=10).stdout.split()]
+    assert got == want
+
+
 def test_static_scratch_is_a_global_symbol_of_the_device_code(B, tmp_path):
     """The runtime finds a device variable by name among the code object's global symbols.
     A file-scope static device array referenced from host code is given global binding by
