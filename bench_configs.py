@@ -642,9 +642,12 @@ def multi_be(torch, B, ctx, be_stream, args):
                             policy=B.POLICY_NONE, be_clients=[1] * n)
         _progress(f"{n} best-effort clients done")
         lat = co["latency_us"][w:]
+        devside = (co["latency_us"] - co["issue_us"])[w:]
         per = co["be_client_kernels_done"] / co["window_us"] * 1e6
         rows[str(n)] = {
             "hi_p50_us": pct(lat, 50), "hi_p99_us": p99(lat),
+            "hi_launch_calls_p50_us": pct(co["issue_us"][w:], 50),
+            "hi_device_side_p50_us": pct(devside, 50), "hi_device_side_p99_us": p99(devside),
             "hi_p99_overhead_pct": ovh(p99(lat), solo_p99),
             "no_scheduling_p99_us": p99(nos["latency_us"][w:]),
             "n_preempts": int(co["n_preempts"]),
@@ -659,6 +662,8 @@ def multi_be(torch, B, ctx, be_stream, args):
                     "4096^3; persistent workers, one stream pair each) vs hi-pri bf16 GEMV 4096x4096 "
                     "every 1000 us",
         "hi_solo_p50_us": solo_p50, "hi_solo_p99_us": solo_p99,
+        "hi_solo_launch_calls_p50_us": pct(solo["issue_us"][w:], 50),
+        "hi_solo_device_side_p50_us": pct((solo["latency_us"] - solo["issue_us"])[w:], 50),
         "turnaround_threshold_ms": thr, "client_configs": picks,
         "client_alone_kernels_per_s": alone,
         "note": "a client's share is relative to its kernel run natively, alone",

@@ -297,6 +297,19 @@ int tally_last_hip_error(void);
 const char *tally_strerror(int status);
 int tally_device_info(uint32_t *num_cus, uint32_t *lds_bytes_per_cu, uint32_t *wave_size);
 
+/* Hardware queues (Section 4.2: a high-priority kernel is dispatched the moment it arrives).
+ * The command processor serves its queues through four pipes.  A kernel resident on a queue
+ * of the high-priority queue's pipe, or two kernels resident on queues that share another
+ * pipe, delay the start of every high-priority kernel by about 10 us.  The library measures
+ * this when it creates a stream for resident best-effort work (relays; the further clients'
+ * stream pairs) and sets aside streams that, busy beside the ones already in use, delay the
+ * high-priority one.  *be_delays_hi: bit 0, the caller's own best-effort stream does
+ * (create the two streams one right after the other to avoid it); bit 1, more streams were
+ * needed than there are free pipes (from the second best-effort client on) and one was
+ * taken although it delays.  *set_aside: streams created and left unused so far.  Either
+ * pointer may be null. */
+int tally_stream_report(tally_ctx *ctx, int *be_delays_hi, uint32_t *set_aside);
+
 /* ---- profile-guided configuration (Section 4.2) ------------------------------------ */
 
 typedef struct {

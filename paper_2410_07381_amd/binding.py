@@ -48,7 +48,7 @@ EXPORTS = [
     "tally_resume", "tally_progress", "tally_pump", "tally_wait", "tally_job_free",
     "tally_launch_ptb_until", "tally_resume_until", "tally_coverage", "tally_marker",
     "tally_marker_read", "tally_last_preempt_latency_us", "tally_last_hip_error",
-    "tally_strerror", "tally_max_workers", "tally_kernel_footprint", "tally_mfma_ceiling_tflops", "tally_device_info", "tally_ptb_turnaround_ms", "tally_select_config",
+    "tally_strerror", "tally_max_workers", "tally_kernel_footprint", "tally_mfma_ceiling_tflops", "tally_device_info", "tally_stream_report", "tally_ptb_turnaround_ms", "tally_select_config",
     "tally_profile", "tally_lookup_config", "tally_sched_run", "tally_set_yield_bound_us",
     "tally_launch_attn_decode_static", "tally_preempt_pausing", "tally_end_pause",
     "tally_candidate_configs", "tally_profile_table", "tally_profile_reset",
@@ -194,6 +194,7 @@ def _load():
         "tally_last_hip_error": ([], i32),
         "tally_strerror": ([i32], C.c_char_p),
         "tally_device_info": ([P(u32), P(u32), P(u32)], i32),
+        "tally_stream_report": ([vp, P(i32), P(u32)], i32),
         "tally_ptb_turnaround_ms": ([dbl, u32, u32, u64], dbl),
         "tally_select_config": ([P(Config), u32, dbl], i32),
         "tally_profile": ([vp, P(KernelDesc), P(Config), u32, u32, dbl, P(u32)], i32),
@@ -431,6 +432,13 @@ class Context:
 
     def set_yield_bound_us(self, us):
         _check(_lib.tally_set_yield_bound_us(self.h, int(us)), "tally_set_yield_bound_us")
+
+    def stream_report(self):
+        """Whether the caller's best-effort stream delays the high-priority one, and how many
+        streams the library created and set aside because they would."""
+        a, b = C.c_int(), C.c_uint32()
+        _check(_lib.tally_stream_report(self.h, C.byref(a), C.byref(b)), "tally_stream_report")
+        return {"be_delays_hi": bool(a.value & 1), "crowded": bool(a.value & 2), "set_aside": b.value}
 
     def set_yield_every(self, steps):
         _check(_lib.tally_set_yield_every(self.h, int(steps)), "tally_set_yield_every")

@@ -338,6 +338,13 @@ __global__ void marker_kernel(uint32_t *word, uint32_t value) {
     __hip_atomic_store(word, value, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
 }
 
+// One idle wave that stays on the GPU for `ticks` of the 100 MHz clock and then leaves
+// (what a stream is kept busy with while its effect on another stream is measured).
+__global__ void hold_kernel(uint32_t ticks) {
+  const unsigned long long t0 = wall_clock64();
+  while (wall_clock64() - t0 < (unsigned long long)ticks) __builtin_amdgcn_s_sleep(32);
+}
+
 __global__ void set_word_kernel(uint32_t *word, uint32_t value) {
   if (threadIdx.x == 0)
     __hip_atomic_store(word, value, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);

@@ -298,6 +298,8 @@ const KernelOps kOps[TALLY_K_COUNT] = {
 
 constexpr size_t kMaxArgs = 96;
 constexpr int kSlots = 64;
+constexpr int kMaxShunned = 64;
+constexpr int kMaxSide = 2 * 8 + 2;
 constexpr int kMaxBeClients = 8;
 constexpr size_t kDevSlotBytes = 512;   // counter | pre | exited, 128 B apart
 constexpr size_t kHostSlotBytes = 256;  // host_flag | status,live,raw,relay,relay_flags | slice_done
@@ -338,6 +340,15 @@ struct tally_ctx {
   // best-effort client's own pair while it launches for that client
   hipStream_t cur_be, cur_ctl;
   hipStream_t client_be[kMaxBeClients], client_ctl[kMaxBeClients];  // owned, [0] unused
+  // streams that were created and found to delay the high-priority stream (same hardware
+  // pipe): never used, kept until the context goes so that their queues stay taken
+  hipStream_t shunned[kMaxShunned];
+  int n_shunned;
+  hipStream_t side[kMaxSide];   // the caller's best-effort stream and the streams chosen so far
+  int n_side;
+  bool side_crowded;            // a stream had to be taken although it delays the high-priority one
+  uint32_t probe_seq;
+  bool be_delays_hi;         // the caller's best-effort stream shares the high-priority one's pipe
   unsigned char *dev_pool;   // device
   uint32_t *copy_pool;       // device: per slot, kFlagCopies copies of the flag word
   unsigned char *host_pool;  // pinned host
@@ -646,6 +657,76 @@ int launch_be_item(tally_ctx *ctx, const tally_be_item *it, tally_job **out);
 }  // namespace
 
 // ================================================================================ C ABI
+namespace {
+
+// Do kernels resident on `other` and on the streams in `also`, all at once, delay kernels
+// on the high-priority stream?  The GPU's command processor serves its hardware queues
+// through four pipes, and HIP hands streams to hardware queues in turn.  Measured on this
+// part with one idle wave held per stream: a queue on the high-priority queue's own pipe
+// (the stream created four, eight, twelve streams later) delays the start of every
+// high-priority kernel by about 10 us (a 7 us request: 21 us instead of 11 us on the
+// device), and so do TWO resident queues that share any other pipe, although either alone
+// does not; three resident queues on three different pipes cost nothing.  (With
+// GPU_MAX_HW_QUEUES at its default two streams may even be one queue and run one after the
+// other.)  Persistent workers and their relays stay resident for a whole kernel, so the
+// streams that carry them are chosen by this measurement, neither HIP nor the driver
+// telling which queue a stream got: the shortest of a few marker round trips on the
+// high-priority stream, first with everything idle, then with the streams held busy.
+bool delays_hi_stream(tally_ctx *ctx, hipStream_t other, const hipStream_t *also, int n_also) {
+  uint32_t *word_dev = ctx->marker_dev + 16, *word_host = ctx->marker_host + 16;
+  auto round_trip_us = [&](int reps) {
+    double best = 1e30;
+    for (int i = 0; i < reps; ++i) {
+      const uint32_t v = ++ctx->probe_seq;
+      const double t0 = now_us();
+      hipLaunchKernelGGL(marker_kernel, dim3(1), dim3(64), 0, ctx->hi, word_dev, v);
+      if (hipGetLastError() != hipSuccess) return 0.0;
+      while (__atomic_load_n(word_host, __ATOMIC_ACQUIRE) != v && now_us() - t0 < 2.0e5) {}
+      const double dt = now_us() - t0;
+      if (dt < best) best = dt;
+    }
+    return best;
+  };
+  auto sync_all = [&]() {
+    bool ok = hipStreamSynchronize(ctx->hi) == hipSuccess && hipStreamSynchronize(other) == hipSuccess;
+    for (int i = 0; i < n_also; ++i) ok = (hipStreamSynchronize(also[i]) == hipSuccess) && ok;
+    return ok;
+  };
+  if (!sync_all()) return false;
+  const double idle = round_trip_us(8);
+  for (int i = 0; i <= n_also; ++i) {
+    hipLaunchKernelGGL(hold_kernel, dim3(1), dim3(64), 0, i < n_also ? also[i] : other, 60000u);   // 600 us
+    if (hipGetLastError() != hipSuccess) { (void)sync_all(); return false; }
+  }
+  const double t0 = now_us();
+  while (now_us() - t0 < 40.0) {}                       // let them start
+  const double busy = round_trip_us(8);
+  (void)sync_all();
+  return busy > idle + 4.0;
+}
+
+// A new stream for resident best-effort work (workers, relays) that, busy together with
+// the streams already chosen for such work, does not delay the high-priority stream.
+// Streams that do are set aside.  Four pipes: after four candidates in a row that do, there
+// is no better one to be had (more resident queues than free pipes) and the last is taken.
+hipError_t make_side_stream(tally_ctx *ctx, hipStream_t *out) {
+  for (int tries = 0;; ++tries) {
+    hipStream_t s;
+    hipError_t e = hipStreamCreateWithFlags(&s, hipStreamNonBlocking);
+    if (e != hipSuccess) return e;
+    const bool delays = delays_hi_stream(ctx, s, ctx->side, ctx->n_side);
+    if (!delays || tries >= 3 || ctx->n_shunned >= kMaxShunned) {
+      if (delays) ctx->side_crowded = true;
+      if (ctx->n_side < kMaxSide) ctx->side[ctx->n_side++] = s;
+      *out = s;
+      return hipSuccess;
+    }
+    ctx->shunned[ctx->n_shunned++] = s;
+  }
+}
+
+}  // namespace
+
 extern "C" {
 
 int tally_create(tally_ctx **out, void *hip_stream_hi, void *hip_stream_be) {
@@ -668,11 +749,15 @@ int tally_create(tally_ctx **out, void *hip_stream_hi, void *hip_stream_be) {
   memset(c->slot_epoch, 0, sizeof(c->slot_epoch));
   c->live_jobs = 0;
   c->next_slot = 0;
+  c->n_shunned = 0;
+  c->n_side = 0;
+  c->side_crowded = false;
+  c->probe_seq = 0;
+  c->ctl = nullptr;
   hipError_t e;
   int dev = 0;
   hipDeviceProp_t prop;
   if ((e = hipGetDevice(&dev)) != hipSuccess || (e = hipGetDeviceProperties(&prop, dev)) != hipSuccess ||
-      (e = hipStreamCreateWithFlags(&c->ctl, hipStreamNonBlocking)) != hipSuccess ||
       (e = hipMalloc((void **)&c->dev_pool, kSlots * kDevSlotBytes)) != hipSuccess ||
       (e = hipMemset(c->dev_pool, 0, kSlots * kDevSlotBytes)) != hipSuccess ||
       (e = hipMalloc((void **)&c->copy_pool, kSlots * kCopySlotBytes)) != hipSuccess ||
@@ -693,6 +778,20 @@ int tally_create(tally_ctx **out, void *hip_stream_hi, void *hip_stream_be) {
   }
   memset(c->host_pool, 0, kSlots * kHostSlotBytes);
   memset(c->marker_host, 0, 256);
+  // the relays' stream: one that, busy beside the best-effort stream, does not hold up the
+  // high-priority stream
+  c->side[c->n_side++] = c->be;
+  if ((e = make_side_stream(c, &c->ctl)) != hipSuccess) {
+    g_last_hip = (int)e;
+    for (int i = 0; i < c->n_shunned; ++i) (void)hipStreamDestroy(c->shunned[i]);
+    (void)hipFree(c->dev_pool);
+    (void)hipFree(c->copy_pool);
+    (void)hipHostFree(c->host_pool);
+    (void)hipHostFree(c->marker_host);
+    delete c;
+    return TALLY_ERR_HIP;
+  }
+  c->be_delays_hi = delays_hi_stream(c, c->be, nullptr, 0);
   c->cur_be = c->be;
   c->cur_ctl = c->ctl;
   c->num_cus = (uint32_t)prop.multiProcessorCount;
@@ -742,6 +841,7 @@ int tally_destroy(tally_ctx *ctx) {
   (void)hipStreamSynchronize(ctx->be);
   (void)hipStreamSynchronize(ctx->ctl);
   (void)hipStreamDestroy(ctx->ctl);
+  for (int i = 0; i < ctx->n_shunned; ++i) (void)hipStreamDestroy(ctx->shunned[i]);
   for (int i = 0; i < kMaxBeClients; ++i) {
     if (ctx->client_be[i]) { (void)hipStreamSynchronize(ctx->client_be[i]); (void)hipStreamDestroy(ctx->client_be[i]); }
     if (ctx->client_ctl[i]) { (void)hipStreamSynchronize(ctx->client_ctl[i]); (void)hipStreamDestroy(ctx->client_ctl[i]); }
@@ -1073,6 +1173,13 @@ int tally_device_info(uint32_t *num_cus, uint32_t *lds_bytes_per_cu, uint32_t *w
   if (num_cus) *num_cus = (uint32_t)prop.multiProcessorCount;
   if (lds_bytes_per_cu) *lds_bytes_per_cu = (uint32_t)prop.maxSharedMemoryPerMultiProcessor;
   if (wave_size) *wave_size = (uint32_t)prop.warpSize;
+  return TALLY_OK;
+}
+
+int tally_stream_report(tally_ctx *ctx, int *be_delays_hi, uint32_t *set_aside) {
+  if (!ctx) return TALLY_ERR_INVALID_ARG;
+  if (be_delays_hi) *be_delays_hi = (ctx->be_delays_hi ? 1 : 0) | (ctx->side_crowded ? 2 : 0);
+  if (set_aside) *set_aside = (uint32_t)ctx->n_shunned;
   return TALLY_OK;
 }
 
@@ -1649,9 +1756,8 @@ int tally_sched_create(tally_ctx *ctx, const tally_sched_opts *opts, tally_sched
       s->clients[c].ctl = ctx->ctl;
     } else {  // further clients get a stream pair of their own, made once per context
       hipError_t e = hipSuccess;
-      if (!ctx->client_be[c]) e = hipStreamCreateWithFlags(&ctx->client_be[c], hipStreamNonBlocking);
-      if (e == hipSuccess && !ctx->client_ctl[c])
-        e = hipStreamCreateWithFlags(&ctx->client_ctl[c], hipStreamNonBlocking);
+      if (!ctx->client_be[c]) e = make_side_stream(ctx, &ctx->client_be[c]);
+      if (e == hipSuccess && !ctx->client_ctl[c]) e = make_side_stream(ctx, &ctx->client_ctl[c]);
       if (e != hipSuccess) { g_last_hip = (int)e; delete s; return TALLY_ERR_HIP; }
       s->clients[c].be = ctx->client_be[c];
       s->clients[c].ctl = ctx->client_ctl[c];
