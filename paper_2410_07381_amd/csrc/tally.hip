@@ -692,7 +692,10 @@ bool delays_hi_stream(tally_ctx *ctx, hipStream_t other, const hipStream_t *also
     for (int i = 0; i < n_also; ++i) ok = (hipStreamSynchronize(also[i]) == hipSuccess) && ok;
     return ok;
   };
-  if (!sync_all()) return false;
+  // a stream gets its hardware queue with its first kernel, which takes a millisecond:
+  // let that happen before anything is timed
+  hipLaunchKernelGGL(hold_kernel, dim3(1), dim3(64), 0, other, 1u);
+  if (hipGetLastError() != hipSuccess || !sync_all()) return false;
   const double idle = round_trip_us(8);
   for (int i = 0; i <= n_also; ++i) {
     hipLaunchKernelGGL(hold_kernel, dim3(1), dim3(64), 0, i < n_also ? also[i] : other, 60000u);   // 600 us
@@ -702,6 +705,9 @@ bool delays_hi_stream(tally_ctx *ctx, hipStream_t other, const hipStream_t *also
   while (now_us() - t0 < 40.0) {}                       // let them start
   const double busy = round_trip_us(8);
   (void)sync_all();
+  if (getenv("TALLY_DEBUG_STREAMS"))
+    fprintf(stderr, "[tally] stream %p beside %d others: marker round trip %.1f us idle, %.1f us busy\n",
+            (void *)other, n_also, idle, busy);
   return busy > idle + 4.0;
 }
 
