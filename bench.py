@@ -201,12 +201,14 @@ def main():
     torch.cuda.set_device(0)
     hi_stream, be_stream = torch.cuda.Stream(), torch.cuda.Stream()
     ctx = B.Context(hi_stream, be_stream)
+    streams = ctx.stream_report()
 
     if args.workload != "cfg1":
         import bench_configs
         out = bench_configs.WORKLOADS[args.workload](torch, B, ctx, be_stream, args)
         out.update({"n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "data": "synthetic",
                     "arrivals_per_step": PERIODS_PER_STEP, "gpu_max_hw_queues": hwq})
+        out["streams"] = ctx.stream_report()
         ctx.close()
         print(json.dumps(out))
         return
@@ -408,7 +410,7 @@ def main():
                            "(blocks alternate inside one run; each block starts with 5 more arrivals that are left out)",
                    "arrivals_per_step": PERIODS_PER_STEP, "timed_arrivals_per_run": n_run,
                    "be_config": choice,
-                   "period_us": args.period_us, "gpu_max_hw_queues": hwq},
+                   "period_us": args.period_us, "gpu_max_hw_queues": hwq, "streams": streams},
         "hi_pri_latency_us": host_side,
         "hi_pri_device_side_latency_us": dict(
             device_side, definition="completion observed minus the moment the request's launch "

@@ -33,6 +33,47 @@ def _wait_for(cond, seconds=20.0):
     return False
 
 
+def test_streams_for_resident_work_do_not_delay_the_high_priority_stream(env):
+    """The relays' stream (and the clients' pairs, made the same way) is chosen by
+    measurement: held busy by one idle wave beside the best-effort stream, it must not slow
+    marker round trips on the high-priority stream.  Checked here from outside, with the
+    public calls only: the same round trips, with a persistent-worker job of one worker (its
+    relay and its worker resident, nothing else on the GPU) and without."""
+    B, ctx, torch = env
+    rep = ctx.stream_report()
+    assert set(rep) == {"be_delays_hi", "crowded", "set_aside"}
+    assert not rep["be_delays_hi"] and not rep["crowded"]     # the fixture makes its two streams together
+    x = torch.zeros(1 << 24, device="cuda")
+    y = torch.zeros(1 << 24, device="cuda")
+    torch.cuda.synchronize()
+    seq = [ctx.marker_read(hi=True)]
+
+    def round_trip_us(n=40):
+        best = 1e9
+        for _ in range(n):
+            seq[0] = (seq[0] + 1) & 0x7FFFFFFF
+            t0 = time.perf_counter()
+            ctx.marker(seq[0], hi=True)
+            while ctx.marker_read(hi=True) != seq[0]:
+                assert time.perf_counter() - t0 < 1.0
+            best = min(best, (time.perf_counter() - t0) * 1e6)
+        return best
+
+    idle = round_trip_us()
+    job = ctx.launch_ptb(B.saxpy(x, y, 1.0), 1)               # 65536 blocks on one worker: long
+    time.sleep(0.0005)
+    busy = round_trip_us()
+    st0 = job.progress()[2]
+    job.preempt()
+    st = job.wait()
+    if st == B.JOB_STOPPED:
+        job.resume()
+        assert job.wait() == B.JOB_COMPLETE
+    job.free()
+    assert st0 == B.JOB_RUNNING                                # it really was resident meanwhile
+    assert busy < idle + 4.0, (idle, busy)
+
+
 def test_candidate_set_follows_section_4_2(env):
     B, ctx, torch = env
     x = torch.rand(1 << 26, device="cuda")
