@@ -298,9 +298,9 @@ const char *tally_strerror(int status);
 int tally_device_info(uint32_t *num_cus, uint32_t *lds_bytes_per_cu, uint32_t *wave_size);
 
 /* Hardware queues (Section 4.2: a high-priority kernel is dispatched the moment it arrives).
- * The command processor serves its queues through four pipes.  A kernel resident on a queue
- * of the high-priority queue's pipe, or two kernels resident on queues that share another
- * pipe, delay the start of every high-priority kernel by about 10 us.  The library measures
+ * The command processors (one per die) serve the queues through four pipes each.  A kernel
+ * resident on a queue that shares the high-priority queue's pipe, on any die, delays the
+ * start of every high-priority kernel with workgroups there by about 10 us.  The library measures
  * this when it creates a stream for resident best-effort work (relays; the further clients'
  * stream pairs) and sets aside streams that, busy beside the ones already in use, delay the
  * high-priority one.  *be_delays_hi: bit 0, the caller's own best-effort stream does

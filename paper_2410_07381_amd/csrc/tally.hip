@@ -660,18 +660,20 @@ int launch_be_item(tally_ctx *ctx, const tally_be_item *it, tally_job **out);
 namespace {
 
 // Do kernels resident on `other` and on the streams in `also`, all at once, delay kernels
-// on the high-priority stream?  The GPU's command processor serves its hardware queues
-// through four pipes, and HIP hands streams to hardware queues in turn.  Measured on this
-// part with one idle wave held per stream: a queue on the high-priority queue's own pipe
-// (the stream created four, eight, twelve streams later) delays the start of every
-// high-priority kernel by about 10 us (a 7 us request: 21 us instead of 11 us on the
-// device), and so do TWO resident queues that share any other pipe, although either alone
-// does not; three resident queues on three different pipes cost nothing.  (With
-// GPU_MAX_HW_QUEUES at its default two streams may even be one queue and run one after the
-// other.)  Persistent workers and their relays stay resident for a whole kernel, so the
+// on the high-priority stream?  The GPU's command processors (one per die) serve the
+// hardware queues through four pipes each, and HIP hands streams to hardware queues in the
+// order of their first use.  Measured on this part, with one idle wave held per stream: a
+// resident kernel on a queue that shares the high-priority queue's pipe delays the start
+// of every high-priority kernel by 8 to 10 us (a 7 us request: 21 us instead of 11 us on the
+// device); any number of resident kernels on the other pipes cost nothing.  The sharing can
+// differ from die to die: with two best-effort clients one of the four streams in use
+// delayed every high-priority kernel that had workgroups on all dies by 11 to 16 us and a
+// one-workgroup kernel not at all, so the probe kernel below has workgroups on every die.
+// (With GPU_MAX_HW_QUEUES at its default two streams may even be one queue and run one after
+// the other.)  Persistent workers and their relays stay resident for a whole kernel, so the
 // streams that carry them are chosen by this measurement, neither HIP nor the driver
-// telling which queue a stream got: the shortest of a few marker round trips on the
-// high-priority stream, first with everything idle, then with the streams held busy.
+// telling which queue a stream got: the shortest of a few round trips on the high-priority
+// stream, first with everything idle, then with the streams held busy.
 bool delays_hi_stream(tally_ctx *ctx, hipStream_t other, const hipStream_t *also, int n_also) {
   uint32_t *word_dev = ctx->marker_dev + 16, *word_host = ctx->marker_host + 16;
   auto round_trip_us = [&](int reps) {
@@ -679,6 +681,9 @@ bool delays_hi_stream(tally_ctx *ctx, hipStream_t other, const hipStream_t *also
     for (int i = 0; i < reps; ++i) {
       const uint32_t v = ++ctx->probe_seq;
       const double t0 = now_us();
+      // a kernel with workgroups on every die, then the marker: a one-workgroup kernel alone
+      // does not feel every conflict (each die's command processor serves its own share)
+      hipLaunchKernelGGL(hold_kernel, dim3(64), dim3(64), 0, ctx->hi, 1u);
       hipLaunchKernelGGL(marker_kernel, dim3(1), dim3(64), 0, ctx->hi, word_dev, v);
       if (hipGetLastError() != hipSuccess) return 0.0;
       while (__atomic_load_n(word_host, __ATOMIC_ACQUIRE) != v && now_us() - t0 < 2.0e5) {}

@@ -36,15 +36,20 @@ def _wait_for(cond, seconds=20.0):
 def test_streams_for_resident_work_do_not_delay_the_high_priority_stream(env):
     """The relays' stream (and the clients' pairs, made the same way) is chosen by
     measurement: held busy by one idle wave beside the best-effort stream, it must not slow
-    marker round trips on the high-priority stream.  Checked here from outside, with the
-    public calls only: the same round trips, with a persistent-worker job of one worker (its
-    relay and its worker resident, nothing else on the GPU) and without."""
+    round trips of a kernel with workgroups on every die on the high-priority stream.  Checked
+    here from outside, with the public calls only: the same round trips, with a
+    persistent-worker job of one worker (its relay and its worker resident, nothing else on the
+    GPU) and without."""
     B, ctx, torch = env
     rep = ctx.stream_report()
     assert set(rep) == {"be_delays_hi", "crowded", "set_aside"}
     assert not rep["be_delays_hi"] and not rep["crowded"]     # the fixture makes its two streams together
     x = torch.zeros(1 << 24, device="cuda")
     y = torch.zeros(1 << 24, device="cuda")
+    torch.cuda.synchronize()
+    px = torch.zeros(1 << 14, device="cuda")
+    py = torch.zeros(1 << 14, device="cuda")
+    probe = B.saxpy(px, py, 1.0)                           # 64 workgroups
     torch.cuda.synchronize()
     seq = [ctx.marker_read(hi=True)]
 
@@ -53,6 +58,7 @@ def test_streams_for_resident_work_do_not_delay_the_high_priority_stream(env):
         for _ in range(n):
             seq[0] = (seq[0] + 1) & 0x7FFFFFFF
             t0 = time.perf_counter()
+            ctx.launch_native(probe, hi=True)              # workgroups on every die, then the marker
             ctx.marker(seq[0], hi=True)
             while ctx.marker_read(hi=True) != seq[0]:
                 assert time.perf_counter() - t0 < 1.0
@@ -72,6 +78,35 @@ def test_streams_for_resident_work_do_not_delay_the_high_priority_stream(env):
     job.free()
     assert st0 == B.JOB_RUNNING                                # it really was resident meanwhile
     assert busy < idle + 4.0, (idle, busy)
+
+
+def test_a_second_client_does_not_delay_requests(env):
+    """Two clients of ONE worker each, never preempted, on an otherwise empty GPU: four
+    resident kernels (two workers, two relays) on four streams.  A request with workgroups
+    on every die must take as long on the device as beside one such client: a stream whose
+    hardware queue shares the high-priority queue's pipe on some die would add 11-16 us to
+    every request, and the library sets such streams aside when it creates the second
+    client's pair."""
+    B, ctx, torch = env
+    gv = TI.gemv_inputs(4096, 4096, config_index=1)
+    x = torch.from_numpy(gv["x"].view(np.int16)).cuda()
+    W = torch.from_numpy(gv["W"].view(np.int16)).cuda()
+    y = torch.zeros(4096, dtype=torch.int16, device="cuda")
+    ax = torch.zeros(1 << 24, device="cuda")
+    ay = torch.zeros(1 << 24, device="cuda")
+    torch.cuda.synchronize()
+    hi = [B.gemv_bf16(x, W, y)]
+    sax = B.saxpy(ax, ay, 1.0)
+    arr = TI.periodic_arrivals_us(1000.0, 300)
+
+    def device_side_p50(n):
+        r = ctx.sched_run(hi, arr, [(sax, (B.CFG_PTB, 1, 1))] * n, policy=B.POLICY_NONE, be_clients=[1] * n)
+        assert (r["latency_us"] > 0).all()
+        return float(np.median((r["latency_us"] - r["issue_us"])[50:]))
+
+    one, two, three = device_side_p50(1), device_side_p50(2), device_side_p50(3)
+    assert two < one + 5.0 and three < one + 5.0, (one, two, three)
+    assert not ctx.stream_report()["crowded"]
 
 
 def test_candidate_set_follows_section_4_2(env):
