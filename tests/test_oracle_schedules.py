@@ -263,3 +263,54 @@ def test_seeded_ptb_runs(grid, workers, pts):
             assert (cov.segment[edges[s]:edges[s + 1]] == s).all()
         for idx in range(total):
             assert tuple(int(v) for v in cov.bidx[idx]) == G.delinearize(idx, grid)
+
+
+# ---- invariants over random grids, worker counts, chunks, preemption points and seeds ---------
+from hypothesis import given, settings, strategies as st  # noqa: E402
+
+
+@settings(max_examples=60, deadline=None)
+@given(gx=st.integers(1, 9), gy=st.integers(1, 5), gz=st.integers(1, 3), workers=st.integers(1, 12),
+       chunk=st.integers(1, 5), seed=st.integers(0, 1000), word0=st.sampled_from([0, 7, (1 << 32) - 3, 1 << 31]),
+       raw_pts=st.lists(st.integers(0, 200), max_size=4), machine=st.sampled_from(["folded", "paper"]))
+def test_ptb_invariants_hold_for_any_run(gx, gy, gz, workers, chunk, seed, word0, raw_pts, machine):
+    """Whatever the grid, the worker count, the chunk, the moments of the requests, the
+    interleaving and the value the shared word starts from (near its wrap-around included):
+    every block runs exactly once with the coordinates of its index, the progress values are
+    non-decreasing, each is a request point rounded up to what the chunks allow and never beyond
+    the grid, and a block's segment is the one whose [start, stop) range holds its index."""
+    grid = (gx, gy, gz)
+    total = G.total_blocks(grid)
+    pts = sorted(p % (total + 1) for p in raw_pts)
+    kw = {"word0": word0} if machine == "folded" else {}
+    cov, log = S.run_ptb(None, grid, {}, workers, preempt_points=pts, seed=seed, chunk=chunk,
+                         machine=machine, **kw)
+    assert cov.exactly_once()
+    assert log[-1] == total and all(a <= b for a, b in zip(log, log[1:]))
+    assert all(0 <= p <= total for p in log)
+    edges = [0] + log
+    for s in range(len(edges) - 1):
+        assert (cov.segment[edges[s]:edges[s + 1]] == s).all()
+    for idx in range(total):
+        assert tuple(int(v) for v in cov.bidx[idx]) == G.delinearize(idx, grid)
+    if chunk == 1:
+        assert log[:-1] == [p for p in pts if p < total] or log[:-1] == pts[:len(log) - 1]
+
+
+@settings(max_examples=60, deadline=None)
+@given(total=st.integers(1, 300), slice_blocks=st.integers(1, 64),
+       stops=st.lists(st.integers(1, 40), max_size=3, unique=True))
+def test_sliced_invariants_hold_for_any_run(total, slice_blocks, stops):
+    """Slices cover [0, total) in order, each block once, the last slice is the remainder, and
+    a stop after n slices starts a new segment at offset n * slice_blocks."""
+    cov, resumes = S.run_sliced(None, (total, 1, 1), {}, slice_blocks, preempt_after_slices=sorted(stops))
+    assert cov.exactly_once()
+    nslices = -(-total // slice_blocks)
+    seg, want_resumes = 0, []
+    for sl in range(nslices):
+        lo, hi = sl * slice_blocks, min((sl + 1) * slice_blocks, total)
+        assert (cov.segment[lo:hi] == seg).all()
+        if (sl + 1) in stops and sl + 1 < nslices:
+            seg += 1
+            want_resumes.append(hi)
+    assert resumes == want_resumes
