@@ -1716,6 +1716,9 @@ void be_thread_main(tally_sched *s) {
       }
     }
     if (stopping && busy == 0) break;
+    // kernels in flight: the loop watches their status words; tell the core it is a spin
+    // wait (a sibling hardware thread, the high-priority client's perhaps, gets the issue slots)
+    if (busy != 0) __builtin_ia32_pause();
     if (busy == 0) {
       // nothing in flight and nothing queued: sleep until a kernel is submitted
       std::unique_lock<std::mutex> lk(s->mu);
