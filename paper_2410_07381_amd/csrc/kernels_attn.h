@@ -30,7 +30,7 @@ __device__ __forceinline__ void unpack8(uint4 u, float (&f)[8]) {
   f[4] = bf16_lo(u.z); f[5] = bf16_hi(u.z); f[6] = bf16_lo(u.w); f[7] = bf16_hi(u.w);
 }
 
-__global__ __launch_bounds__(256) void attn_decode_partial(tally_attn_decode_args a, uint32_t chunk,
+__global__ __launch_bounds__(256, 4) void attn_decode_partial(tally_attn_decode_args a, uint32_t chunk,
                                                            uint32_t urgent) {
   if (urgent) __builtin_amdgcn_s_setprio(3);
   __shared__ float s_score[kAttnMaxChunk];
@@ -48,21 +48,38 @@ __global__ __launch_bounds__(256) void attn_decode_partial(tally_attn_decode_arg
   const uint4 qq = *reinterpret_cast<const uint4 *>(a.q + (uint64_t)h * kAttnDim + sub * 8);
   const float scale = 0.08838834764831845f;                // 1 / sqrt(128)
 
+  // Both passes take their tokens eight at a time per 16-lane group and issue the eight
+  // 16-byte loads before they use the first: with one load in flight per pass of the loop a
+  // workgroup was a chain of sixteen memory latencies for its 128 tokens (the whole kernel
+  // 11 us for 33.6 MB, twice that from a cold cache), and beside the paused tiles of a
+  // best-effort GEMM there are few other waves on the compute unit to hide them.
+  constexpr int U = 8;
+  const uint4 zero4 = make_uint4(0, 0, 0, 0);
+
   // pass 1: scores of this workgroup's tokens
   float mloc = -INFINITY;
-  for (uint32_t t = wave * 4 + grp; t < chunk; t += 16) {  // uniform trip count per wave
-    float s = 0.f;
-    if (t < cnt) {
-      const uint4 kk = *reinterpret_cast<const uint4 *>(Kh + (uint64_t)(t0 + t) * row);
-      s = GemvBody::dot8(kk, qq, 0.f);
+  for (uint32_t tb = wave * 4 + grp; tb < chunk; tb += 16 * U) {  // uniform trip count per wave
+    uint4 kk[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const uint32_t t = tb + 16 * u;
+      kk[u] = zero4;
+      if (t < cnt) kk[u] = *reinterpret_cast<const uint4 *>(Kh + (uint64_t)(t0 + t) * row);
     }
-    s += __shfl_xor(s, 8, kWave);
-    s += __shfl_xor(s, 4, kWave);
-    s += __shfl_xor(s, 2, kWave);
-    s += __shfl_xor(s, 1, kWave);
-    s = (t < cnt) ? s * scale : -INFINITY;
-    if (sub == 0) s_score[t] = s;
-    mloc = fmaxf(mloc, s);
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const uint32_t t = tb + 16 * u;
+      if (t < chunk) {                                     // chunk is a multiple of 16: wave-uniform
+        float s = GemvBody::dot8(kk[u], qq, 0.f);
+        s += __shfl_xor(s, 8, kWave);
+        s += __shfl_xor(s, 4, kWave);
+        s += __shfl_xor(s, 2, kWave);
+        s += __shfl_xor(s, 1, kWave);
+        s = (t < cnt) ? s * scale : -INFINITY;
+        if (sub == 0) s_score[t] = s;
+        mloc = fmaxf(mloc, s);
+      }
+    }
   }
   mloc = wave_max(mloc);
   if (lane == 0) s_red[wave] = mloc;
@@ -72,13 +89,28 @@ __global__ __launch_bounds__(256) void attn_decode_partial(tally_attn_decode_arg
   // pass 2: weights and weighted sum of V
   float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   float l = 0.f;
-  for (uint32_t t = wave * 4 + grp; t < chunk; t += 16) {
-    if (t < cnt) {
-      float p = __expf(s_score[t] - m);
-      float v[8];
-      unpack8(*reinterpret_cast<const uint4 *>(Vh + (uint64_t)(t0 + t) * row), v);
+  for (uint32_t tb = wave * 4 + grp; tb < chunk; tb += 16 * U) {
+    uint4 vv[U];
 #pragma unroll
-      for (int e = 0; e < 8; ++e) acc[e] = __builtin_fmaf(p, v[e], acc[e]);
+    for (int u = 0; u < U; ++u) {
+      const uint32_t t = tb + 16 * u;
+      vv[u] = zero4;
+      if (t < cnt) vv[u] = *reinterpret_cast<const uint4 *>(Vh + (uint64_t)(t0 + t) * row);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const uint32_t t = tb + 16 * u;
+      // a token beyond the range has weight 0 and a zero row: it adds nothing
+      const float p = (t < cnt) ? __expf(s_score[t < cnt ? t : 0u] - m) : 0.f;
+      const uint4 r = vv[u];
+      acc[0] = __builtin_fmaf(p, bf16_lo(r.x), acc[0]);
+      acc[1] = __builtin_fmaf(p, bf16_hi(r.x), acc[1]);
+      acc[2] = __builtin_fmaf(p, bf16_lo(r.y), acc[2]);
+      acc[3] = __builtin_fmaf(p, bf16_hi(r.y), acc[3]);
+      acc[4] = __builtin_fmaf(p, bf16_lo(r.z), acc[4]);
+      acc[5] = __builtin_fmaf(p, bf16_hi(r.z), acc[5]);
+      acc[6] = __builtin_fmaf(p, bf16_lo(r.w), acc[6]);
+      acc[7] = __builtin_fmaf(p, bf16_hi(r.w), acc[7]);
       l += p;
     }
   }

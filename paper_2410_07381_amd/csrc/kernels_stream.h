@@ -219,8 +219,11 @@ struct GemvBody {
                                         __builtin_bit_cast(bf16x2_t, x.w), s, false);
     return s;
   }
-  static __device__ __forceinline__ void run_be(const Args &a, uint32_t x, uint32_t y, uint32_t z) { run(a, x, y, z); }
-  static __device__ __forceinline__ void run(const Args &a, uint32_t bx, uint32_t, uint32_t) {
+  // (the best-effort forms keep four loads in flight: their loop has no registers to spare)
+  static __device__ __forceinline__ void run_be(const Args &a, uint32_t x, uint32_t y, uint32_t z) { run_t<false>(a, x, y, z); }
+  static __device__ __forceinline__ void run(const Args &a, uint32_t x, uint32_t y, uint32_t z) { run_t<true>(a, x, y, z); }
+  template <bool DEEP>
+  static __device__ __forceinline__ void run_t(const Args &a, uint32_t bx, uint32_t, uint32_t) {
     const uint32_t lane = threadIdx.x & (kWave - 1);
     const uint32_t row = bx * 4 + threadIdx.x / kWave;
     if (row >= a.n) return;  // wave-uniform; the body holds no barrier
@@ -229,6 +232,27 @@ struct GemvBody {
     const uint4 *x = reinterpret_cast<const uint4 *>(a.x);
     float acc0 = 0.f, acc1 = 0.f, acc2 = 0.f, acc3 = 0.f;
     uint32_t v = lane;
+    // Eight 16-byte loads of the row in flight per lane (8 KB per wave; a 4096-wide row is
+    // one such batch).  Beside the paused tiles of a best-effort GEMM only two of these
+    // waves fit on a SIMD, and with four loads each the eight waves of a compute unit had
+    // 32 KB on their way where the HBM's latency times the unit's share of its bandwidth
+    // asks for ~45 KB: the decode-like request ran at 4.3 TB/s co-located against 5.6 alone.
+    // The operand x comes from the caches; its loads are taken four at a time to stay
+    // within the 64 registers that let two waves fit.
+    for (; DEEP && v + 7 * kWave < nvec; v += 8 * kWave) {
+      const uint4 w0 = w[v], w1 = w[v + kWave], w2 = w[v + 2 * kWave], w3 = w[v + 3 * kWave];
+      const uint4 w4 = w[v + 4 * kWave], w5 = w[v + 5 * kWave], w6 = w[v + 6 * kWave], w7 = w[v + 7 * kWave];
+      uint4 x0 = x[v], x1 = x[v + kWave], x2 = x[v + 2 * kWave], x3 = x[v + 3 * kWave];
+      acc0 = dot8(w0, x0, acc0);
+      acc1 = dot8(w1, x1, acc1);
+      acc2 = dot8(w2, x2, acc2);
+      acc3 = dot8(w3, x3, acc3);
+      x0 = x[v + 4 * kWave]; x1 = x[v + 5 * kWave]; x2 = x[v + 6 * kWave]; x3 = x[v + 7 * kWave];
+      acc0 = dot8(w4, x0, acc0);
+      acc1 = dot8(w5, x1, acc1);
+      acc2 = dot8(w6, x2, acc2);
+      acc3 = dot8(w7, x3, acc3);
+    }
     for (; v + 3 * kWave < nvec; v += 4 * kWave) {
       uint4 w0 = w[v], w1 = w[v + kWave], w2 = w[v + 2 * kWave], w3 = w[v + 3 * kWave];
       acc0 = dot8(w0, x[v], acc0);
