@@ -326,19 +326,28 @@ def _profile_step(torch, B, ctx, be_stream, step, threshold_ms, runs=3):
     scheduler's lookup of these measurements)."""
     table, items = {}, []
     for name, k, flops, nbytes in step:
-        nat = _time(torch, B, be_stream, lambda: (ctx.launch_native(k), None)[1], reps=3, warm=1)
         cands = ctx.candidate_configs(k)
         meas, chosen = ctx.profile(k, cands, runs=runs, threshold_ms=threshold_ms)
         c = meas[chosen]
         # the profiler's figure is the host's (launch call to completion observed, what the
         # scheduler can see); the comparison with the original form uses the same clock for
-        # both: HIP events on the best-effort stream around one launch
+        # both, HIP events on the best-effort stream around one launch, and takes the two
+        # forms in turn (the shader clock follows the load of the last milliseconds: a form
+        # timed right after the profiler's thirty runs would be timed at a lower clock than
+        # one timed after a pause)
         if c["kind"] == B.CFG_PTB:
-            ev = _time(torch, B, be_stream, lambda: ctx.launch_ptb(k, c["param"], chunk=c["chunk"]),
-                       reps=3, warm=1)
+            launch_chosen, wait = (lambda: ctx.launch_ptb(k, c["param"], chunk=c["chunk"])), False
         else:
-            ev = _time(torch, B, be_stream, lambda: ctx.launch_sliced(k, c["param"], max_in_flight=c["chunk"]),
-                       reps=3, warm=1, wait_before_stop=True)
+            launch_chosen, wait = (lambda: ctx.launch_sliced(k, c["param"], max_in_flight=c["chunk"])), True
+        nat_us, ev_us = [], []
+        for rep in range(6):
+            n1 = _time(torch, B, be_stream, lambda: (ctx.launch_native(k), None)[1], reps=1, warm=0)
+            e1 = _time(torch, B, be_stream, launch_chosen, reps=1, warm=0, wait_before_stop=wait)
+            if rep:                                       # the first pair warms up
+                nat_us.append(n1[0])
+                ev_us.append(e1[0])
+        nat = (float(np.median(nat_us)), float(np.min(nat_us)))
+        ev = (float(np.median(ev_us)), float(np.min(ev_us)))
         row = {"blocks": k.total_blocks, "native_us": nat[0], "candidates": len(cands),
                "chosen": {"form": "ptb" if c["kind"] == B.CFG_PTB else "sliced", "param": c["param"],
                           "chunk": c["chunk"]},
