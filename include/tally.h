@@ -347,6 +347,7 @@ int tally_lookup_config(tally_ctx *ctx, const tally_kernel_desc *desc, tally_con
 /* get_candidate_configs() of Figure 4 (Section 4.2): persistent-worker counts that are
  * multiples of the compute-unit count up to tally_max_workers(), each with 1, 4 and 16 task
  * indices per fetch where every worker then still has a fetch to make, and slices of
+ * 1/1 (the whole grid in one launch: what a kernel shorter than the threshold needs),
  * 1/2, 1/4, ... 1/256 of the grid.  Writes at most cap entries (latency and turnaround zero)
  * and their number. */
 int tally_candidate_configs(tally_ctx *ctx, const tally_kernel_desc *desc, tally_config *out,

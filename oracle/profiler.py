@@ -47,8 +47,11 @@ def ptb_candidates(total_blocks, num_cus, max_blocks_per_cu):
     return out
 
 
-def slice_candidates(total_blocks, fractions=(1 / 2, 1 / 4, 1 / 8, 1 / 16, 1 / 32, 1 / 64,
+def slice_candidates(total_blocks, fractions=(1, 1 / 2, 1 / 4, 1 / 8, 1 / 16, 1 / 32, 1 / 64,
                                              1 / 128, 1 / 256)):
+    """Blocks per slice for slices of the given shares of the grid (Section 4.2 names no
+    shares; the whole grid is one of them: one launch, which is all a kernel shorter than
+    the threshold needs)."""
     out = []
     for f in fractions:
         n = max(1, int(total_blocks * f))

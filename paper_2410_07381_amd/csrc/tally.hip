@@ -1272,7 +1272,8 @@ uint32_t candidate_configs(tally_ctx *ctx, uint32_t kernel_id, uint64_t total, t
       if (ch == 1 || (uint64_t)workers * ch <= total) push(0, workers, ch);
     if ((uint64_t)w >= total) break;
   }
-  for (uint32_t sh = 1; sh <= 8; ++sh) {
+  // the whole grid as one slice first: a kernel shorter than the threshold complies as it is
+  for (uint32_t sh = 0; sh <= 8; ++sh) {
     const uint64_t blocks = total >> sh;
     push(1, (uint32_t)(blocks ? blocks : 1), 1);
   }

@@ -120,7 +120,7 @@ def test_candidate_set_follows_section_4_2(env):
     ptb1 = [p for kind, p, c in cands if kind == B.CFG_PTB and c == 1]
     assert ptb1 == OP.ptb_candidates(k.total_blocks, cus, occ)        # k x CUs, k = 1 .. occupancy
     sliced = [p for kind, p, c in cands if kind == B.CFG_SLICED]
-    assert sliced == OP.slice_candidates(k.total_blocks)              # 1/2 ... 1/256 of the grid
+    assert sliced == OP.slice_candidates(k.total_blocks)              # 1/1, 1/2 ... 1/256 of the grid
     for kind, p, c in cands:
         if kind == B.CFG_PTB:
             assert c in (1, 4, 16) and (c == 1 or p * c <= k.total_blocks)

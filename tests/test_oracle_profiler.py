@@ -70,8 +70,8 @@ def test_candidates():
     assert P.ptb_candidates(65536, 256, 4) == [256, 512, 768, 1024]
     assert P.ptb_candidates(256, 256, 8) == [256]            # capped at the grid size
     assert P.ptb_candidates(600, 256, 3) == [256, 512, 600]
-    assert P.slice_candidates(65536)[:3] == [32768, 16384, 8192]
-    assert P.slice_candidates(4) == [2, 1]
+    assert P.slice_candidates(65536)[:4] == [65536, 32768, 16384, 8192]
+    assert P.slice_candidates(4) == [4, 2, 1]
 
 
 def _m(kind, param, lat, turn):
