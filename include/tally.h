@@ -135,7 +135,13 @@ typedef struct tally_job tally_job; /* one best-effort kernel instance and its p
 /* ---- context ---------------------------------------------------------------------- */
 
 /* Create a context on the current device for one high-priority and one best-effort
- * stream (Section 4: one high-priority task next to best-effort tasks). */
+ * stream (Section 4: one high-priority task next to best-effort tasks).  The two
+ * hipStream_t stay the caller's (never destroyed here; default priority expected).  The
+ * call allocates the context's device and pinned host words, creates the stream the relay
+ * kernels use, and times a few microsecond-long kernels on the streams to choose it
+ * (see tally_stream_report): it synchronises both streams and takes some milliseconds, so
+ * call it while they are idle.  TALLY_ERR_NOMEM / TALLY_ERR_HIP (tally_last_hip_error())
+ * on failure, with nothing left allocated. */
 int tally_create(tally_ctx **out, void *hip_stream_hi, void *hip_stream_be);
 int tally_destroy(tally_ctx *ctx); /* all jobs must have been freed */
 
