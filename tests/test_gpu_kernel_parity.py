@@ -245,7 +245,12 @@ def test_gemm_small_forms(env, form):
 # ------------------------------------------------------------------ GEMV
 @pytest.mark.parametrize("n,k,form", [(130, 96, "native"), (130, 96, "ptb_preempted"),
                                       (4096, 4096, "native_hi"), (4096, 11008, "native_hi"),
-                                      (11008, 4096, "native_hi"), (1000, 2056, "sliced")])
+                                      (11008, 4096, "native_hi"), (1000, 2056, "sliced"),
+                                      # the original form takes a row in batches of eight, then four
+                                      # loads per lane, then singles: rows shorter than a batch, fewer
+                                      # rows than a workgroup has waves, ragged ends of every loop
+                                      (5, 8, "native"), (3, 520, "native_hi"), (1031, 4104, "native"),
+                                      (300, 11264, "native_hi"), (37, 11272, "native")])
 def test_gemv(env, n, k, form):
     B, ctx, torch = env
     from gpu_util import dev, host, assert_bf16_close
