@@ -131,6 +131,40 @@ def test_candidate_set_follows_section_4_2(env):
     assert len(set(cs)) == len(cs)
 
 
+def test_a_kernel_shorter_than_the_threshold_runs_as_one_slice(env):
+    """Section 4.2's rule on the library's own candidate set: for a kernel that is over before the
+    threshold, the whole grid in one launch complies; the library's choice is the oracle's
+    selection on the same measurements, and the run is right."""
+    B, ctx, torch = env
+    from gpu_util import host
+    ctx.profile_reset()
+    x = torch.ones(1 << 20, device="cuda")
+    y = torch.zeros(1 << 20, device="cuda")
+    torch.cuda.synchronize()
+    k = B.saxpy(x, y, 1.0)                               # 4096 blocks, a few microseconds
+    cands = ctx.candidate_configs(k)
+    assert (B.CFG_SLICED, k.total_blocks, 1) in cands
+    meas, chosen = ctx.profile(k, cands, runs=5, threshold_ms=0.0316)
+    runs_so_far = len(cands) * 6                         # one warm-up and five samples each
+    assert (host(y) == float(runs_so_far)).all()         # every measurement ran the kernel once
+    table = [{"kind": "ptb" if m["kind"] == B.CFG_PTB else "sliced", "param": m["param"],
+              "latency_ms": m["latency_ms"], "turnaround_ms": m["turnaround_ms"]} for m in meas]
+    want = OP.select_config(table, 0.0316)
+    got = meas[chosen]
+    assert (want["kind"], want["param"]) == ("ptb" if got["kind"] == B.CFG_PTB else "sliced", got["param"])
+    whole = [m for m in meas if m["kind"] == B.CFG_SLICED and m["param"] == k.total_blocks][0]
+    assert whole["turnaround_ms"] == pytest.approx(whole["latency_ms"], rel=1e-4)   # one slice: itself
+    assert whole["turnaround_ms"] <= 0.0316
+    # the one-piece run complies, so whatever was chosen is at least as fast (on this part it
+    # is the one-piece run itself: every other candidate adds launches or a worker loop)
+    assert got["latency_ms"] <= whole["latency_ms"]
+    job = ctx.launch_sliced(k, got["param"], max_in_flight=got["chunk"])
+    assert job.wait() == B.JOB_COMPLETE
+    job.free()
+    torch.cuda.synchronize()
+    assert (host(y) == float(runs_so_far + 1)).all()
+
+
 def test_kernels_submitted_while_the_loop_runs(env):
     """Best-effort kernels the scheduler has never seen are handed over while it is already
     serving others and high-priority requests; each runs exactly once with the right result."""
