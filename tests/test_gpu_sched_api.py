@@ -131,7 +131,7 @@ def test_candidate_set_follows_section_4_2(env):
     assert len(set(cs)) == len(cs)
 
 
-def test_a_kernel_shorter_than_the_threshold_runs_as_one_slice(env):
+def test_a_kernel_shorter_than_the_threshold_complies_as_one_slice(env):
     """Section 4.2's rule on the library's own candidate set: for a kernel that is over before the
     threshold, the whole grid in one launch complies; the library's choice is the oracle's
     selection on the same measurements, and the run is right."""
@@ -158,7 +158,10 @@ def test_a_kernel_shorter_than_the_threshold_runs_as_one_slice(env):
     # the one-piece run complies, so whatever was chosen is at least as fast (on this part it
     # is the one-piece run itself: every other candidate adds launches or a worker loop)
     assert got["latency_ms"] <= whole["latency_ms"]
-    job = ctx.launch_sliced(k, got["param"], max_in_flight=got["chunk"])
+    if got["kind"] == B.CFG_SLICED:
+        job = ctx.launch_sliced(k, got["param"], max_in_flight=got["chunk"])
+    else:
+        job = ctx.launch_ptb(k, got["param"], chunk=got["chunk"])
     assert job.wait() == B.JOB_COMPLETE
     job.free()
     torch.cuda.synchronize()
